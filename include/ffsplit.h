@@ -1,0 +1,168 @@
+/*
+ * libffsplit: the split feed-forward layer of FFSplit (arXiv 2401.04044) on
+ * one AMD MI355X (gfx950).
+ *
+ * The feed-forward layer FFN(X) = sigma(X U) V is a sum of d_ff rank-one terms,
+ * one per neuron (Sec. 2, Eq. 1).  Neurons are scored on a calibration token
+ * set (Sec. 4.1, Eq. 3), the k highest-scoring ones form the heavy set h2, and
+ * the layer is evaluated as FFN_1 (heavy neurons, weights untouched) plus FFN_2
+ * (the remaining neurons, compressed) (Sec. 2, Eq. 2; Sec. 4.2).
+ *
+ * Names: W1 = up projection (the paper's U, [d_model, d_ff]); Wg = SwiGLU gate
+ * ([d_model, d_ff]); W2 = down projection (the paper's V, [d_ff, d_model]).
+ * A neuron is one column of W1 (and Wg) together with the matching row of W2.
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - Matrices are row-major and contiguous; device pointers are 16-byte aligned.
+ *   - Element type of X, Y and all dense weights/factors is desc->dtype.
+ *   - The library allocates nothing, keeps no state between calls and never
+ *     synchronises: a call validates its arguments on the host, enqueues
+ *     kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and returns.  Outputs are valid once the caller has synchronised the stream.
+ *   - Caller owns every buffer.  `workspace` is scratch of at least
+ *     ffsplit_workspace_bytes(...) bytes, 256-byte aligned, contents undefined
+ *     on entry and on exit; it may be reused by later calls on the same stream.
+ *   - Return value: FFSPLIT_OK or a negative FFSPLIT_E_* code.  Argument errors
+ *     are found before anything is launched.
+ *   - T = 0, k = 0 and k = d_ff are valid (the empty part contributes zero).
+ *   - Results are deterministic: the same call on the same inputs gives the
+ *     same bits (no floating-point atomics anywhere).
+ */
+#ifndef FFSPLIT_H
+#define FFSPLIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { FFSPLIT_ACT_GELU = 0,      /* exact GeLU z*Phi(z) (erf form)                      */
+       FFSPLIT_ACT_SWIGLU = 1 };  /* silu(X Wg) * (X W1)                                  */
+enum { FFSPLIT_F32 = 0, FFSPLIT_BF16 = 1 };
+enum { FFSPLIT_REM_NONE = 0,      /* FFN_2 dropped                                        */
+       FFSPLIT_REM_DENSE = 1,     /* FFN_2 kept uncompressed                              */
+       FFSPLIT_REM_LOWRANK = 2,   /* each remainder matrix given as two rank-r factors    */
+       FFSPLIT_REM_INT4 = 3 };    /* remainder weights as group-wise symmetric int4       */
+enum { FFSPLIT_SCORE_SUMSQ = 0,   /* Eq. 3: ||sigma(X U[:,j])||_F^2 * ||V[j,:]||_F^2      */
+       FFSPLIT_SCORE_MEAN_L2 = 1, /* mean_t ||sigma(x_t U[:,j]) V[j,:]||_2                */
+       FFSPLIT_SCORE_ACT_ONLY = 2 /* ||sigma(X U[:,j])||_F^2 (Sec. 2's heavy-hitter norm) */ };
+enum { FFSPLIT_WS_SCORE = 0, FFSPLIT_WS_SELECT = 1, FFSPLIT_WS_BUILD = 2, FFSPLIT_WS_FORWARD = 3 };
+
+enum { FFSPLIT_OK = 0,
+       FFSPLIT_E_NULLPTR = -1,     /* a required pointer is NULL                          */
+       FFSPLIT_E_BADDESC = -2,     /* unknown act / dtype / rem_kind, non-positive sizes  */
+       FFSPLIT_E_BADSHAPE = -3,    /* k > d_ff, rank > min(d_model, m), group does not    */
+                                   /* divide d_model, d_model % 8 != 0, T < 0             */
+       FFSPLIT_E_ALIGN = -4,       /* a pointer is not 16-byte aligned                    */
+       FFSPLIT_E_WORKSPACE = -5,   /* workspace missing or too small                      */
+       FFSPLIT_E_UNSUPPORTED = -6, /* valid but not implemented combination               */
+       FFSPLIT_E_NONFINITE = -7,   /* reported through select_heavy's device flag only    */
+       FFSPLIT_E_HIP = -8          /* a HIP runtime call failed                           */ };
+
+/* Plain data, passed by pointer, never retained. */
+typedef struct {
+  int32_t d_model;   /* d; multiple of 8                                                  */
+  int32_t d_ff;      /* number of neurons                                                 */
+  int32_t act;       /* FFSPLIT_ACT_*                                                     */
+  int32_t dtype;     /* FFSPLIT_F32 / FFSPLIT_BF16                                        */
+  int32_t k;         /* |h2|, 0..d_ff                                                     */
+  int32_t rem_kind;  /* FFSPLIT_REM_*                                                     */
+  int32_t rank;      /* LOWRANK: r, the same for every factored matrix                    */
+  int32_t group;     /* INT4: group length along d_model (must divide it; multiple of 32) */
+} ffsplit_desc_t;
+
+/* Static description of a status code. */
+const char* ffsplit_status_string(int status);
+
+/* Bytes of scratch the given call needs for T tokens (pure host arithmetic). */
+size_t ffsplit_workspace_bytes(const ffsplit_desc_t* desc, int32_t call_id, int64_t T);
+
+/* Bytes of the packed split produced by ffsplit_build_split (pure host arithmetic). */
+size_t ffsplit_split_bytes(const ffsplit_desc_t* desc);
+
+/*
+ * Calibration, one token batch (Sec. 4.2 first step; Sec. 4.1, Eq. 3).
+ * For every neuron j adds this batch to the running sums
+ *     acc[j]        += sum_t H[t,j]^2        acc[d_ff + j] += sum_t |H[t,j]|
+ * with H = gelu(X W1) or silu(X Wg) * (X W1), computed on the unmodified dense
+ * weights, and adds T to *T_total.  If `scores` is not NULL it then writes
+ *     SUMSQ    scores[j] = acc[j] * sum_c W2[j,c]^2
+ *     MEAN_L2  scores[j] = acc[d_ff+j] / T_total * sqrt(sum_c W2[j,c]^2)
+ *     ACT_ONLY scores[j] = acc[j]
+ * X [T, d_model]; W1, Wg [d_model, d_ff]; W2 [d_ff, d_model] (Wg NULL unless
+ * SWIGLU; W2 may be NULL when scores is NULL).  acc: [2*d_ff] fp32, owned and
+ * zeroed by the caller before the first batch (calibration can be resumed by
+ * keeping acc and *T_total).  T_total: host pointer, in/out.  scores: [d_ff] fp32.
+ * desc->k, rem_kind, rank, group are ignored.
+ */
+int ffsplit_score_neurons(const ffsplit_desc_t* desc, const void* X, int64_t T,
+                          const void* W1, const void* Wg, const void* W2,
+                          float* acc, int64_t* T_total, float* scores, int32_t score_kind,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Heavy-hitter selection (Sec. 4.1 / 5.1.1: the neurons with the highest score).
+ * Writes to idx[0..k) the indices of the k largest scores ordered by score
+ * descending, equal scores by ascending index; -0 counts as +0, +Inf as the
+ * largest value.  If perm is not NULL it receives the neuron permutation
+ * [idx ; every other index ascending] of length d_ff (Eq. 2's partition).
+ * If a score is NaN, *nan_flag (if not NULL) is set to FFSPLIT_E_NONFINITE,
+ * else to 0; idx is then still a valid set of distinct indices (NaN ranks as
+ * the largest value).  scores: [d_ff] fp32, all >= 0 or NaN.  Bit-exact.
+ */
+int ffsplit_select_heavy(const float* scores, int32_t d_ff, int32_t k,
+                         int32_t* idx, int32_t* perm, int32_t* nan_flag,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Split construction (Eq. 2; Fig. 3: U1 = U[:,h2], V1 = V[h2,:], U2, V2 the
+ * rest; Sec. 4.2: only U2, V2 are compressed).  Gathers the heavy neurons'
+ * columns/rows into dense blocks and packs the remainder into `split`
+ * (ffsplit_split_bytes(desc) bytes, 256-byte aligned; private layout,
+ * position independent so it may be copied).
+ *   idx      [k] distinct neuron indices (int32), any order.
+ *   DENSE    remainder columns/rows gathered in ascending index order.
+ *   LOWRANK  factors (HOST array of 6 device pointers P1, Q1, Pg, Qg, P2, Q2)
+ *            with W1[:,rest] ~= P1 Q1, Wg[:,rest] ~= Pg Qg, W2[rest,:] ~= P2 Q2,
+ *            rest = the non-heavy neurons ascending; P1, Pg [d_model, r];
+ *            Q1, Qg [r, m]; P2 [m, r]; Q2 [r, d_model]; Pg, Qg NULL unless
+ *            SWIGLU.  W1, Wg, W2 are read for the heavy part only.
+ *   INT4     each remainder neuron's W1 column, Wg column and W2 row (all of
+ *            length d_model) is quantised round-to-nearest in groups of
+ *            desc->group (Sec. 5.2), in fp32:  a = max|w|, s = fp16(a / 7),
+ *            q = s == 0 ? 0 : clamp(rint(w / float(s)), -8, 7) (ties to even),
+ *            dequantised value float(s) * q.  Requires dtype BF16.
+ */
+int ffsplit_build_split(const ffsplit_desc_t* desc, const void* W1, const void* Wg,
+                        const void* W2, const int32_t* idx, const void* const* factors,
+                        void* split, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Split forward pass (Eq. 2):  Y = FFN_1(X) + FFN_2~(X), with
+ * FFN_1 = act(X W1[:,h2] [, X Wg[:,h2]]) W2[h2,:] and FFN_2~ the remainder in
+ * its compressed form (LOWRANK: act((X P1) Q1 [, (X Pg) Qg]) P2 Q2).
+ * X [T, d_model]; Y [T, d_model].  Y_heavy / Y_rem: NULL, or [T, d_model]
+ * buffers that receive FFN_1(X) and FFN_2~(X) separately (diagnostic; costs
+ * extra launches).  Accumulation is fp32; intermediates between the chained
+ * products are stored in desc->dtype.
+ */
+int ffsplit_forward(const ffsplit_desc_t* desc, const void* split, const void* X, int64_t T,
+                    void* Y, void* Y_heavy, void* Y_rem,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Test hook: unpack the INT4 remainder of a built split into logical order.
+ * what = 0 (W1 columns), 1 (Wg columns), 2 (W2 rows).  q_out: [m, d_model] int8
+ * codes; s_out: [m, d_model/group] fp16 scale bits (uint16); neuron order =
+ * remainder ascending.
+ */
+int ffsplit_split_export(const ffsplit_desc_t* desc, const void* split, int32_t what,
+                         int8_t* q_out, uint16_t* s_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFSPLIT_H */

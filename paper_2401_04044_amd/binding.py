@@ -1,0 +1,170 @@
+"""ctypes binding: same names as the C ABI, argument marshalling only."""
+import ctypes
+import os
+
+import torch
+
+ACT_GELU, ACT_SWIGLU = 0, 1
+F32, BF16 = 0, 1
+REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4 = 0, 1, 2, 3
+SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY = 0, 1, 2
+WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD = 0, 1, 2, 3
+E_NONFINITE = -7
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libffsplit.so")
+
+
+class FFSplitError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("act", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("k", ctypes.c_int32), ("rem_kind", ctypes.c_int32),
+                ("rank", ctypes.c_int32), ("group", ctypes.c_int32)]
+
+
+def _load():
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    L = ctypes.CDLL(path)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    dp = ctypes.POINTER(Desc)
+    L.ffsplit_status_string.restype = ctypes.c_char_p
+    L.ffsplit_status_string.argtypes = [ctypes.c_int]
+    L.ffsplit_workspace_bytes.restype = sz
+    L.ffsplit_workspace_bytes.argtypes = [dp, i32, i64]
+    L.ffsplit_split_bytes.restype = sz
+    L.ffsplit_split_bytes.argtypes = [dp]
+    L.ffsplit_score_neurons.restype = ctypes.c_int
+    L.ffsplit_score_neurons.argtypes = [dp, vp, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp, i32, vp, sz, vp]
+    L.ffsplit_select_heavy.restype = ctypes.c_int
+    L.ffsplit_select_heavy.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.ffsplit_build_split.restype = ctypes.c_int
+    L.ffsplit_build_split.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
+    L.ffsplit_forward.restype = ctypes.c_int
+    L.ffsplit_forward.argtypes = [dp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.ffsplit_split_export.restype = ctypes.c_int
+    L.ffsplit_split_export.argtypes = [dp, vp, i32, vp, vp, vp]
+    return L
+
+
+lib = _load()
+
+
+def status_string(code: int) -> str:
+    return lib.ffsplit_status_string(int(code)).decode()
+
+
+def make_desc(d_model, d_ff, act="gelu", dtype="bf16", k=0, rem_kind="none", rank=0, group=0) -> Desc:
+    acts = {"gelu": ACT_GELU, "swiglu": ACT_SWIGLU}
+    dts = {"f32": F32, "bf16": BF16}
+    rems = {"none": REM_NONE, "dense": REM_DENSE, "lowrank": REM_LOWRANK, "int4": REM_INT4}
+    return Desc(d_model, d_ff, acts.get(act, act), dts.get(dtype, dtype), k, rems.get(rem_kind, rem_kind),
+                rank, group)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(code, where):
+    if code != 0:
+        raise FFSplitError(code, where)
+
+
+def workspace_bytes(desc: Desc, call_id: int, T: int = 0) -> int:
+    return int(lib.ffsplit_workspace_bytes(ctypes.byref(desc), call_id, T))
+
+
+def split_bytes(desc: Desc) -> int:
+    return int(lib.ffsplit_split_bytes(ctypes.byref(desc)))
+
+
+def _ws(nbytes, workspace, device):
+    if workspace is not None:
+        return workspace
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def score_neurons(desc, X, W1, Wg, W2, acc, T_total, scores=None, score_kind=SCORE_SUMSQ, workspace=None):
+    """One calibration batch.  Returns the updated token count."""
+    T = 0 if X is None else X.shape[0]
+    ws = _ws(workspace_bytes(desc, WS_SCORE, T), workspace, acc.device)
+    tt = ctypes.c_int64(int(T_total))
+    rc = lib.ffsplit_score_neurons(ctypes.byref(desc), _ptr(X), T, _ptr(W1), _ptr(Wg), _ptr(W2), _ptr(acc),
+                                   ctypes.byref(tt), _ptr(scores), score_kind, _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_score_neurons")
+    return tt.value
+
+
+def select_heavy(scores, k, want_perm=False, workspace=None):
+    """Returns (idx [k] int32, perm [d_ff] int32 or None, nan_flag [1] int32), all on the device."""
+    d_ff = scores.numel()
+    dev = scores.device
+    idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)[:k]
+    perm = torch.empty(d_ff, dtype=torch.int32, device=dev) if want_perm else None
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws = _ws(12 * d_ff + 256, workspace, dev)
+    rc = lib.ffsplit_select_heavy(_ptr(scores), d_ff, k, _ptr(idx) if k > 0 else None, _ptr(perm), _ptr(flag),
+                                  _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_select_heavy")
+    return idx, perm, flag
+
+
+def build_split(desc, W1, Wg, W2, idx, factors=None, split=None, workspace=None):
+    """factors: dict with P1, Q1, Pg, Qg, P2, Q2 (device tensors or None).  Returns the packed split."""
+    dev = W1.device
+    nbytes = split_bytes(desc)
+    if nbytes == 0:
+        _check(-2, "ffsplit_split_bytes")
+    if split is None:
+        split = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    ws = _ws(workspace_bytes(desc, WS_BUILD, 0), workspace, dev)
+    fac = None
+    if factors is not None:
+        arr = (ctypes.c_void_p * 6)()
+        for i, nm in enumerate(("P1", "Q1", "Pg", "Qg", "P2", "Q2")):
+            t = factors.get(nm)
+            arr[i] = None if t is None else t.data_ptr()
+        fac = arr
+    rc = lib.ffsplit_build_split(ctypes.byref(desc), _ptr(W1), _ptr(Wg), _ptr(W2),
+                                 _ptr(idx) if idx is not None and idx.numel() > 0 else None, fac, _ptr(split),
+                                 _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_build_split")
+    return split
+
+
+def forward(desc, split, X, Y=None, want_parts=False, workspace=None):
+    """Returns Y, or (Y, Y_heavy, Y_rem) with want_parts."""
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, desc.d_model), dtype=X.dtype, device=X.device)
+    Yh = torch.empty_like(Y) if want_parts else None
+    Yr = torch.empty_like(Y) if want_parts else None
+    ws = _ws(workspace_bytes(desc, WS_FORWARD, T), workspace, X.device)
+    rc = lib.ffsplit_forward(ctypes.byref(desc), _ptr(split), _ptr(X), T, _ptr(Y), _ptr(Yh), _ptr(Yr), _ptr(ws),
+                             ws.numel(), _stream())
+    _check(rc, "ffsplit_forward")
+    return (Y, Yh, Yr) if want_parts else Y
+
+
+def split_export(desc, split, what):
+    """INT4 test hook: (q int8 [m, d_model], scale bits uint16 as int16 tensor [m, d_model/group])."""
+    m = desc.d_ff - desc.k
+    q = torch.empty((m, desc.d_model), dtype=torch.int8, device=split.device)
+    s = torch.empty((m, desc.d_model // desc.group), dtype=torch.int16, device=split.device)
+    rc = lib.ffsplit_split_export(ctypes.byref(desc), _ptr(split), what, _ptr(q), _ptr(s), _stream())
+    _check(rc, "ffsplit_split_export")
+    return q, s

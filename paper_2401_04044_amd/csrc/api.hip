@@ -1,0 +1,365 @@
+// C ABI of libffsplit (declared in include/ffsplit.h): host-side validation,
+// the private packed-split layout, and the launch sequences of the four calls.
+#include "../../include/ffsplit.h"
+#include "layout.h"
+#include "prep.h"
+#include "int4.h"
+
+using namespace ffs;
+
+namespace {
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+int check_desc(const ffsplit_desc_t* d, bool need_split_fields) {
+  if (!d) return FFSPLIT_E_NULLPTR;
+  if (d->d_model <= 0 || d->d_ff <= 0) return FFSPLIT_E_BADDESC;
+  if (d->act != FFSPLIT_ACT_GELU && d->act != FFSPLIT_ACT_SWIGLU) return FFSPLIT_E_BADDESC;
+  if (d->dtype != FFSPLIT_F32 && d->dtype != FFSPLIT_BF16) return FFSPLIT_E_BADDESC;
+  if (d->d_model % 8 != 0) return FFSPLIT_E_BADSHAPE;
+  if (!need_split_fields) return FFSPLIT_OK;
+  if (d->rem_kind < FFSPLIT_REM_NONE || d->rem_kind > FFSPLIT_REM_INT4) return FFSPLIT_E_BADDESC;
+  if (d->k < 0 || d->k > d->d_ff) return FFSPLIT_E_BADSHAPE;
+  const int m = d->d_ff - d->k;
+  if (d->rem_kind == FFSPLIT_REM_LOWRANK && m > 0) {
+    if (d->rank <= 0) return FFSPLIT_E_BADSHAPE;
+    if (d->rank > (d->d_model < m ? d->d_model : m)) return FFSPLIT_E_BADSHAPE;
+  }
+  if (d->rem_kind == FFSPLIT_REM_INT4) {
+    if (d->group <= 0 || d->group % 32 != 0 || d->d_model % d->group != 0) return FFSPLIT_E_BADSHAPE;
+    if (d->dtype != FFSPLIT_BF16) return FFSPLIT_E_UNSUPPORTED;
+    if (d->group != 128 || d->d_model % 128 != 0) return FFSPLIT_E_UNSUPPORTED;
+  }
+  return FFSPLIT_OK;
+}
+
+inline int act_of(const ffsplit_desc_t* d) { return d->act == FFSPLIT_ACT_SWIGLU ? ACT_GLU : ACT_GELU; }
+
+#define FFS_TRY(expr)                      \
+  do {                                     \
+    if ((expr) != 0) return FFSPLIT_E_HIP; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* ffsplit_status_string(int s) {
+  switch (s) {
+    case FFSPLIT_OK: return "ok";
+    case FFSPLIT_E_NULLPTR: return "required pointer is NULL";
+    case FFSPLIT_E_BADDESC: return "invalid descriptor field";
+    case FFSPLIT_E_BADSHAPE: return "inconsistent shape (k, rank, group, d_model or T)";
+    case FFSPLIT_E_ALIGN: return "pointer not 16-byte aligned";
+    case FFSPLIT_E_WORKSPACE: return "workspace missing or too small";
+    case FFSPLIT_E_UNSUPPORTED: return "combination not supported";
+    case FFSPLIT_E_NONFINITE: return "NaN among the scores";
+    case FFSPLIT_E_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t ffsplit_split_bytes(const ffsplit_desc_t* d) {
+  if (check_desc(d, true) != FFSPLIT_OK) return 0;
+  return make_layout(*d).total_bytes;
+}
+
+size_t ffsplit_workspace_bytes(const ffsplit_desc_t* d, int32_t call_id, int64_t T) {
+  if (call_id == FFSPLIT_WS_SELECT) return d ? select_workspace_bytes(d->d_ff) : 0;
+  if (check_desc(d, call_id != FFSPLIT_WS_SCORE) != FFSPLIT_OK || T < 0) return 0;
+  const size_t esz = d->dtype == FFSPLIT_BF16 ? 2 : 4;
+  if (call_id == FFSPLIT_WS_SCORE) {
+    const ScoreWs w = make_score_ws(*d, T);
+    return w.total_bytes;
+  }
+  if (call_id == FFSPLIT_WS_BUILD) return build_ws_bytes(*d);
+  if (call_id == FFSPLIT_WS_FORWARD) {
+    const Layout L = make_layout(*d);
+    const FwdWs w = make_fwd_ws(*d, L, T);
+    (void)esz;
+    return w.total_bytes;
+  }
+  return 0;
+}
+
+int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, const void* W1, const void* Wg,
+                          const void* W2, float* acc, int64_t* T_total, float* scores, int32_t score_kind,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_desc(d, false);
+  if (rc) return rc;
+  if (T < 0 || T > 0x7fffffff) return FFSPLIT_E_BADSHAPE;
+  if (score_kind < 0 || score_kind > 2) return FFSPLIT_E_BADDESC;
+  const bool glu = d->act == FFSPLIT_ACT_SWIGLU;
+  if (!acc || !T_total || !W1 || (glu && !Wg) || (T > 0 && !X)) return FFSPLIT_E_NULLPTR;
+  if (scores && score_kind != FFSPLIT_SCORE_ACT_ONLY && !W2) return FFSPLIT_E_NULLPTR;
+  if (misaligned(X) || misaligned(W1) || misaligned(Wg) || misaligned(W2) || misaligned(acc) || misaligned(scores))
+    return FFSPLIT_E_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  const int bf16 = d->dtype == FFSPLIT_BF16;
+  const int esz = bf16 ? 2 : 4;
+  if (T > 0) {
+    const ScoreWs w = make_score_ws(*d, T);
+    if (!workspace || workspace_bytes < w.total_bytes) return FFSPLIT_E_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return FFSPLIT_E_ALIGN;
+    char* ws = (char*)workspace;
+    void* Wt = ws + w.off_wt;
+    float* p2 = (float*)(ws + w.off_p2);
+    float* p1 = (float*)(ws + w.off_p1);
+    // transposed (neuron-major) copy of the up projection(s); rows beyond d_ff are zero
+    FFS_TRY(launch_fill_zero(Wt, w.wt_bytes, st));
+    PermArgs pa = {};
+    pa.lds = d->d_ff;
+    pa.dst = Wt;
+    pa.ldd = d->d_model;
+    pa.n_count = d->d_ff;
+    pa.c_count = d->d_model;
+    if (glu) {
+      pa.src = Wg; pa.glu_mode = 1;
+      FFS_TRY(launch_permute_transpose(pa, esz, st));
+      pa.src = W1; pa.glu_mode = 2;
+      FFS_TRY(launch_permute_transpose(pa, esz, st));
+    } else {
+      pa.src = W1; pa.glu_mode = 0;
+      FFS_TRY(launch_permute_transpose(pa, esz, st));
+    }
+    GemmArgs g = {};
+    g.A = X; g.lda = d->d_model;
+    g.Bt = Wt; g.ldb = d->d_model;
+    g.M = (int)T; g.N = w.n_gemm; g.K = d->d_model;
+    g.act_cols = w.n_gemm;
+    g.part_s2 = p2; g.part_s1 = p1; g.n_out = w.n_out;
+    FFS_TRY(launch_gemm(g, bf16, act_of(d), true, st));
+    FFS_TRY(launch_reduce_partials(p2, p1, w.tiles_m, w.n_out, d->d_ff, acc, st));
+    *T_total += T;
+  }
+  if (scores)
+    FFS_TRY(launch_finalize_scores(W2, bf16, d->d_model, d->d_ff, acc, (float)*T_total, score_kind, scores, st));
+  return FFSPLIT_OK;
+}
+
+int ffsplit_select_heavy(const float* scores, int32_t d_ff, int32_t k, int32_t* idx, int32_t* perm,
+                         int32_t* nan_flag, void* workspace, size_t workspace_bytes, void* stream) {
+  if (d_ff <= 0) return FFSPLIT_E_BADDESC;
+  if (k < 0 || k > d_ff) return FFSPLIT_E_BADSHAPE;
+  if (!scores || (k > 0 && !idx)) return FFSPLIT_E_NULLPTR;
+  if (!workspace || workspace_bytes < select_workspace_bytes(d_ff)) return FFSPLIT_E_WORKSPACE;
+  if (misaligned(scores) || misaligned(workspace)) return FFSPLIT_E_ALIGN;
+  FFS_TRY(launch_select(scores, d_ff, k, idx, perm, nan_flag, workspace, (hipStream_t)stream));
+  return FFSPLIT_OK;
+}
+
+int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg, const void* W2,
+                        const int32_t* idx, const void* const* factors, void* split, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  int rc = check_desc(d, true);
+  if (rc) return rc;
+  const bool glu = d->act == FFSPLIT_ACT_SWIGLU;
+  const int k = d->k, m = d->d_ff - d->k, dm = d->d_model;
+  if (!split || !W1 || !W2 || (glu && !Wg) || (k > 0 && !idx)) return FFSPLIT_E_NULLPTR;
+  const bool lowrank = d->rem_kind == FFSPLIT_REM_LOWRANK && m > 0;
+  if (lowrank) {
+    if (!factors) return FFSPLIT_E_NULLPTR;
+    for (int i = 0; i < 6; ++i) {
+      const bool gate = (i == 2 || i == 3);
+      if ((!gate || glu) && !factors[i]) return FFSPLIT_E_NULLPTR;
+      if (misaligned(factors[i])) return FFSPLIT_E_ALIGN;
+    }
+  }
+  if (misaligned(W1) || misaligned(Wg) || misaligned(W2) || ((uintptr_t)split & 255u)) return FFSPLIT_E_ALIGN;
+  const bool need_rest = (d->rem_kind == FFSPLIT_REM_DENSE || d->rem_kind == FFSPLIT_REM_INT4) && m > 0;
+  const size_t ws_need = need_rest ? build_ws_bytes(*d) : 0;
+  if (need_rest && (!workspace || workspace_bytes < ws_need)) return FFSPLIT_E_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int esz = d->dtype == FFSPLIT_BF16 ? 2 : 4;
+  const Layout L = make_layout(*d);
+  char* sp = (char*)split;
+  FFS_TRY(launch_fill_zero(split, L.total_bytes, st));
+
+  // remainder neurons in ascending order (needed when the library itself gathers them)
+  int32_t* rest = nullptr;
+  if (need_rest) {
+    rest = (int32_t*)workspace;
+    FFS_TRY(launch_rest_order(idx, k, d->d_ff, rest, (int32_t*)workspace + d->d_ff, st));
+  }
+
+  if (d->rem_kind == FFSPLIT_REM_INT4) {
+    FFS_TRY(launch_int4_pack(*d, L, W1, Wg, W2, rest, idx, sp, st));
+    return FFSPLIT_OK;
+  }
+
+  // ---- heavy block: W1h^T (and Wgh^T) rows of B1t, W2h^T columns of B4t
+  PermArgs pa = {};
+  if (k > 0) {
+    pa = {};
+    pa.lds = d->d_ff; pa.dst = sp + L.off_b1; pa.ldd = dm;
+    pa.n_count = k; pa.c_count = dm; pa.nmap = idx;
+    if (glu) {
+      pa.src = Wg; pa.glu_mode = 1; FFS_TRY(launch_permute_transpose(pa, esz, st));
+      pa.src = W1; pa.glu_mode = 2; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    } else {
+      pa.src = W1; pa.glu_mode = 0; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    }
+    pa = {};
+    pa.src = W2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4;
+    pa.n_count = dm; pa.c_count = k; pa.cmap = idx;
+    FFS_TRY(launch_permute_transpose(pa, esz, st));
+  }
+  if (m == 0 || d->rem_kind == FFSPLIT_REM_NONE) return FFSPLIT_OK;
+
+  if (d->rem_kind == FFSPLIT_REM_DENSE) {
+    // remainder neurons appended to the same blocks after the padded heavy part
+    pa = {};
+    pa.lds = d->d_ff; pa.dst = sp + L.off_b1; pa.ldd = dm;
+    pa.n_count = m; pa.c_count = dm; pa.nmap = rest;
+    pa.row_off = (int64_t)L.n_up * L.kp;
+    if (glu) {
+      pa.src = Wg; pa.glu_mode = 1; FFS_TRY(launch_permute_transpose(pa, esz, st));
+      pa.src = W1; pa.glu_mode = 2; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    } else {
+      pa.src = W1; pa.glu_mode = 0; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    }
+    pa = {};
+    pa.src = W2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4;
+    pa.n_count = dm; pa.c_count = m; pa.cmap = rest; pa.coff = L.kp;
+    FFS_TRY(launch_permute_transpose(pa, esz, st));
+    return FFSPLIT_OK;
+  }
+
+  if (d->rem_kind == FFSPLIT_REM_LOWRANK) {
+    const int r = d->rank;
+    const void* P1 = factors[0]; const void* Q1 = factors[1];
+    const void* Pg = factors[2]; const void* Qg = factors[3];
+    const void* P2 = factors[4]; const void* Q2 = factors[5];
+    // P^T rows of B1t after the heavy rows: [Pg^T ; P1^T] (SwiGLU) or [P1^T]
+    pa = {};
+    pa.lds = r; pa.dst = sp + L.off_b1; pa.ldd = dm; pa.n_count = r; pa.c_count = dm;
+    pa.row_off = (int64_t)L.n_up * L.kp;
+    if (glu) {
+      pa.src = Pg; FFS_TRY(launch_permute_transpose(pa, esz, st));
+      pa.row_off += L.rp;
+    }
+    pa.src = P1; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    // Q1^T (and Qg^T, interleaved in 32-row blocks): [n_up*mp, rp]
+    pa = {};
+    pa.lds = m; pa.dst = sp + L.off_q1; pa.ldd = L.rp; pa.n_count = m; pa.c_count = r;
+    if (glu) {
+      pa.src = Qg; pa.glu_mode = 1; FFS_TRY(launch_permute_transpose(pa, esz, st));
+      pa.src = Q1; pa.glu_mode = 2; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    } else {
+      pa.src = Q1; FFS_TRY(launch_permute_transpose(pa, esz, st));
+    }
+    // P2^T: [rp, mp]
+    pa = {};
+    pa.src = P2; pa.lds = r; pa.dst = sp + L.off_p2; pa.ldd = L.mp; pa.n_count = r; pa.c_count = m;
+    FFS_TRY(launch_permute_transpose(pa, esz, st));
+    // Q2^T into the columns of B4t after the heavy ones
+    pa = {};
+    pa.src = Q2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4; pa.n_count = dm; pa.c_count = r;
+    pa.coff = L.kp;
+    FFS_TRY(launch_permute_transpose(pa, esz, st));
+    return FFSPLIT_OK;
+  }
+  return FFSPLIT_E_UNSUPPORTED;
+}
+
+int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, int64_t T, void* Y, void* Y_heavy,
+                    void* Y_rem, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_desc(d, true);
+  if (rc) return rc;
+  if (T < 0 || T > 0x7fffffff) return FFSPLIT_E_BADSHAPE;
+  if (T == 0) return FFSPLIT_OK;
+  if (!split || !X || !Y) return FFSPLIT_E_NULLPTR;
+  if (misaligned(X) || misaligned(Y) || misaligned(Y_heavy) || misaligned(Y_rem) || ((uintptr_t)split & 255u))
+    return FFSPLIT_E_ALIGN;
+  const Layout L = make_layout(*d);
+  const FwdWs w = make_fwd_ws(*d, L, T);
+  if (!workspace || workspace_bytes < w.total_bytes) return FFSPLIT_E_WORKSPACE;
+  if ((uintptr_t)workspace & 255u) return FFSPLIT_E_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  const int bf16 = d->dtype == FFSPLIT_BF16;
+  const int esz = bf16 ? 2 : 4;
+  const int act = act_of(d);
+  const bool glu = act == ACT_GLU;
+  const int dm = d->d_model, k = d->k, m = d->d_ff - d->k;
+  const char* sp = (const char*)split;
+  char* ws = (char*)workspace;
+  char* cat = ws + w.off_cat;    // [T, k4]  = [h1 | t2] (or [h1 | h_rest] for DENSE)
+  char* tbuf = ws + w.off_t;     // [T, n_up*rp]
+  char* h2 = ws + w.off_h2;      // [T, mp]
+  const int M = (int)T;
+  const bool rem_lr = d->rem_kind == FFSPLIT_REM_LOWRANK && m > 0;
+  const bool rem_dense = d->rem_kind == FFSPLIT_REM_DENSE && m > 0;
+  if (d->rem_kind == FFSPLIT_REM_INT4) {
+    const int r4 = int4_forward(*d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st);
+    return r4 == 0 ? FFSPLIT_OK : (r4 == -2 ? FFSPLIT_E_UNSUPPORTED : FFSPLIT_E_HIP);
+  }
+
+  // G1: X * [W1h | P1] (SwiGLU: [gate/up heavy pairs | Pg | P1]) -> h1 (activated) and t
+  if (L.n1 > 0) {
+    GemmArgs g = {};
+    g.A = X; g.lda = dm; g.Bt = sp + L.off_b1; g.ldb = dm;
+    g.M = M; g.N = L.n1; g.K = dm;
+    const int acted = rem_dense ? (L.kp + L.mp) : L.kp;   // neurons activated in this product
+    g.act_cols = L.n_up * acted;
+    g.split_col = acted;
+    g.C0 = cat; g.ldc0 = L.k4;
+    g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp;
+    FFS_TRY(launch_gemm(g, bf16, act, false, st));
+  }
+  if (rem_lr) {
+    // G2: t * Q1 -> activation -> h2
+    GemmArgs g = {};
+    g.A = tbuf; g.lda = (int64_t)L.n_up * L.rp;
+    if (glu) g.A1 = tbuf + (size_t)L.rp * esz;
+    g.Bt = sp + L.off_q1; g.ldb = L.rp;
+    g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
+    g.act_cols = g.N; g.split_col = L.mp;
+    g.C0 = h2; g.ldc0 = L.mp;
+    FFS_TRY(launch_gemm(g, bf16, act, false, st));
+    // G3: h2 * P2 -> t2 into cat[:, kp:]
+    g = {};
+    g.A = h2; g.lda = L.mp; g.Bt = sp + L.off_p2; g.ldb = L.mp;
+    g.M = M; g.N = L.rp; g.K = L.mp;
+    g.split_col = L.rp;
+    g.C0 = cat + (size_t)L.kp * esz; g.ldc0 = L.k4;
+    FFS_TRY(launch_gemm(g, bf16, ACT_NONE, false, st));
+  }
+  // G4: [h1 | t2] * [W2h ; Q2] -> Y   (one fp32 accumulation, one rounding: Eq. 2's sum)
+  auto down = [&](void* out, int koff, int klen) -> int {
+    GemmArgs g = {};
+    g.A = cat + (size_t)koff * esz; g.lda = L.k4;
+    g.Bt = sp + L.off_b4 + (size_t)koff * esz; g.ldb = L.k4;
+    g.M = M; g.N = dm; g.K = klen;
+    g.split_col = dm; g.C0 = out; g.ldc0 = dm;
+    return launch_gemm(g, bf16, ACT_NONE, false, st);
+  };
+  if (L.k4 > 0) {
+    FFS_TRY(down(Y, 0, L.k4));
+  } else {
+    FFS_TRY(launch_fill_zero(Y, (size_t)M * dm * esz, st));
+  }
+  if (Y_heavy) {
+    if (L.kp > 0) FFS_TRY(down(Y_heavy, 0, L.kp));
+    else FFS_TRY(launch_fill_zero(Y_heavy, (size_t)M * dm * esz, st));
+  }
+  if (Y_rem) {
+    if (L.k4 > L.kp) FFS_TRY(down(Y_rem, L.kp, L.k4 - L.kp));
+    else FFS_TRY(launch_fill_zero(Y_rem, (size_t)M * dm * esz, st));
+  }
+  (void)k;
+  return FFSPLIT_OK;
+}
+
+int ffsplit_split_export(const ffsplit_desc_t* d, const void* split, int32_t what, int8_t* q_out, uint16_t* s_out,
+                         void* stream) {
+  int rc = check_desc(d, true);
+  if (rc) return rc;
+  if (d->rem_kind != FFSPLIT_REM_INT4) return FFSPLIT_E_UNSUPPORTED;
+  if (!split || !q_out || !s_out) return FFSPLIT_E_NULLPTR;
+  if (what < 0 || what > 2 || (what == 1 && d->act != FFSPLIT_ACT_SWIGLU)) return FFSPLIT_E_BADDESC;
+  const Layout L = make_layout(*d);
+  FFS_TRY(launch_int4_export(*d, L, (const char*)split, what, q_out, s_out, (hipStream_t)stream));
+  return FFSPLIT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+// Internal: the private layout of the packed split and of the per-call scratch.
+// Pure host arithmetic on the descriptor, so that no call ever has to read
+// device memory to find its way around a split.
+#pragma once
+#include "../../include/ffsplit.h"
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ffs {
+
+inline int round_up(int v, int q) { return (v + q - 1) / q * q; }
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// All matrices of the split are stored "neuron-major" (transposed, K-contiguous),
+// zero-padded: a padded neuron has a zero up column and a zero down row, and
+// gelu(0) = silu(0)*0 = 0, so padding changes no result.
+//   B1t [n1, d]      rows: heavy W1^T (SwiGLU: 32-row blocks gate/up interleaved),
+//                    then LOWRANK: Pg^T, P1^T ;  DENSE: the remainder's W1^T likewise
+//   Q1t [n_up*mp, rp] LOWRANK: Q1^T (SwiGLU: Qg^T / Q1^T interleaved in 32-row blocks)
+//   P2t [rp, mp]      LOWRANK: P2^T
+//   B4t [d, k4]       columns: heavy W2^T (kp), then Q2^T (rp) or the remainder's W2^T (mp)
+struct Layout {
+  int n_up;   // 1 GeLU, 2 SwiGLU
+  int esz;
+  int kp, rp, mp;
+  int k4;     // K of the last product
+  int n1;     // rows of B1t
+  size_t off_b1, off_q1, off_p2, off_b4;
+  // INT4 remainder (decode layout, see int4.hip)
+  int jp16, jp128, kp128, groups;
+  size_t off_i4[3], off_s4[3];       // nibbles / scales of gate(W1), Wg, W2
+  size_t off_hv[3];                  // heavy bf16 blocks in decode order
+  size_t total_bytes;
+};
+
+inline Layout make_layout(const ffsplit_desc_t& d) {
+  Layout L = {};
+  L.n_up = d.act == FFSPLIT_ACT_SWIGLU ? 2 : 1;
+  L.esz = d.dtype == FFSPLIT_BF16 ? 2 : 4;
+  const int m = d.d_ff - d.k;
+  L.kp = round_up(d.k, 64);
+  const bool lr = d.rem_kind == FFSPLIT_REM_LOWRANK && m > 0;
+  const bool dn = d.rem_kind == FFSPLIT_REM_DENSE && m > 0;
+  const bool i4 = d.rem_kind == FFSPLIT_REM_INT4;
+  L.rp = lr ? round_up(d.rank, 64) : 0;
+  L.mp = (lr || dn) ? round_up(m, 64) : 0;
+  L.k4 = L.kp + (lr ? L.rp : 0) + (dn ? L.mp : 0);
+  L.n1 = L.n_up * L.k4;
+  size_t off = 0;
+  if (!i4) {
+    L.off_b1 = off; off = align256(off + (size_t)L.n1 * d.d_model * L.esz);
+    L.off_q1 = off; if (lr) off = align256(off + (size_t)L.n_up * L.mp * L.rp * L.esz);
+    L.off_p2 = off; if (lr) off = align256(off + (size_t)L.rp * L.mp * L.esz);
+    L.off_b4 = off; off = align256(off + (size_t)d.d_model * L.k4 * L.esz);
+  } else {
+    L.groups = d.d_model / 128;
+    L.jp16 = round_up(m, 16);
+    L.jp128 = round_up(m, 128);
+    L.kp = round_up(d.k, 16);
+    L.kp128 = round_up(d.k, 128);
+    L.k4 = L.kp; L.n1 = 0;
+    for (int w = 0; w < 3; ++w) {
+      const bool used = (w != 1) || L.n_up == 2;
+      const size_t nib = w == 2 ? (size_t)L.jp128 * d.d_model / 2 : (size_t)L.jp16 * d.d_model / 2;
+      const size_t sc = w == 2 ? (size_t)L.jp128 * L.groups * 2 : (size_t)L.jp16 * L.groups * 2;
+      const size_t hv = w == 2 ? (size_t)L.kp128 * d.d_model * 2 : (size_t)L.kp * d.d_model * 2;
+      L.off_i4[w] = off; if (used) off = align256(off + nib);
+      L.off_s4[w] = off; if (used) off = align256(off + sc);
+      L.off_hv[w] = off; if (used) off = align256(off + hv);
+    }
+  }
+  L.total_bytes = off > 0 ? off : 256;
+  return L;
+}
+
+struct ScoreWs {
+  int n_gemm, n_out, tiles_m;
+  size_t off_wt, wt_bytes, off_p2, off_p1, total_bytes;
+};
+
+inline ScoreWs make_score_ws(const ffsplit_desc_t& d, int64_t T) {
+  ScoreWs w = {};
+  const int n_up = d.act == FFSPLIT_ACT_SWIGLU ? 2 : 1;
+  const int esz = d.dtype == FFSPLIT_BF16 ? 2 : 4;
+  const int tile_m = d.dtype == FFSPLIT_BF16 ? 128 : 64;
+  w.n_out = round_up(d.d_ff, 64);
+  w.n_gemm = n_up * w.n_out;
+  w.tiles_m = (int)((T + tile_m - 1) / tile_m);
+  w.off_wt = 0;
+  w.wt_bytes = align256((size_t)w.n_gemm * d.d_model * esz);
+  w.off_p2 = w.wt_bytes;
+  const size_t pb = align256((size_t)(w.tiles_m > 0 ? w.tiles_m : 1) * w.n_out * 4);
+  w.off_p1 = w.off_p2 + pb;
+  w.total_bytes = w.off_p1 + pb;
+  return w;
+}
+
+struct FwdWs {
+  size_t off_cat, off_t, off_h2;
+  // INT4 decode scratch
+  size_t off_h, off_part;
+  int n_split;
+  size_t total_bytes;
+};
+
+inline size_t build_ws_bytes(const ffsplit_desc_t& d) { return align256((size_t)8 * d.d_ff) + 256; }
+
+FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T);
+
+}  // namespace ffs

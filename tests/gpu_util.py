@@ -1,0 +1,47 @@
+"""Helpers for the GPU parity tests: move the seeded inputs to the device in
+their storage dtype and run the library's calls through the binding."""
+import numpy as np
+import torch
+
+TOL = {"bf16": 1e-2, "f32": 1e-5}      # relative Frobenius error, from the benchmark spec
+TDT = {"bf16": torch.bfloat16, "f32": torch.float32}
+
+
+def dev(a, dtype):
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda", dtype=TDT[dtype])
+
+
+def host(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def relf(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
+
+
+def desc_for(ff, cfg, rem_kind=None, k=None, rank=None):
+    rk = cfg.rem_kind if rem_kind is None else rem_kind
+    return ff.make_desc(cfg.d_model, cfg.d_ff, cfg.act, cfg.dtype, cfg.k if k is None else k, rk,
+                        (cfg.rank if rank is None else rank) if rk == "lowrank" else 0,
+                        cfg.group if rk == "int4" else 0)
+
+
+def layer_to_dev(L, dtype):
+    return {nm: dev(L[nm], dtype) for nm in ("W1", "W2", "Wg")}
+
+
+def gpu_scores(ff, desc, Ld, Xd_batches, kind=0):
+    d_ff = desc.d_ff
+    acc = torch.zeros(2 * d_ff, dtype=torch.float32, device="cuda")
+    scores = torch.empty(d_ff, dtype=torch.float32, device="cuda")
+    tt = 0
+    for i, Xd in enumerate(Xd_batches):
+        last = i == len(Xd_batches) - 1
+        tt = ff.score_neurons(desc, Xd, Ld["W1"], Ld["Wg"], Ld["W2"], acc, tt, scores if last else None, kind)
+    torch.cuda.synchronize()
+    return scores, acc, tt

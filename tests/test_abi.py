@@ -1,0 +1,85 @@
+"""The C-ABI library loads, exports every symbol the header declares, and turns
+bad arguments into error codes on the host before anything is launched (these
+run without a GPU: no call here reaches a kernel launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    txt = open(os.path.join(ROOT, "include", "ffsplit.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(ffsplit_[a-z_0-9]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2401_04044_amd as ff
+    syms = declared_symbols()
+    assert {"ffsplit_score_neurons", "ffsplit_select_heavy", "ffsplit_build_split", "ffsplit_forward"} <= set(syms)
+    for s in syms:
+        assert hasattr(ff.lib, s), s
+
+
+def test_status_strings_and_sizes():
+    import paper_2401_04044_amd as ff
+    assert ff.status_string(0) == "ok"
+    for c in range(-8, 0):
+        assert ff.status_string(c) != "unknown status"
+    d = ff.make_desc(2048, 8192, "gelu", "bf16", 246, "lowrank", 512)
+    sb = ff.split_bytes(d)
+    algorithmic = 2 * 2 * (2048 * 246 + 512 * (2048 + 7946))
+    assert algorithmic <= sb <= 1.03 * algorithmic        # padding stays small
+    assert ff.workspace_bytes(d, ff.WS_FORWARD, 4096) > 0
+    assert ff.workspace_bytes(d, ff.WS_FORWARD, 0) >= 0
+    d4 = ff.make_desc(4096, 11008, "swiglu", "bf16", 550, "int4", 0, 128)
+    assert 79.78e6 <= ff.split_bytes(d4) <= 1.02 * 79.78e6
+    # invalid descriptors give size 0
+    assert ff.split_bytes(ff.make_desc(2048, 8192, "gelu", "bf16", 9000, "lowrank", 512)) == 0
+    assert ff.split_bytes(ff.make_desc(2044, 8192, "gelu", "bf16", 10, "none")) == 0
+
+
+def test_argument_errors_are_found_on_the_host():
+    import paper_2401_04044_amd as ff
+    L = ff.lib
+    fake = ctypes.c_void_p(0x1000)          # aligned, never dereferenced: every call below fails validation
+    odd = ctypes.c_void_p(0x1004)
+    tt = ctypes.c_int64(0)
+    good = ff.make_desc(64, 256, "gelu", "bf16", 16, "lowrank", 8)
+    ref = ctypes.byref
+    # NULL descriptor / pointers
+    assert L.ffsplit_forward(None, fake, fake, 4, fake, None, None, fake, 1 << 30, None) == -1
+    assert L.ffsplit_forward(ref(good), None, fake, 4, fake, None, None, fake, 1 << 30, None) == -1
+    assert L.ffsplit_score_neurons(ref(good), fake, 4, None, None, fake, fake, ref(tt), None, 0, fake, 1 << 30, None) == -1
+    # bad descriptor fields
+    bad = ff.make_desc(64, 256, 7, "bf16", 16, "none")
+    assert L.ffsplit_forward(ref(bad), fake, fake, 4, fake, None, None, fake, 1 << 30, None) == -2
+    bad = ff.make_desc(64, 256, "gelu", 5, 16, "none")
+    assert L.ffsplit_build_split(ref(bad), fake, None, fake, fake, None, fake, fake, 1 << 30, None) == -2
+    # bad shapes
+    for bad in (ff.make_desc(64, 256, "gelu", "bf16", 257, "none"),
+                ff.make_desc(60, 256, "gelu", "bf16", 16, "none"),
+                ff.make_desc(64, 256, "gelu", "bf16", 16, "lowrank", 0),
+                ff.make_desc(64, 256, "gelu", "bf16", 16, "lowrank", 65),
+                ff.make_desc(256, 1024, "swiglu", "bf16", 16, "int4", 0, 96)):
+        assert L.ffsplit_forward(ref(bad), fake, fake, 4, fake, None, None, fake, 1 << 30, None) == -3
+    assert L.ffsplit_forward(ref(good), fake, fake, -1, fake, None, None, fake, 1 << 30, None) == -3
+    assert L.ffsplit_select_heavy(fake, 100, 101, fake, None, None, fake, 1 << 20, None) == -3
+    # int4 needs bf16
+    bad = ff.make_desc(256, 1024, "swiglu", "f32", 16, "int4", 0, 128)
+    assert L.ffsplit_forward(ref(bad), fake, fake, 4, fake, None, None, fake, 1 << 30, None) == -6
+    # alignment
+    assert L.ffsplit_forward(ref(good), fake, odd, 4, fake, None, None, fake, 1 << 30, None) == -4
+    # workspace too small / missing
+    assert L.ffsplit_forward(ref(good), fake, fake, 4, fake, None, None, fake, 16, None) == -5
+    assert L.ffsplit_forward(ref(good), fake, fake, 4, fake, None, None, None, 0, None) == -5
+    assert L.ffsplit_select_heavy(fake, 100, 10, fake, None, None, fake, 8, None) == -5
+    assert L.ffsplit_score_neurons(ref(good), fake, 4, fake, None, fake, fake, ref(tt), None, 0, fake, 16, None) == -5
+    # missing factors for a low-rank build
+    assert L.ffsplit_build_split(ref(good), fake, None, fake, fake, None, fake, fake, 1 << 30, None) == -1
+    # T = 0 is a valid no-op that launches nothing
+    assert L.ffsplit_forward(ref(good), fake, fake, 0, fake, None, None, None, 0, None) == 0
+    assert tt.value == 0

@@ -1,0 +1,250 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same seeded
+inputs.  Integer results (heavy indices, int4 codes, scale bits) are compared
+bit for bit; floating-point outputs by relative Frobenius error, 1e-2 for bf16
+and 1e-5 for fp32."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ffsplit_oracle as orc
+import workloads as wl
+from workloads.configs import C1, C2, C3, C4, C5, reduced
+from gpu_util import TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ff():
+    import paper_2401_04044_amd as m
+    return m
+
+
+# ---------------------------------------------------------------- select: bit-exact
+
+def select_cases():
+    rng = np.random.default_rng(0)
+    big = rng.random(20480).astype(np.float32)
+    big[rng.integers(0, 20480, 3000)] = 0.5                       # many duplicates
+    return [
+        ("dups", rng.integers(0, 4, 1000).astype(np.float32), [0, 1, 7, 500, 1000]),
+        ("all_equal", np.full(3000, 2.5, np.float32), [0, 1, 1024, 1025, 3000]),
+        ("zeros_denormals", np.array([0.0, -0.0, 1e-45, 0.0, 1e-38, -0.0, 3e-45] * 37, np.float32), [1, 5, 100, 259]),
+        ("inf", np.array([np.inf, 1.0, np.inf, 3.0, 0.0], np.float32), [1, 2, 3, 5]),
+        ("random_ragged", rng.random(3077).astype(np.float32) ** 8, [154, 1023, 1024, 1025, 3077]),
+        ("big", big, [819, 4096, 20480]),
+        ("one", np.array([3.0], np.float32), [0, 1]),
+    ]
+
+
+@pytest.mark.parametrize("name,scores,ks", select_cases(), ids=[c[0] for c in select_cases()])
+def test_select_heavy_bit_exact(ff, name, scores, ks):
+    sd = torch.from_numpy(scores).cuda()
+    for k in ks:
+        idx, perm, flag = ff.select_heavy(sd, k, want_perm=True)
+        torch.cuda.synchronize()
+        want = orc.select_heavy(scores, k)
+        assert np.array_equal(idx.cpu().numpy(), want), (name, k)
+        assert np.array_equal(perm.cpu().numpy(), orc.neuron_permutation(want, len(scores))), (name, k)
+        assert int(flag.item()) == 0
+
+
+def test_select_reports_nan_and_stays_valid(ff):
+    s = np.array([1.0, np.nan, 3.0, 2.0], np.float32)
+    idx, perm, flag = ff.select_heavy(torch.from_numpy(s).cuda(), 2, want_perm=True)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == -7
+    assert sorted(perm.cpu().tolist()) == [0, 1, 2, 3]
+    assert idx.cpu().tolist() == [1, 2]
+
+
+# ---------------------------------------------------------------- score
+
+def f32_variant(cfg):
+    return cfg.__class__(**{**cfg.__dict__, "dtype": "f32", "name": cfg.name + "-f32"})
+
+
+SCORE_CASES = [
+    ("c1_full", C1, 512, (512,)),
+    ("c1_ragged_batches", C1, 333, (100, 1, 232)),
+    ("c2_reduced", reduced(C2, 256, 1000, rank=64), 300, (300,)),
+    ("c3_reduced_swiglu", reduced(C3, 192, 700, rank=64), 257, (129, 128)),
+    ("c3_reduced_swiglu_f32", f32_variant(reduced(C3, 64, 200, rank=16)), 70, (70,)),
+]
+
+
+@pytest.mark.parametrize("name,cfg,T,batches", SCORE_CASES, ids=[c[0] for c in SCORE_CASES])
+def test_score_and_selection_match_oracle(ff, name, cfg, T, batches):
+    L = wl.make_layer(cfg)
+    X = wl.make_tokens(cfg, T, wl.gen.S_CALIB)
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc = desc_for(ff, cfg, "none")
+    acc_o = orc.new_accumulator(cfg.d_ff)
+    xs, lo = [], 0
+    for b in batches:
+        orc.score_accumulate(acc_o, X[lo:lo + b], L["W1"], L["Wg"], cfg.act)
+        xs.append(dev(X[lo:lo + b], cfg.dtype))
+        lo += b
+    for kind in (0, 1, 2):
+        scores, acc, tt = gpu_scores(ff, desc, Ld, xs, kind)
+        assert tt == T
+        want = orc.neuron_scores(acc_o, L["W2"], kind)
+        got = scores.cpu().numpy()
+        assert relf(got, want) < TOL[cfg.dtype], (kind, relf(got, want))
+        assert relf(acc.cpu().numpy()[:cfg.d_ff], acc_o["S2"]) < TOL[cfg.dtype]
+        assert relf(acc.cpu().numpy()[cfg.d_ff:], acc_o["S1"]) < TOL[cfg.dtype]
+        # kernel exactness: the oracle's selection rule on the GPU's own scores
+        idx, _, _ = ff.select_heavy(scores, cfg.k)
+        torch.cuda.synchronize()
+        assert np.array_equal(idx.cpu().numpy(), orc.select_heavy(got, cfg.k))
+        # end to end: the same heavy set as the fp64 oracle (= the planted set)
+        if kind != 2:
+            assert np.array_equal(np.sort(idx.cpu().numpy()), np.sort(orc.select_heavy(want, cfg.k)))
+            assert np.array_equal(np.sort(idx.cpu().numpy()), L["planted"])
+
+
+def test_score_is_deterministic(ff):
+    cfg = reduced(C2, 256, 1000, rank=64)
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    xs = [dev(wl.make_tokens(cfg, 300, wl.gen.S_CALIB), cfg.dtype)]
+    a, _, _ = gpu_scores(ff, desc_for(ff, cfg, "none"), Ld, xs)
+    b, _, _ = gpu_scores(ff, desc_for(ff, cfg, "none"), Ld, xs)
+    assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------- forward, low-rank / dense / none
+
+FWD_CASES = [
+    ("c1_full", C1, 128),
+    ("c1_ragged_T", C1, 77),
+    ("c2_reduced", reduced(C2, 256, 1000, rank=64), 300),
+    ("c2_reduced_odd", reduced(C2, 320, 1111, rank=72), 131),
+    ("c3_reduced_swiglu", reduced(C3, 192, 700, rank=64), 257),
+    ("c3_reduced_swiglu_f32", f32_variant(reduced(C3, 64, 200, rank=16)), 70),
+    ("c5_reduced", reduced(C5, 128, 520, rank=40), 65),
+    ("single_token", reduced(C3, 128, 300, rank=32), 1),
+]
+
+
+def run_forward(ff, cfg, L, idx, T, rem_kind, factors=None, rank=None, X=None):
+    X = wl.make_tokens(cfg, T) if X is None else X
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc = desc_for(ff, cfg, rem_kind, k=len(idx), rank=rank)
+    fd = None if factors is None else {k: dev(v, cfg.dtype) for k, v in factors.items()}
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(np.asarray(idx, np.int32)).cuda(), fd)
+    Y, Yh, Yr = ff.forward(desc, split, dev(X, cfg.dtype), want_parts=True)
+    Y_only = ff.forward(desc, split, dev(X, cfg.dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y_only)
+    want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], np.asarray(idx), cfg.act, rem_kind, factors,
+                             group=cfg.group or 128)
+    return (host(Y), host(Yh), host(Yr)), want
+
+
+@pytest.mark.parametrize("name,cfg,T", FWD_CASES, ids=[c[0] for c in FWD_CASES])
+def test_forward_lowrank_matches_oracle(ff, name, cfg, T):
+    L = wl.make_layer(cfg)
+    idx = L["planted"][::-1].copy()             # any order of the heavy set is allowed
+    fac = wl.make_factors(cfg, L, idx)
+    got, want = run_forward(ff, cfg, L, idx, T, "lowrank", fac)
+    tol = TOL[cfg.dtype]
+    for g, w, nm in zip(got, want, ("Y", "Y_heavy", "Y_rem")):
+        assert relf(g, w) < tol, (nm, relf(g, w))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_forward_special_cases(ff, dtype, act):
+    base = reduced(C3 if act == "swiglu" else C2, 128, 333, rank=32)
+    cfg = base.__class__(**{**base.__dict__, "dtype": dtype})
+    L = wl.make_layer(cfg)
+    T = 50
+    X = wl.make_tokens(cfg, T)
+    dense = orc.dense_ffn(X, L["W1"], L["W2"], L["Wg"], act)
+    tol = TOL[dtype]
+    # heavy = all neurons: the split layer is the dense layer
+    allidx = np.arange(cfg.d_ff, dtype=np.int32)
+    for rk in ("none", "dense", "lowrank"):
+        got, want = run_forward(ff, cfg, L, allidx, T, rk, None, rank=8, X=X)
+        assert relf(got[0], dense) < tol and relf(got[0], want[0]) < tol
+        assert not got[2].any()
+    # dense remainder: again the dense layer, and the two parts add up
+    idx = L["planted"]
+    got, want = run_forward(ff, cfg, L, idx, T, "dense", X=X)
+    assert relf(got[0], dense) < tol
+    assert relf(got[1], want[1]) < tol and relf(got[2], want[2]) < tol
+    # remainder dropped
+    got, want = run_forward(ff, cfg, L, idx, T, "none", X=X)
+    assert relf(got[0], want[0]) < tol and not got[2].any()
+    # no heavy neuron at all: pure low-rank layer
+    none = np.zeros(0, np.int32)
+    fac = wl.make_factors(cfg, L, none, rank=32)
+    got, want = run_forward(ff, cfg, L, none, T, "lowrank", fac, rank=32, X=X)
+    assert relf(got[0], want[0]) < tol and not got[1].any()
+    # full-rank factors reproduce the dense layer
+    if dtype == "f32":
+        fac = wl.make_factors(cfg, L, idx, rank=128)
+        got, want = run_forward(ff, cfg, L, idx, T, "lowrank", fac, rank=128, X=X)
+        assert relf(got[0], dense) < 2e-4       # factors were rounded to fp32 after an fp64 factorisation
+        assert relf(got[0], want[0]) < tol
+
+
+def test_forward_is_deterministic_and_T0_is_noop(ff):
+    cfg = reduced(C2, 256, 1000, rank=64)
+    L = wl.make_layer(cfg)
+    fac = wl.make_factors(cfg, L, L["planted"])
+    a, _ = run_forward(ff, cfg, L, L["planted"], 200, "lowrank", fac)
+    b, _ = run_forward(ff, cfg, L, L["planted"], 200, "lowrank", fac)
+    assert np.array_equal(a[0], b[0])
+    desc = desc_for(ff, cfg, "lowrank")
+    assert ff.lib.ffsplit_forward(__import__("ctypes").byref(desc), None, None, 0, None, None, None, None, 0, None) == 0
+
+
+# ---------------------------------------------------------------- int4 remainder
+
+I4_CASES = [
+    ("c4_reduced", reduced(C4, 256, 700), (1, 4, 16)),
+    ("c4_reduced_ragged", reduced(C4, 384, 1000), (3, 16, 21)),
+    ("c4_gelu", reduced(C2, 256, 500).__class__(**{**reduced(C2, 256, 500).__dict__, "rem_kind": "int4", "group": 128}), (2,)),
+    ("c4_width1024", reduced(C4, 1024, 600), (5,)),
+]
+
+
+@pytest.mark.parametrize("name,cfg,Bs", I4_CASES, ids=[c[0] for c in I4_CASES])
+def test_int4_codes_scales_and_forward(ff, name, cfg, Bs):
+    L = wl.make_layer(cfg)
+    idx = L["planted"]
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc = desc_for(ff, cfg, "int4")
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
+    sw = orc.split_weights(L["W1"], L["W2"], L["Wg"], idx)
+    qw = orc.quantize_remainder(sw, cfg.group)
+    for what, nm in ((0, "W1r"), (1, "Wgr"), (2, "W2r")):
+        if nm not in qw:
+            continue
+        q, s = ff.split_export(desc, split, what)
+        torch.cuda.synchronize()
+        assert np.array_equal(q.cpu().numpy(), qw[nm][0]), nm            # integer codes, bit for bit
+        assert np.array_equal(s.cpu().numpy().view(np.uint16), qw[nm][1].view(np.uint16)), nm
+    for B in Bs:
+        X = wl.make_tokens(cfg, B)
+        Y, Yh, Yr = ff.forward(desc, split, dev(X, cfg.dtype), want_parts=True)
+        torch.cuda.synchronize()
+        want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=cfg.group)
+        for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
+            assert relf(host(g), w) < TOL["bf16"], (B, nm, relf(host(g), w))
+
+
+def test_int4_edge_sets(ff):
+    cfg = reduced(C4, 256, 300)
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    X = wl.make_tokens(cfg, 4)
+    for idx in (np.zeros(0, np.int32), np.arange(300, dtype=np.int32)):
+        desc = desc_for(ff, cfg, "int4", k=len(idx))
+        split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
+        Y = ff.forward(desc, split, dev(X, cfg.dtype))
+        torch.cuda.synchronize()
+        want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=128)
+        assert relf(host(Y), want[0]) < TOL["bf16"]
