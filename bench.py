@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the split feed-forward layer on one MI355X.
+
+Headline workload: the OPT-1.3B-shaped layer (d_model 2048, d_ff 8192, GeLU,
+bf16, k = 246 heavy neurons, rank-512 remainder), prefill of 8 x 512 = 4096
+tokens.  A step is one ffsplit_forward over that batch; the split it runs on
+comes from the library's own score -> select -> build calls (timed once, reported
+under "pipeline").  Inputs, weights and the packed split are resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+Also measured, as extra keys: the int4 decode of the Llama-2-7B-shaped layer at
+batch 1/4/16 against the HBM roofline (rotating over enough split copies that
+every weight byte comes from HBM, not from the 256 MB last-level cache).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15   # FLOP/s, dense bf16, MI355X datasheet
+HBM_PEAK = 8.0e12         # B/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-decode", action="store_true", help="skip the int4 decode section")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--copies", type=int, default=4, help="split copies rotated through in the prefill loop")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2401_04044_amd as ff
+    import workloads as wl
+    from workloads.configs import C2, C4
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    bf = torch.bfloat16
+    t_start = time.perf_counter()
+
+    def note(msg):
+        print(f"[bench {time.perf_counter() - t_start:6.1f}s] {msg}", file=sys.stderr, flush=True)
+
+    def dev(a, dt=bf):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to("cuda", dtype=dt)
+
+    def timed(fn, n, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) * 1e-3 / n, wall / n
+
+    # ------------------------------------------------------------ headline: C2 prefill
+    cfg = C2
+    T = cfg.prefill_T
+    L = wl.make_layer(cfg)
+    note("C2 weights generated")
+    W1, W2 = dev(L["W1"]), dev(L["W2"])
+    Xc = dev(wl.make_tokens(cfg, cfg.calib_T, wl.gen.S_CALIB))
+    desc = ff.make_desc(cfg.d_model, cfg.d_ff, cfg.act, cfg.dtype, cfg.k, "lowrank", cfg.rank)
+    acc = torch.zeros(2 * cfg.d_ff, dtype=torch.float32, device="cuda")
+    scores = torch.empty(cfg.d_ff, dtype=torch.float32, device="cuda")
+    ws_score = torch.empty(ff.workspace_bytes(desc, ff.WS_SCORE, cfg.calib_T), dtype=torch.uint8, device="cuda")
+
+    def do_score():
+        acc.zero_()
+        ff.score_neurons(desc, Xc, W1, None, W2, acc, 0, scores, ff.SCORE_SUMSQ, ws_score)
+
+    t_score, _ = timed(do_score, 5, 2)
+    t_select, _ = timed(lambda: ff.select_heavy(scores, cfg.k), 5, 2)
+    idx, _, flag = ff.select_heavy(scores, cfg.k)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    heavy_ok = bool(np.array_equal(np.sort(idx_h), L["planted"])) and int(flag.item()) == 0
+    note(f"score {t_score*1e6:.0f} us, select {t_select*1e6:.0f} us, heavy set ok={heavy_ok}")
+    fac = wl.make_factors(cfg, L, idx_h)
+    note("rank-512 factors of the remainder computed (host)")
+    facd = {k: dev(v) for k, v in fac.items()}
+    split0 = ff.build_split(desc, W1, None, W2, idx, facd)
+    t_build, _ = timed(lambda: ff.build_split(desc, W1, None, W2, idx, facd, split0), 3, 1)
+    splits = [split0] + [split0.clone() for _ in range(max(args.copies, 1) - 1)]
+    Xe_h = wl.make_tokens(cfg, T)
+    Xs = [dev(Xe_h)] + [dev(wl.make_tokens(cfg, T, wl.gen.S_EVAL, layer=i)) for i in range(1, len(splits))]
+    Y = torch.empty((T, cfg.d_model), dtype=bf, device="cuda")
+    ws = torch.empty(ff.workspace_bytes(desc, ff.WS_FORWARD, T), dtype=torch.uint8, device="cuda")
+    del Xc, ws_score
+    state = {"i": 0}
+
+    def step():
+        i = state["i"] % len(splits)
+        state["i"] += 1
+        ff.forward(desc, splits[i], Xs[i], Y, False, ws)
+
+    t_ev, t_wall = timed(step, args.steps, args.warmup)
+    flops = cfg.flops_per_token() * T
+    note(f"forward {t_ev*1e6:.1f} us/step (events), {t_wall*1e6:.1f} us/step (wall)")
+    # parity of the timed configuration on sampled rows (rows of X are independent)
+    from oracle import ffsplit_oracle as orc
+    ff.forward(desc, splits[0], Xs[0], Y, False, ws)
+    torch.cuda.synchronize()
+    rows = np.random.default_rng(0).choice(T, 32, replace=False)
+    want = orc.forward_split(Xe_h[rows], L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
+    got = Y[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    rel_err = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+
+    out = {
+        "metric": "split-FFN tokens/s per layer; % of MFMA peak (prefill) / HBM BW (decode)",
+        "value": T / t_wall,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": t_wall * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "C2 OPT-1.3B-shaped split FFN prefill: d_model=2048 d_ff=8192 GeLU k=246 rank=512 "
+                               "T=8x512=4096, one layer", "split_copies": len(splits)},
+        "roofline": {"bound": "mfma", "kernel": "ffsplit_forward: 4 chained gemm_bf16_kernel launches",
+                     "achieved": flops / t_ev / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                     "frac": flops / t_ev / MFMA_BF16_PEAK, "traffic": None,
+                     "flops_per_launch": flops, "us_per_launch_hip_events": t_ev * 1e6},
+        "parity": {"rel_frobenius_vs_oracle_32_rows": rel_err, "heavy_set_equals_planted": heavy_ok},
+        "pipeline": {"score_us_T4096": t_score * 1e6,
+                     "score_tflops": 2.0 * cfg.calib_T * cfg.d_model * cfg.d_ff / t_score / 1e12,
+                     "select_us": t_select * 1e6, "build_split_us": t_build * 1e6},
+    }
+
+    # ------------------------------------------------------------ cpu baseline: the oracle as it stands
+    if not args.no_cpu:
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        reps, spent = 0, 0.0
+        while spent < 10.0 and reps < 8:
+            t0 = time.perf_counter()
+            orc.forward_split(Xe_h, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)
+            spent += time.perf_counter() - t0
+            reps += 1
+        note(f"oracle timed: {reps} reps in {spent:.1f} s")
+        out["cpu_baseline"] = {"value": T * reps / spent, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"{reps} x the full {T}-token forward of the same layer (numpy fp64)"}
+
+    # ------------------------------------------------------------ extra: int4 decode (HBM-bound)
+    if not args.no_decode:
+        del splits, Xs, W1, W2, facd
+        torch.cuda.empty_cache()
+        c4 = C4
+        L4 = wl.make_layer(c4)
+        note("C4 weights generated")
+        d4 = ff.make_desc(c4.d_model, c4.d_ff, c4.act, c4.dtype, c4.k, "int4", 0, c4.group)
+        s4 = ff.build_split(d4, dev(L4["W1"]), dev(L4["Wg"]), dev(L4["W2"]), torch.from_numpy(L4["planted"]).cuda())
+        torch.cuda.synchronize()
+        n_copies = 16                                   # 16 x 80.8 MB = 1.3 GB >> 256 MB last-level cache
+        s4s = [s4] + [s4.clone() for _ in range(n_copies - 1)]
+        ws4 = torch.empty(ff.workspace_bytes(d4, ff.WS_FORWARD, 16), dtype=torch.uint8, device="cuda")
+        dec = {}
+        for B in c4.decode_B:
+            xb = dev(wl.make_tokens(c4, B))
+            yb = torch.empty((B, c4.d_model), dtype=bf, device="cuda")
+            st = {"i": 0}
+
+            def dstep():
+                ff.forward(d4, s4s[st["i"] % n_copies], xb, yb, False, ws4)
+                st["i"] += 1
+
+            t4, _ = timed(dstep, 160, 32)
+            note(f"int4 decode B={B}: {t4*1e6:.1f} us")
+            dec[f"B{B}"] = {"us": t4 * 1e6, "tokens_per_s": B / t4, "GBps": c4.weight_bytes() / t4 / 1e9,
+                            "frac_hbm": c4.weight_bytes() / t4 / HBM_PEAK}
+        out["decode_int4"] = {"workload": "C4 Llama-2-7B-shaped SwiGLU, k=550 bf16 heavy + int4-g128 remainder",
+                              "bytes_per_step": c4.weight_bytes(), "split_copies": n_copies, **dec}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

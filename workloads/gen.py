@@ -92,16 +92,16 @@ def truncated_factors(W: np.ndarray, r: int):
     """Best rank-r factors of W [p, q] (fp64): W ~= P @ Q, P [p, r], Q [r, q],
     from the eigen-decomposition of the Gram matrix on W's smaller side.  The
     singular values are shared evenly (sqrt each) between P and Q."""
-    W = np.asarray(W, dtype=np.float64)
+    W = np.ascontiguousarray(W, dtype=np.float64)
     p, q = W.shape
     if p <= q:
         lam, L = np.linalg.eigh(W @ W.T)            # ascending
-        L = L[:, ::-1][:, :r]
+        L = np.ascontiguousarray(L[:, ::-1][:, :r])
         s = np.sqrt(np.maximum(lam[::-1][:r], 0.0))
         Rt = (L.T @ W) / np.where(s > 0, s, 1.0)[:, None]
     else:
         lam, R = np.linalg.eigh(W.T @ W)
-        R = R[:, ::-1][:, :r]
+        R = np.ascontiguousarray(R[:, ::-1][:, :r])
         s = np.sqrt(np.maximum(lam[::-1][:r], 0.0))
         Rt = R.T
         L = (W @ R) / np.where(s > 0, s, 1.0)[None, :]
