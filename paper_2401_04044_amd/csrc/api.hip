@@ -5,7 +5,7 @@
 #include "prep.h"
 #include "int4.h"
 
-using namespace ffs;
+using namespace ffsplit;
 
 namespace {
 
@@ -110,7 +110,8 @@ int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, con
     PermArgs pa = {};
     pa.lds = d->d_ff;
     pa.dst = Wt;
-    pa.ldd = d->d_model;
+    pa.ldd = w.dk;
+    pa.dst_tiled = bf16;
     pa.n_count = d->d_ff;
     pa.c_count = d->d_model;
     if (glu) {
@@ -124,11 +125,13 @@ int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, con
     }
     GemmArgs g = {};
     g.A = X; g.lda = d->d_model;
-    g.Bt = Wt; g.ldb = d->d_model;
+    g.Bt = Wt; g.ldb = w.dk;
     g.M = (int)T; g.N = w.n_gemm; g.K = d->d_model;
+    g.group_m = 8;
     g.act_cols = w.n_gemm;
     g.part_s2 = p2; g.part_s1 = p1; g.n_out = w.n_out;
-    FFS_TRY(launch_gemm(g, bf16, act_of(d), true, st));
+    if (bf16) FFS_TRY(launch_gemm_bf16(g, act_of(d), true, 0, 1, st));
+    else FFS_TRY(launch_gemm_f32(g, act_of(d), true, st));
     FFS_TRY(launch_reduce_partials(p2, p1, w.tiles_m, w.n_out, d->d_ff, acc, st));
     *T_total += T;
   }
@@ -191,7 +194,7 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
   PermArgs pa = {};
   if (k > 0) {
     pa = {};
-    pa.lds = d->d_ff; pa.dst = sp + L.off_b1; pa.ldd = dm;
+    pa.lds = d->d_ff; pa.dst = sp + L.off_b1; pa.ldd = L.dk; pa.dst_tiled = L.tiled;
     pa.n_count = k; pa.c_count = dm; pa.nmap = idx;
     if (glu) {
       pa.src = Wg; pa.glu_mode = 1; FFS_TRY(launch_permute_transpose(pa, esz, st));
@@ -200,7 +203,7 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
       pa.src = W1; pa.glu_mode = 0; FFS_TRY(launch_permute_transpose(pa, esz, st));
     }
     pa = {};
-    pa.src = W2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4;
+    pa.src = W2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4; pa.dst_tiled = L.tiled;
     pa.n_count = dm; pa.c_count = k; pa.cmap = idx;
     FFS_TRY(launch_permute_transpose(pa, esz, st));
   }
@@ -209,7 +212,7 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
   if (d->rem_kind == FFSPLIT_REM_DENSE) {
     // remainder neurons appended to the same blocks after the padded heavy part
     pa = {};
-    pa.lds = d->d_ff; pa.dst = sp + L.off_b1; pa.ldd = dm;
+    pa.lds = d->d_ff; pa.dst = sp + L.off_b1; pa.ldd = L.dk; pa.dst_tiled = L.tiled;
     pa.n_count = m; pa.c_count = dm; pa.nmap = rest;
     pa.row_off = (int64_t)L.n_up * L.kp;
     if (glu) {
@@ -219,7 +222,7 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
       pa.src = W1; pa.glu_mode = 0; FFS_TRY(launch_permute_transpose(pa, esz, st));
     }
     pa = {};
-    pa.src = W2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4;
+    pa.src = W2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4; pa.dst_tiled = L.tiled;
     pa.n_count = dm; pa.c_count = m; pa.cmap = rest; pa.coff = L.kp;
     FFS_TRY(launch_permute_transpose(pa, esz, st));
     return FFSPLIT_OK;
@@ -232,7 +235,7 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
     const void* P2 = factors[4]; const void* Q2 = factors[5];
     // P^T rows of B1t after the heavy rows: [Pg^T ; P1^T] (SwiGLU) or [P1^T]
     pa = {};
-    pa.lds = r; pa.dst = sp + L.off_b1; pa.ldd = dm; pa.n_count = r; pa.c_count = dm;
+    pa.lds = r; pa.dst = sp + L.off_b1; pa.ldd = L.dk; pa.dst_tiled = L.tiled; pa.n_count = r; pa.c_count = dm;
     pa.row_off = (int64_t)L.n_up * L.kp;
     if (glu) {
       pa.src = Pg; FFS_TRY(launch_permute_transpose(pa, esz, st));
@@ -241,7 +244,7 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
     pa.src = P1; FFS_TRY(launch_permute_transpose(pa, esz, st));
     // Q1^T (and Qg^T, interleaved in 32-row blocks): [n_up*mp, rp]
     pa = {};
-    pa.lds = m; pa.dst = sp + L.off_q1; pa.ldd = L.rp; pa.n_count = m; pa.c_count = r;
+    pa.lds = m; pa.dst = sp + L.off_q1; pa.ldd = L.rp; pa.dst_tiled = L.tiled; pa.n_count = m; pa.c_count = r;
     if (glu) {
       pa.src = Qg; pa.glu_mode = 1; FFS_TRY(launch_permute_transpose(pa, esz, st));
       pa.src = Q1; pa.glu_mode = 2; FFS_TRY(launch_permute_transpose(pa, esz, st));
@@ -250,11 +253,11 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
     }
     // P2^T: [rp, mp]
     pa = {};
-    pa.src = P2; pa.lds = r; pa.dst = sp + L.off_p2; pa.ldd = L.mp; pa.n_count = r; pa.c_count = m;
+    pa.src = P2; pa.lds = r; pa.dst = sp + L.off_p2; pa.ldd = L.mp; pa.dst_tiled = L.tiled; pa.n_count = r; pa.c_count = m;
     FFS_TRY(launch_permute_transpose(pa, esz, st));
     // Q2^T into the columns of B4t after the heavy ones
     pa = {};
-    pa.src = Q2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4; pa.n_count = dm; pa.c_count = r;
+    pa.src = Q2; pa.lds = dm; pa.dst = sp + L.off_b4; pa.ldd = L.k4; pa.dst_tiled = L.tiled; pa.n_count = dm; pa.c_count = r;
     pa.coff = L.kp;
     FFS_TRY(launch_permute_transpose(pa, esz, st));
     return FFSPLIT_OK;
@@ -294,44 +297,63 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     return r4 == 0 ? FFSPLIT_OK : (r4 == -2 ? FFSPLIT_E_UNSUPPORTED : FFSPLIT_E_HIP);
   }
 
+  // Column offset inside a K-contiguous buffer: elements (row-major) or whole 16-wide
+  // k blocks of 1 KiB (tiled).
+  auto koff_bytes = [&](int koff) -> size_t { return L.tiled ? (size_t)(koff / 16) * 1024 : (size_t)koff * esz; };
+  auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
+    g.group_m = 8;
+    g.m_pad = w.t_pad;
+    if (!bf16) return launch_gemm_f32(g, a, false, st);
+    return launch_gemm_bf16(g, a, false, shape, n_split, st);
+  };
+  const int big_m = M > 1024;   // 256-row tiles only pay off with enough rows
+
   // G1: X * [W1h | P1] (SwiGLU: [gate/up heavy pairs | Pg | P1]) -> h1 (activated) and t
   if (L.n1 > 0) {
     GemmArgs g = {};
-    g.A = X; g.lda = dm; g.Bt = sp + L.off_b1; g.ldb = dm;
+    g.A = X; g.lda = dm; g.Bt = sp + L.off_b1; g.ldb = L.dk;
     g.M = M; g.N = L.n1; g.K = dm;
     const int acted = rem_dense ? (L.kp + L.mp) : L.kp;   // neurons activated in this product
     g.act_cols = L.n_up * acted;
     g.split_col = acted;
-    g.C0 = cat; g.ldc0 = L.k4;
-    g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp;
-    FFS_TRY(launch_gemm(g, bf16, act, false, st));
+    g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
+    g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
+    FFS_TRY(run(g, act, (big_m && L.n1 >= 4096) ? 5 : 4, 1));
   }
   if (rem_lr) {
     // G2: t * Q1 -> activation -> h2
     GemmArgs g = {};
-    g.A = tbuf; g.lda = (int64_t)L.n_up * L.rp;
-    if (glu) g.A1 = tbuf + (size_t)L.rp * esz;
+    g.A = tbuf; g.lda = (int64_t)L.n_up * L.rp; g.a_tiled = L.tiled;
+    if (glu) g.A1 = tbuf + koff_bytes(L.rp);
     g.Bt = sp + L.off_q1; g.ldb = L.rp;
     g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
     g.act_cols = g.N; g.split_col = L.mp;
-    g.C0 = h2; g.ldc0 = L.mp;
-    FFS_TRY(launch_gemm(g, bf16, act, false, st));
-    // G3: h2 * P2 -> t2 into cat[:, kp:]
+    g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
+    FFS_TRY(run(g, act, big_m ? 5 : 4, 1));
+    // G3: h2 * P2 -> t2 into cat[:, kp:]  (long reduction: split-K, fixed-order sum)
     g = {};
-    g.A = h2; g.lda = L.mp; g.Bt = sp + L.off_p2; g.ldb = L.mp;
+    g.A = h2; g.lda = L.mp; g.a_tiled = L.tiled;
+    g.Bt = sp + L.off_p2; g.ldb = L.mp;
     g.M = M; g.N = L.rp; g.K = L.mp;
     g.split_col = L.rp;
-    g.C0 = cat + (size_t)L.kp * esz; g.ldc0 = L.k4;
-    FFS_TRY(launch_gemm(g, bf16, ACT_NONE, false, st));
+    if (bf16 && w.g3_split > 1) {
+      float* part = (float*)(ws + w.off_kpart);
+      g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
+      FFS_TRY(run(g, ACT_NONE, big_m ? 5 : 4, w.g3_split));
+      FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, 1, st));
+    } else {
+      g.C0 = cat + koff_bytes(L.kp); g.ldc0 = L.k4; g.c0_tiled = L.tiled;
+      FFS_TRY(run(g, ACT_NONE, big_m ? 5 : 4, 1));
+    }
   }
   // G4: [h1 | t2] * [W2h ; Q2] -> Y   (one fp32 accumulation, one rounding: Eq. 2's sum)
   auto down = [&](void* out, int koff, int klen) -> int {
     GemmArgs g = {};
-    g.A = cat + (size_t)koff * esz; g.lda = L.k4;
-    g.Bt = sp + L.off_b4 + (size_t)koff * esz; g.ldb = L.k4;
+    g.A = cat + koff_bytes(koff); g.lda = L.k4; g.a_tiled = L.tiled;
+    g.Bt = sp + L.off_b4 + koff_bytes(koff); g.ldb = L.k4;
     g.M = M; g.N = dm; g.K = klen;
-    g.split_col = dm; g.C0 = out; g.ldc0 = dm;
-    return launch_gemm(g, bf16, ACT_NONE, false, st);
+    g.split_col = dm; g.C0 = out; g.ldc0 = dm; g.n_store = dm;
+    return run(g, ACT_NONE, 4, 1);
   };
   if (L.k4 > 0) {
     FFS_TRY(down(Y, 0, L.k4));

@@ -5,7 +5,7 @@
 #include <stdint.h>
 #include <stddef.h>
 
-namespace ffs {
+namespace ffsplit {
 
 typedef uint16_t bf16_t;  // raw bf16 bits
 
@@ -17,8 +17,14 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
+// two fp32 -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const bf16x2_t r = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+  uint32_t u;
+  __builtin_memcpy(&u, &r, 4);
+  return u;
 }
 
 // exact GeLU z * Phi(z) (Sec. 2 cites it as the FFN activation)
@@ -48,14 +54,18 @@ __device__ __forceinline__ int block_prefix_1024(bool flag, int* wsum, int* tota
 }
 
 // One GEMM launch:  D[M, N] = A[M, K] * Bt[N, K]^T  followed by an epilogue.
-// A and Bt are K-contiguous.  With dual_a, 32-column blocks alternate between
-// A (even blocks) and A1 (odd blocks) as the left operand.
+// fp32 kernels: A and Bt row-major, K-contiguous.  bf16 kernels: Bt in the tiled
+// layout (see gemm_bf16.hip), A row-major or tiled, outputs row-major or tiled.
+// With A1 set, 32-column blocks alternate between A (even blocks) and A1 (odd
+// blocks) as the left operand.
 struct GemmArgs {
   const void* A;
   const void* A1;
   const void* Bt;
-  int64_t lda, ldb;
+  int64_t lda, ldb;   // row-major: elements per row; tiled: padded K of the buffer
   int M, N, K;
+  int a_tiled;
+  int group_m;     // bf16 kernels: row tiles per rasterisation group (>= 1)
   // epilogue
   // Columns [0, act_cols) get the activation; with ACT_GLU they are (gate, up)
   // pairs of 32-column blocks and produce act_cols/2 output columns.
@@ -66,14 +76,21 @@ struct GemmArgs {
   void* C0;
   void* C1;
   int64_t ldc0, ldc1;
-  int out_f32;     // bf16 kernels only: store fp32 instead of bf16
+  int c0_tiled, c1_tiled;
+  int m_pad;       // rows of a tiled destination (multiple of 32)
+  int n_store;     // valid columns of a row-major destination
+  int partial;     // bf16 kernels: write fp32 split-K partials [split][M][ldc0] to C0 instead
   // score mode: per-row-tile partial column sums of h^2 and |h|
   float* part_s2;  // [tiles_m, n_out]
   float* part_s1;
   int n_out;
 };
 
-int launch_gemm(const GemmArgs& a, int dtype_bf16, int act, bool score, hipStream_t st);
-int gemm_tile_m(int dtype_bf16);  // rows per score partial
+int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st);
+// shape: 0 = 128x128 tile, 1 = 256x128 tile; n_split > 1 only with a.partial
+int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_split, hipStream_t st);
+int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
+                         hipStream_t st);
+int bf16_score_tile_m();
 
-}  // namespace ffs
+}  // namespace ffsplit

@@ -1,0 +1,449 @@
+// bf16 MFMA GEMM of the split feed-forward path, gfx950 only.
+//
+//   D[M, N] = A[M, K] * B[N, K]^T ,  fp32 accumulation, fused epilogue.
+//
+// Data layouts
+//   "tiled": the matrix is cut into blocks of 32 rows x 16 k-elements (1 KiB).
+//     Inside a block the 16-byte chunk of lane l = 32 c + r holds row r,
+//     k-elements 8 c .. 8 c + 7, which is exactly the operand register image of
+//     v_mfma_f32_32x32x16_bf16.  Blocks are ordered [row block][k block], so a
+//     K slab of one row block is contiguous.  All packed weights and all
+//     intermediates between the chained products use this layout: global loads
+//     and LDS reads are then contiguous 1 KiB per wavefront instruction and free
+//     of bank conflicts by construction.
+//   "row-major": ordinary [rows, ld] (the caller's X and Y).
+//
+// Kernel: BM x BN workgroup tile, BK-deep slabs double-buffered in LDS, next
+// slab prefetched into registers during the MFMA phase; each wavefront owns a
+// (BM/WGM) x (BN/WGN) sub-tile of 32x32 MFMA tiles.  The MFMA is issued with the
+// weights as the first operand so that a lane ends up with 4 consecutive output
+// columns of one row; one v_permlane32_swap turns that into 8 consecutive
+// columns = one 16-byte chunk of the tiled (or row-major) output.
+//
+// Epilogues: plain / GeLU / SwiGLU (on (gate, up) pairs of 32-column blocks)
+// with two output destinations, fp32 split-K partials, and the neuron-norm
+// column reduction of Sec. 4.1 (Eq. 3) for the calibration pass.
+#include "common.h"
+
+namespace ffsplit {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;  // native vector: stays in registers
+
+union Frag {
+  u32x4_t u;
+  bf16x8_t v;
+};
+
+__device__ __forceinline__ int xcd_remap(int i, int total) {
+  const int q = total >> 3, rem = total & 7, x = i & 7;
+  return x * q + (x < rem ? x : rem) + (i >> 3);
+}
+
+// GeLU for the bf16 path: z * sigmoid(p(z)), p an odd quintic fitted to the exact
+// z * Phi(z); max abs error 2.8e-5 on the real line (bf16 rounding of the result
+// is ~2e-3 relative).  p is evaluated on z clamped to [-9, 9].
+__device__ __forceinline__ float gelu_fast(float z) {
+  const float zc = __builtin_amdgcn_fmed3f(z, -9.0f, 9.0f);
+  const float z2 = zc * zc;
+  float t = fmaf(z2, 0.0010238121f, -0.10683461f);   // -log2(e) * (c5, c3)
+  t = fmaf(z2, t, -2.3010564f);                      // -log2(e) * c1
+  const float e = __builtin_amdgcn_exp2f(t * zc);
+  return z * __builtin_amdgcn_rcpf(1.0f + e);
+}
+__device__ __forceinline__ float silu_fast(float z) {
+  const float e = __builtin_amdgcn_exp2f(-1.44269504f * z);
+  return z * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+template <int ACT>
+__device__ __forceinline__ float act_bf16(float z, float g) {
+  if (ACT == ACT_GELU) return gelu_fast(z);
+  if (ACT == ACT_GLU) return silu_fast(g) * z;
+  return z;
+}
+
+// swap the upper 32 lanes of a with the lower 32 lanes of b
+__device__ __forceinline__ void swap32(uint32_t& a, uint32_t& b) {
+  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  a = r[0];
+  b = r[1];
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int PF, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+__global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) gemm_bf16_kernel(const GemmArgs p) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int NA = DUAL ? 2 : 1;
+  constexpr int KB = BK / 16;                  // k blocks per slab
+  constexpr int A_CH = BM / 32 * KB * 64;      // 16-byte chunks of one A slab
+  constexpr int B_CH = BN / 32 * KB * 64;
+  constexpr int CA = A_CH / NT, CB = B_CH / NT;
+  constexpr int STAGE = NA * A_CH + B_CH;      // chunks per stage
+  constexpr bool SWAP = !SCORE;
+  static_assert(A_CH % NT == 0 && B_CH % NT == 0, "slab must divide over the threads");
+  static_assert(ACT != ACT_GLU || (TN % 2 == 0), "GLU needs paired column blocks per wave");
+
+  extern __shared__ u32x4_t smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int tiles_n = (p.N + BN - 1) / BN;
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int logical = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  // row tiles are walked in groups of p.group_m so that the tiles an XCD works on at
+  // one time form a compact 2-D block (operands shared through its L2)
+  const int gsz = p.group_m * tiles_n;
+  const int first_m = (logical / gsz) * p.group_m;
+  const int gm = min(tiles_m - first_m, p.group_m);
+  const int tm = first_m + (logical % gsz) % gm, tn = (logical % gsz) / gm;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // K range of this split (multiples of BK)
+  const int kt_total = (p.K + BK - 1) / BK;
+  const int kt_per = (kt_total + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int kt0 = blockIdx.y * kt_per;
+  const int kt1 = min(kt_total, kt0 + kt_per);
+
+  const char* Aptr[NA] = {(const char*)p.A};
+  if (DUAL) Aptr[NA - 1] = (const char*)p.A1;
+
+  // ---- per-thread source addresses and LDS slots
+  const char* a_src[NA][CA];
+  const char* b_src[CB];
+  int a_dst[CA];
+  int a_kc[CA];  // row-major: k offset (elements) of the chunk inside the slab
+  const int mrb_last = (p.M + 31) / 32 - 1;  // last valid row block of a tiled A
+#pragma unroll
+  for (int i = 0; i < CA; ++i) {
+    const int u = tid + i * NT;
+    if (A_TILED) {
+      // chunk u of the slab: row block u / (KB*64), then contiguous
+      const int rb = u / (KB * 64), rest = u % (KB * 64);
+      int grb = m0 / 32 + rb;
+      grb = grb <= mrb_last ? grb : mrb_last;
+#pragma unroll
+      for (int s = 0; s < NA; ++s)
+        a_src[s][i] = Aptr[s] + ((int64_t)grb * (p.lda / 16) * 64 + rest) * 16;
+      a_dst[i] = u;
+      a_kc[i] = 0;
+    } else {
+      // coalesced rows: 8 lanes x 8 rows per 16-byte column of chunks
+      constexpr int CPR = BK / 8;  // chunks per row
+      const int r8 = u & 7, ch = (u >> 3) % CPR, rg = u / (8 * CPR);
+      const int row = rg * 8 + r8;
+      int g = m0 + row;
+      g = g < p.M ? g : p.M - 1;
+#pragma unroll
+      for (int s = 0; s < NA; ++s) a_src[s][i] = Aptr[s] + ((int64_t)g * p.lda + ch * 8) * 2;
+      a_dst[i] = ((row >> 5) * KB + (ch >> 1)) * 64 + (ch & 1) * 32 + (row & 31);
+      a_kc[i] = ch * 8;
+    }
+  }
+  const int nrb_last = (p.N + 31) / 32 - 1;
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    const int u = tid + i * NT;
+    const int rb = u / (KB * 64), rest = u % (KB * 64);
+    int grb = n0 / 32 + rb;
+    grb = grb <= nrb_last ? grb : nrb_last;
+    b_src[i] = (const char*)p.Bt + ((int64_t)grb * (p.ldb / 16) * 64 + rest) * 16;
+  }
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // PF register sets hold the slabs in flight from global memory (slab s lives in set
+  // (s - kt0) % PF); LDS is double-buffered.
+  u32x4_t ra[PF][NA][CA], rb_[PF][CB];
+
+  auto load_global = [&](int kt, int set) {
+    const int64_t a_off = A_TILED ? (int64_t)kt * KB * 1024 : (int64_t)kt * BK * 2;
+    const int64_t b_off = (int64_t)kt * KB * 1024;
+#pragma unroll
+    for (int s = 0; s < NA; ++s)
+#pragma unroll
+      for (int i = 0; i < CA; ++i) {
+        if (A_TILED) ra[set][s][i] = *(const u32x4_t*)(a_src[s][i] + a_off);
+        else ra[set][s][i] = (kt * BK + a_kc[i]) < p.K ? *(const u32x4_t*)(a_src[s][i] + a_off) : u32x4_t{0, 0, 0, 0};
+      }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) rb_[set][i] = *(const u32x4_t*)(b_src[i] + b_off);
+  };
+  auto store_lds = [&](int buf, int set) {
+    u32x4_t* sA = smem + buf * STAGE;
+    u32x4_t* sB = sA + NA * A_CH;
+#pragma unroll
+    for (int s = 0; s < NA; ++s)
+#pragma unroll
+      for (int i = 0; i < CA; ++i) sA[s * A_CH + a_dst[i]] = ra[set][s][i];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) sB[tid + i * NT] = rb_[set][i];
+  };
+
+#pragma unroll
+  for (int j = 0; j < PF; ++j)
+    if (kt0 + j < kt1) load_global(kt0 + j, j);
+  if (kt0 < kt1) {
+    store_lds(0, 0);
+    if (kt0 + PF < kt1) load_global(kt0 + PF, 0);
+  }
+  __syncthreads();
+
+  for (int ktb = kt0; ktb < kt1; ktb += PF) {
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+      const int kt = ktb + j;
+      if (kt >= kt1) break;
+      const int cur = (kt - kt0) & 1;
+      const u32x4_t* sA = smem + cur * STAGE;
+      const u32x4_t* sB = sA + NA * A_CH;
+#pragma unroll
+      for (int ks = 0; ks < KB; ++ks) {
+        Frag a[NA][TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int s = 0; s < NA; ++s) a[s][i].u = sA[s * A_CH + ((wm * TM + i) * KB + ks) * 64 + lane];
+#pragma unroll
+        for (int jj = 0; jj < TN; ++jj) b[jj].u = sB[((wn * TN + jj) * KB + ks) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int jj = 0; jj < TN; ++jj) {
+            const Frag& af = a[DUAL ? (jj & 1) : 0][i];
+            if (SWAP)
+              acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[jj].v, af.v, acc[i][jj], 0, 0, 0);
+            else
+              acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, b[jj].v, acc[i][jj], 0, 0, 0);
+          }
+      }
+      if (kt + 1 < kt1) {
+        const int set = (j + 1) % PF;
+        store_lds(cur ^ 1, set);
+        if (kt + 1 + PF < kt1) load_global(kt + 1 + PF, set);
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---------------------------------------------------------------- epilogue
+  constexpr int JSTEP = (ACT == ACT_GLU) ? 2 : 1;
+  if (!SCORE) {
+    // lane: row = lane & 31; columns 8 g + 4 (lane >> 5) + 0..3 of each 32x32 tile
+    const int half = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int cb = n0 + wn * WN + j * 32;  // GEMM column of this 32-block
+      if (cb >= p.N) continue;
+      const bool act_here = cb < p.act_cols;
+      int oc;       // output column of the block
+      int jz = j, jg = j;  // accumulator tiles holding the value and the gate
+      if (ACT == ACT_GLU) {
+        if (act_here) {
+          if (j & 1) continue;  // the pair is written when its gate block comes up
+          oc = cb / 2; jz = j + 1; jg = j;
+        } else {
+          oc = cb - p.act_cols / 2;
+        }
+      } else {
+        oc = cb;
+      }
+      char* base;
+      int64_t ld;
+      int occ, tiled;
+      if (oc < p.split_col) { base = (char*)p.C0; ld = p.ldc0; occ = oc; tiled = p.c0_tiled; }
+      else { base = (char*)p.C1; ld = p.ldc1; occ = oc - p.split_col; tiled = p.c1_tiled; }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int rblk = (m0 + wm * WM) / 32 + i;
+        const int row = rblk * 32 + (lane & 31);
+        if (p.partial) {
+          // fp32 split-K partial, row-major [split][M][ld]
+          if (row < p.M) {
+            float* dst = (float*)base + ((int64_t)blockIdx.y * p.M + row) * ld + occ + 4 * half;
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              *(float4*)(dst + 8 * g) = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                                    acc[i][j][4 * g + 3]);
+          }
+          continue;
+        }
+        uint32_t pk[4][2];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float z = acc[i][(ACT == ACT_GLU) ? jz : j][4 * g + e];
+            const float gt = acc[i][(ACT == ACT_GLU) ? jg : j][4 * g + e];
+            v[e] = act_here ? act_bf16<ACT>(z, gt) : z;
+          }
+          pk[g][0] = pack_bf16x2(v[0], v[1]);
+          pk[g][1] = pack_bf16x2(v[2], v[3]);
+        }
+        // groups (0,1) and (2,3) each cover 16 consecutive columns: after the swap the lower
+        // lanes hold columns 0..7 and the upper lanes columns 8..15 of those 16
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          swap32(pk[2 * t][0], pk[2 * t + 1][0]);
+          swap32(pk[2 * t][1], pk[2 * t + 1][1]);
+          const u32x4_t val = {pk[2 * t][0], pk[2 * t][1], pk[2 * t + 1][0], pk[2 * t + 1][1]};
+          const int col = occ + 16 * t;  // block of 16 output columns
+          if (tiled) {
+            if (rblk * 32 < p.m_pad)
+              *(u32x4_t*)(base + (((int64_t)rblk * (ld / 16) + col / 16) * 64 + lane) * 16) = val;
+          } else {
+            if (row < p.M && col + 8 * half < p.n_store)
+              *(u32x4_t*)(base + ((int64_t)row * ld + col + 8 * half) * 2) = val;
+          }
+        }
+      }
+    }
+  } else {
+    // lane: column = lane & 31; rows 8 g + 4 (lane >> 5) + 0..3 of each 32x32 tile
+    constexpr int BNO = BN / JSTEP;
+    float* red2 = (float*)smem;  // [WGM][BNO]
+    float* red1 = red2 + WGM * BNO;
+#pragma unroll
+    for (int j = 0; j < TN; j += JSTEP) {
+      float s2 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          const float z = acc[i][(ACT == ACT_GLU) ? j + 1 : j][v];
+          const float gt = acc[i][j][v];
+          float h = (ACT == ACT_GLU) ? silu_f(gt) * z : gelu_f(z);   // exact forms for the scores
+          h = row < p.M ? h : 0.f;
+          s2 += h * h;
+          s1 += fabsf(h);
+        }
+      s2 += __shfl_xor(s2, 32);
+      s1 += __shfl_xor(s1, 32);
+      if (lane < 32) {
+        const int cl = (wn * WN + j * 32) / JSTEP + lane;
+        red2[wm * BNO + cl] = s2;
+        red1[wm * BNO + cl] = s1;
+      }
+    }
+    __syncthreads();
+    for (int t = tid; t < BNO; t += NT) {
+      const int col = n0 / JSTEP + t;
+      if (col < p.n_out) {
+        float a2 = 0.f, a1 = 0.f;
+#pragma unroll
+        for (int w = 0; w < WGM; ++w) { a2 += red2[w * BNO + t]; a1 += red1[w * BNO + t]; }
+        p.part_s2[(int64_t)tm * p.n_out + col] = a2;
+        p.part_s1[(int64_t)tm * p.n_out + col] = a1;
+      }
+    }
+  }
+}
+
+// Sum of fp32 split-K partials [n_split][M][N] (fixed order) -> bf16, tiled or row-major.
+__global__ void splitk_reduce_kernel(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc,
+                                     int tiled) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 8-column chunk each
+  const int cpr = N / 8;
+  if (id >= (int64_t)m_pad * cpr) return;
+  const int row = (int)(id / cpr), c8 = (int)(id % cpr) * 8;
+  float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (row < M)
+    for (int s = 0; s < n_split; ++s) {
+      const float4 a = *(const float4*)(part + ((int64_t)s * M + row) * N + c8);
+      const float4 b = *(const float4*)(part + ((int64_t)s * M + row) * N + c8 + 4);
+      v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w; v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+    }
+  const uint4 val = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                               pack_bf16x2(v[6], v[7]));
+  if (tiled) {
+    const int64_t blk = (int64_t)(row / 32) * (ldc / 16) + c8 / 16;
+    *(uint4*)((char*)C + ((blk * 64) + ((c8 >> 3) & 1) * 32 + (row & 31)) * 16) = val;
+  } else if (row < M) {
+    *(uint4*)((char*)C + ((int64_t)row * ldc + c8) * 2) = val;
+  }
+}
+
+int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
+                         hipStream_t st) {
+  const int64_t n = (int64_t)m_pad * (N / 8);
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, n_split, M, N,
+                     m_pad, C, ldc, tiled);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// ------------------------------------------------------------------ host launcher
+
+template <int BM, int BN, int BK, int WGM, int WGN, int PF, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+static int launch_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
+  constexpr int NA = DUAL ? 2 : 1;
+  constexpr size_t lds = (size_t)2 * (NA * BM + BN) * BK * 2;
+  auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, PF, ACT, DUAL, SCORE, A_TILED>;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return -1;
+    configured = true;
+  }
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * 64), lds, st, a);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int PF>
+static int launch_shape(const GemmArgs& a, int act, bool score, int n_split, hipStream_t st) {
+  const bool dual = a.A1 != nullptr;
+  const bool at = a.a_tiled != 0;
+  if (score) {
+    if constexpr (BM == 128 && BN == 128 && PF == 1 && BK == 64) {
+      if (at) return -1;
+      if (act == ACT_GELU) return launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GELU, false, true, false>(a, 1, st);
+      if (act == ACT_GLU) return launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, false, true, false>(a, 1, st);
+    }
+    return -1;
+  }
+  if (act == ACT_NONE)
+    return at ? launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_NONE, false, false, true>(a, n_split, st)
+              : launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_NONE, false, false, false>(a, n_split, st);
+  if (act == ACT_GELU)
+    return at ? launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GELU, false, false, true>(a, 1, st)
+              : launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GELU, false, false, false>(a, 1, st);
+  if (act == ACT_GLU && !dual)
+    return at ? launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, false, false, true>(a, 1, st)
+              : launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, false, false, false>(a, 1, st);
+  if (act == ACT_GLU && dual && at) return launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, true, false, true>(a, 1, st);
+  return -1;
+}
+
+int bf16_score_tile_m() { return 128; }
+
+// shape: 0 = 128x128 tile (small / skinny problems), 1 = 256x128 tile
+int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_split, hipStream_t st) {
+  if (a.M <= 0 || a.N <= 0) return 0;
+  if (score) return launch_shape<128, 128, 64, 2, 2, 1>(a, act, score, n_split, st);
+  switch (shape) {
+    case 0: return launch_shape<128, 128, 64, 2, 2, 1>(a, act, score, n_split, st);
+    case 1: return launch_shape<256, 128, 32, 2, 2, 1>(a, act, score, n_split, st);
+    case 2: return launch_shape<256, 256, 64, 2, 4, 1>(a, act, score, n_split, st);
+    case 3: return launch_shape<256, 256, 32, 2, 4, 1>(a, act, score, n_split, st);
+    case 4: return launch_shape<128, 128, 64, 2, 2, 2>(a, act, score, n_split, st);
+    case 5: return launch_shape<256, 128, 32, 2, 2, 2>(a, act, score, n_split, st);
+    case 6: return launch_shape<256, 128, 32, 2, 2, 3>(a, act, score, n_split, st);
+    case 7: return launch_shape<256, 256, 32, 2, 4, 2>(a, act, score, n_split, st);
+    case 8: return launch_shape<256, 256, 32, 2, 4, 3>(a, act, score, n_split, st);
+    case 9: return launch_shape<128, 128, 32, 2, 2, 3>(a, act, score, n_split, st);
+  }
+  return -1;
+}
+
+}  // namespace ffsplit

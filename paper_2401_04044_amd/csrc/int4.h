@@ -5,7 +5,7 @@
 #include "layout.h"
 #include "prep.h"
 
-namespace ffs {
+namespace ffsplit {
 
 int launch_rest_order(const int32_t* idx, int k, int d_ff, int32_t* rest, int32_t* flags, hipStream_t st);
 int launch_int4_pack(const ffsplit_desc_t& d, const Layout& L, const void* W1, const void* Wg, const void* W2,
@@ -15,4 +15,4 @@ int launch_int4_export(const ffsplit_desc_t& d, const Layout& L, const char* spl
 int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X, int M,
                  void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st);
 
-}  // namespace ffs
+}  // namespace ffsplit

@@ -23,7 +23,7 @@
 // MFMA operand per lane and 32-element step).
 #include "int4.h"
 
-namespace ffs {
+namespace ffsplit {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -569,9 +569,23 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     return w;
   }
   size_t off = 0;
-  w.off_cat = off; off = align256(off + (size_t)T * L.k4 * L.esz);
-  w.off_t = off; off = align256(off + (size_t)T * L.n_up * L.rp * L.esz);
-  w.off_h2 = off; off = align256(off + (size_t)T * L.mp * L.esz);
+  w.t_pad = L.tiled ? round_up((int)T, 32) : (int)T;
+  w.off_cat = off; off = align256(off + (size_t)w.t_pad * L.k4 * L.esz);
+  w.off_t = off; off = align256(off + (size_t)w.t_pad * L.n_up * L.rp * L.esz);
+  w.off_h2 = off; off = align256(off + (size_t)w.t_pad * L.mp * L.esz);
+  w.g3_split = 1;
+  w.off_kpart = off;
+  if (L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
+    // split the long reduction of h2 * P2 until about two workgroups per CU exist
+    const int tiles = (int)((T + 255) / 256) * ((L.rp + 127) / 128);
+    int sp = 512 / (tiles > 0 ? tiles : 1);
+    const int max_sp = L.mp / 256 > 0 ? L.mp / 256 : 1;   // keep >= 8 slabs of 32 per split
+    if (sp > max_sp) sp = max_sp;
+    if (sp > 16) sp = 16;
+    if (sp < 1) sp = 1;
+    w.g3_split = sp;
+    if (sp > 1) off = align256(off + (size_t)sp * T * L.rp * 4);
+  }
   w.total_bytes = off > 0 ? off : 256;
   return w;
 }
@@ -643,4 +657,4 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
   return 0;
 }
 
-}  // namespace ffs
+}  // namespace ffsplit

@@ -6,14 +6,16 @@
 #include <stddef.h>
 #include <stdint.h>
 
-namespace ffs {
+namespace ffsplit {
 
 inline int round_up(int v, int q) { return (v + q - 1) / q * q; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // All matrices of the split are stored "neuron-major" (transposed, K-contiguous),
 // zero-padded: a padded neuron has a zero up column and a zero down row, and
-// gelu(0) = silu(0)*0 = 0, so padding changes no result.
+// gelu(0) = silu(0)*0 = 0, so padding changes no result.  fp32: row-major with
+// the given row length.  bf16: the 32x16-block tiled layout of gemm_bf16.hip,
+// rows padded to 32 and the row length (K) to 64.
 //   B1t [n1, d]      rows: heavy W1^T (SwiGLU: 32-row blocks gate/up interleaved),
 //                    then LOWRANK: Pg^T, P1^T ;  DENSE: the remainder's W1^T likewise
 //   Q1t [n_up*mp, rp] LOWRANK: Q1^T (SwiGLU: Qg^T / Q1^T interleaved in 32-row blocks)
@@ -25,6 +27,9 @@ struct Layout {
   int kp, rp, mp;
   int k4;     // K of the last product
   int n1;     // rows of B1t
+  int tiled;  // bf16: tiled layout
+  int dk;     // row length of B1t (d_model, padded to 64 when tiled)
+  int dn;     // rows of B4t (d_model, padded to 32 when tiled)
   size_t off_b1, off_q1, off_p2, off_b4;
   // INT4 remainder (decode layout, see int4.hip)
   int jp16, jp128, kp128, groups;
@@ -47,11 +52,14 @@ inline Layout make_layout(const ffsplit_desc_t& d) {
   L.k4 = L.kp + (lr ? L.rp : 0) + (dn ? L.mp : 0);
   L.n1 = L.n_up * L.k4;
   size_t off = 0;
+  L.tiled = d.dtype == FFSPLIT_BF16;
+  L.dk = L.tiled ? round_up(d.d_model, 64) : d.d_model;
+  L.dn = L.tiled ? round_up(d.d_model, 32) : d.d_model;
   if (!i4) {
-    L.off_b1 = off; off = align256(off + (size_t)L.n1 * d.d_model * L.esz);
+    L.off_b1 = off; off = align256(off + (size_t)L.n1 * L.dk * L.esz);
     L.off_q1 = off; if (lr) off = align256(off + (size_t)L.n_up * L.mp * L.rp * L.esz);
     L.off_p2 = off; if (lr) off = align256(off + (size_t)L.rp * L.mp * L.esz);
-    L.off_b4 = off; off = align256(off + (size_t)d.d_model * L.k4 * L.esz);
+    L.off_b4 = off; off = align256(off + (size_t)L.dn * L.k4 * L.esz);
   } else {
     L.groups = d.d_model / 128;
     L.jp16 = round_up(m, 16);
@@ -74,7 +82,7 @@ inline Layout make_layout(const ffsplit_desc_t& d) {
 }
 
 struct ScoreWs {
-  int n_gemm, n_out, tiles_m;
+  int n_gemm, n_out, tiles_m, dk;
   size_t off_wt, wt_bytes, off_p2, off_p1, total_bytes;
 };
 
@@ -87,7 +95,8 @@ inline ScoreWs make_score_ws(const ffsplit_desc_t& d, int64_t T) {
   w.n_gemm = n_up * w.n_out;
   w.tiles_m = (int)((T + tile_m - 1) / tile_m);
   w.off_wt = 0;
-  w.wt_bytes = align256((size_t)w.n_gemm * d.d_model * esz);
+  w.dk = d.dtype == FFSPLIT_BF16 ? round_up(d.d_model, 64) : d.d_model;
+  w.wt_bytes = align256((size_t)w.n_gemm * w.dk * esz);
   w.off_p2 = w.wt_bytes;
   const size_t pb = align256((size_t)(w.tiles_m > 0 ? w.tiles_m : 1) * w.n_out * 4);
   w.off_p1 = w.off_p2 + pb;
@@ -96,7 +105,9 @@ inline ScoreWs make_score_ws(const ffsplit_desc_t& d, int64_t T) {
 }
 
 struct FwdWs {
-  size_t off_cat, off_t, off_h2;
+  size_t off_cat, off_t, off_h2, off_kpart;
+  int t_pad;       // rows of the intermediates (T, padded to 32 when tiled)
+  int g3_split;    // split-K factor of the h2 * P2 product
   // INT4 decode scratch
   size_t off_h, off_part;
   int n_split;
@@ -107,4 +118,4 @@ inline size_t build_ws_bytes(const ffsplit_desc_t& d) { return align256((size_t)
 
 FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T);
 
-}  // namespace ffs
+}  // namespace ffsplit

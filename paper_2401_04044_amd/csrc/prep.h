@@ -3,7 +3,7 @@
 #pragma once
 #include "common.h"
 
-namespace ffs {
+namespace ffsplit {
 
 // dst[f(n)][coff + c] = src[cmap(c)][nmap(n)] for n < n_count, c < c_count, where
 // f(n) = row_off + n                         (glu_mode 0)
@@ -22,6 +22,7 @@ struct PermArgs {
   int coff;
   int64_t row_off;
   int glu_mode;
+  int dst_tiled;   // dst in the 32x16-block tiled layout of gemm_bf16.hip, ldd = padded K
 };
 
 int launch_fill_zero(void* p, size_t bytes, hipStream_t st);
@@ -36,4 +37,4 @@ size_t select_workspace_bytes(int d_ff);
 int launch_select(const float* scores, int d_ff, int k, int32_t* idx, int32_t* perm, int32_t* nan_flag,
                   void* ws, hipStream_t st);
 
-}  // namespace ffs
+}  // namespace ffsplit

@@ -3,7 +3,7 @@
 // the score partials and the W2 row-norm / score finalisation of Eq. 3.
 #include "prep.h"
 
-namespace ffs {
+namespace ffsplit {
 
 __global__ void fill_zero_kernel(uint4* p, size_t n16) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -48,7 +48,12 @@ __global__ void permute_transpose_kernel(const PermArgs a) {
       int64_t drow;
       if (a.glu_mode == 0) drow = a.row_off + nq;
       else drow = a.row_off + (int64_t)(nq >> 5) * 64 + (nq & 31) + (a.glu_mode == 2 ? 32 : 0);
-      dst[drow * a.ldd + a.coff + c] = tile[tx][nn];
+      const int64_t dcol = a.coff + c;
+      if (a.dst_tiled)
+        dst[((drow >> 5) * (a.ldd >> 4) + (dcol >> 4)) * 512 + ((dcol >> 3) & 1) * 256 + (drow & 31) * 8 + (dcol & 7)] =
+            tile[tx][nn];
+      else
+        dst[drow * a.ldd + dcol] = tile[tx][nn];
     }
   }
 }
@@ -133,4 +138,4 @@ int launch_finalize_scores(const void* W2, int bf16, int d_model, int d_ff, cons
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-}  // namespace ffs
+}  // namespace ffsplit

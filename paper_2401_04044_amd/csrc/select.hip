@@ -5,7 +5,7 @@
 // by counting, which yields the order (score descending, index ascending).
 #include "prep.h"
 
-namespace ffs {
+namespace ffsplit {
 
 __device__ __forceinline__ uint32_t score_key(float s, int* saw_nan) {
   uint32_t b = __float_as_uint(s);
@@ -120,4 +120,4 @@ int launch_select(const float* scores, int d_ff, int k, int32_t* idx, int32_t* p
   return 0;
 }
 
-}  // namespace ffs
+}  // namespace ffsplit

@@ -124,6 +124,9 @@ FWD_CASES = [
     ("c3_reduced_swiglu_f32", f32_variant(reduced(C3, 64, 200, rank=16)), 70),
     ("c5_reduced", reduced(C5, 128, 520, rank=40), 65),
     ("single_token", reduced(C3, 128, 300, rank=32), 1),
+    # more than 1024 rows: 256-row tiles, split-K of the long reduction, dual-operand SwiGLU
+    ("c2_reduced_tall", reduced(C2, 256, 2100, rank=128), 1300),
+    ("c3_reduced_tall", reduced(C3, 192, 1500, rank=64), 1059),
 ]
 
 
