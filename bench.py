@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--no-decode", action="store_true", help="skip the int4 decode section")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--copies", type=int, default=4, help="split copies rotated through in the prefill loop")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference dispatch for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -73,6 +76,15 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         return e0.elapsed_time(e1) * 1e-3 / n, wall / n
+
+    if args.calib_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        note("reference copy done: 3 x 256 MiB read + 256 MiB written")
 
     # ------------------------------------------------------------ headline: C2 prefill
     cfg = C2
