@@ -22,6 +22,7 @@
 // Heavy bf16 weights use the same block order with 4 KiB blocks (one 16-byte
 // MFMA operand per lane and 32-element step).
 #include "int4.h"
+#include <cstdlib>
 
 namespace ffsplit {
 
@@ -287,284 +288,424 @@ int launch_int4_export(const ffsplit_desc_t& d, const Layout& L, const char* spl
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// ---------------------------------------------------------------- decode, phase 1
-// h[t, j] = act(x_t . up_j [, x_t . gate_j]) for every heavy and remainder neuron.
-// A workgroup of 8 wavefronts walks over neuron tiles; wavefront w owns the
-// quantisation groups w*GPW .. w*GPW+GPW-1 of the reduction and keeps the tokens'
-// activations for them in registers for the whole kernel; the 8 partial 16x16
-// results are added in a fixed order through LDS.
+// ---------------------------------------------------------------- decode
+// Up to 16 tokens per pass, HBM-bound: every weight byte is read once with 16-byte loads
+// that are contiguous across the wavefront, dequantised in registers and fed to
+// v_mfma_f32_16x16x32_bf16 with the tokens as the other operand.  Both kernels request
+// their weights before anything else so that one memory latency covers the whole
+// workgroup's share.
+//
+// phase 1   h[t, j] = act(x_t . up_j [, x_t . gate_j]) for every neuron (bf16).
+//           A workgroup of 8 wavefronts owns one heavy tile of 16 neurons or TPW int4
+//           tiles; wavefront w owns the quantisation groups w*GPW.. of the reduction and
+//           keeps the tokens' activations for them in registers; the 8 partial 16x16
+//           results are added in a fixed order through LDS.
+// phase 2   y[t, c] = sum_j h[t, j] * down[j, c].  Workgroup (cg, s) owns the 128 outputs
+//           of column group cg and every S-th block of 128 neurons; wavefront w owns the
+//           16 outputs cg*128 + 16 w.  The scaled activations (MFMA operands) of the
+//           workgroup's neuron blocks are prepared once into LDS.  Partial sums are
+//           written with device-scope stores; the last of the S workgroups of a column
+//           group to arrive (integer arrival counter) adds them in a fixed order and
+//           writes Y: no floating-point atomics, results independent of arrival order.
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+union VFrag {
+  u32x4_t u;
+  bf16x8_t v;
+  uint32_t w[4];
+};
+
+__device__ __forceinline__ VFrag dequant8v(uint32_t w) {
+  VFrag f;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) f.w[p] = ((w >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
+  return f;
+}
+
+// partial sums cross workgroups of one launch: device-scope accesses go to the point where
+// the per-XCD L2 caches are coherent, so no cache write-back or invalidate is needed
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 struct Phase1Args {
-  const bf16_t* X;      // [T, d]
+  const bf16_t* X;        // [T, d]
   int T, d, G;
-  int n_up;             // 1: GeLU(up)   2: silu(gate) * up
-  const uint4* hv_up;   // heavy blocks
-  const uint4* hv_gate;
+  int n_up;               // 1: GeLU(up)   2: silu(gate) * up
+  const u32x4_t* hv_up;   // heavy bf16 blocks [tile][group][4 steps][64 lanes]
+  const u32x4_t* hv_gate;
   int n_htiles;
-  const uint4* q_up;    // int4 blocks
-  const uint4* q_gate;
-  const uint16_t* s_up;
+  const u32x4_t* q_up;    // int4 blocks [tile][group][64 lanes]
+  const u32x4_t* q_gate;
+  const uint16_t* s_up;   // [tile][group][16] fp16
   const uint16_t* s_gate;
-  int n_qtiles;
-  float* h;             // [16, hl] fp32
-  int hl, h_off_q;      // remainder neurons start at column h_off_q
+  int n_qtiles, tpw;      // int4 tiles per workgroup
+  bf16_t* h;              // [16, hl] bf16; heavy neurons at column 0, remainder at h_off_q
+  int hl, h_off_q;
 };
+
 
 template <int GPW>
 __global__ void __launch_bounds__(512) int4_phase1_kernel(const Phase1Args p) {
-  __shared__ float red[2][8][2][256];
+  constexpr int P1_MAXT = GPW >= 4 ? 1 : 2;   // int4 tiles in flight per workgroup (register budget)
+  __shared__ float red[P1_MAXT][8][2][256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
+  const int wg = blockIdx.x;
+  const bool heavy = wg < p.n_htiles;
 
-  Frag xr[GPW][4];
+  // ---- weights first.  One register array serves both roles: an int4 workgroup holds
+  // P1_MAXT tiles (gate and up codes of GPW groups each), a heavy workgroup holds the bf16
+  // operands of half of its groups at a time (HG groups x 4 steps x (up, gate)).
+  constexpr int HG = GPW >= 4 ? GPW / 4 : 1;
+  constexpr int NR = (P1_MAXT * GPW * 2 > HG * 8) ? P1_MAXT * GPW * 2 : HG * 8;
+  u32x4_t R[NR];
+  u32x2_t su[P1_MAXT][GPW], sg[P1_MAXT][GPW];
+  const int qt0 = (wg - p.n_htiles) * p.tpw;
+  const int qt_end = min(p.n_qtiles, qt0 + p.tpw);
+  auto load_q = [&](int t, int qt) {
+#pragma unroll
+    for (int i = 0; i < GPW; ++i) {
+      const int g = wave * GPW + i;
+      if (g >= p.G) continue;
+      const int64_t blk = (int64_t)qt * p.G + g;
+      R[(t * GPW + i) * 2] = p.q_up[blk * 64 + lane];
+      su[t][i] = *(const u32x2_t*)(p.s_up + blk * 16 + 4 * q);
+      if (p.n_up == 2) {
+        R[(t * GPW + i) * 2 + 1] = p.q_gate[blk * 64 + lane];
+        sg[t][i] = *(const u32x2_t*)(p.s_gate + blk * 16 + 4 * q);
+      }
+    }
+  };
+  auto load_h = [&](int half) {
+#pragma unroll
+    for (int ii = 0; ii < HG; ++ii) {
+      const int i = half * HG + ii;
+      const int g = wave * GPW + i;
+      if (i >= GPW || g >= p.G) continue;
+      const int64_t base = (((int64_t)wg * p.G + g) * 4) * 64 + lane;
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        R[(ii * 4 + st) * 2] = p.hv_up[base + st * 64];
+        if (p.n_up == 2) R[(ii * 4 + st) * 2 + 1] = p.hv_gate[base + st * 64];
+      }
+    }
+  };
+  if (heavy) {
+    load_h(0);
+  } else {
+#pragma unroll
+    for (int t = 0; t < P1_MAXT; ++t)
+      if (qt0 + t < qt_end) load_q(t, qt0 + t);
+  }
+
+  // ---- tokens' activations for this wavefront's quantisation groups, as MFMA operands
+  VFrag xr[GPW][4];
   float xsum[GPW];
 #pragma unroll
   for (int i = 0; i < GPW; ++i) {
     const int g = wave * GPW + i;
-    float s = 0.f;
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (g < p.G && n < p.T) v = *(const uint4*)(p.X + (int64_t)n * p.d + g * 128 + 32 * st + 8 * q);
+      u32x4_t v = {0, 0, 0, 0};
+      if (g < p.G && n < p.T) v = *(const u32x4_t*)(p.X + (int64_t)n * p.d + g * 128 + 32 * st + 8 * q);
       xr[i][st].u = v;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < GPW; ++i) {
+    float s = 0.f;
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         s += __uint_as_float(xr[i][st].w[e] << 16);
         s += __uint_as_float(xr[i][st].w[e] & 0xffff0000u);
       }
-    }
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
     xsum[i] = s;
   }
 
-  const int n_tiles = p.n_htiles + p.n_qtiles;
-  int par = 0;
-  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x, par ^= 1) {
-    f32x4_t au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
-    int hcol;
-    if (tile < p.n_htiles) {
-      hcol = tile * 16;
-#pragma unroll
-      for (int i = 0; i < GPW; ++i) {
-        const int g = wave * GPW + i;
-        if (g >= p.G) continue;
-        const int64_t base = (((int64_t)tile * p.G + g) * 4) * 64 + lane;
-        Frag wu[4], wg[4];
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          wu[st].u = p.hv_up[base + st * 64];
-          if (p.n_up == 2) wg[st].u = p.hv_gate[base + st * 64];
-        }
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wu[st].v, xr[i][st].v, au, 0, 0, 0);
-          if (p.n_up == 2) ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wg[st].v, xr[i][st].v, ag, 0, 0, 0);
-        }
-      }
-    } else {
-      const int qt = tile - p.n_htiles;
-      hcol = p.h_off_q + qt * 16;
-      uint4 wu[GPW], wg[GPW];
-      uint2 su[GPW], sg[GPW];
-#pragma unroll
-      for (int i = 0; i < GPW; ++i) {
-        const int g = wave * GPW + i;
-        if (g >= p.G) continue;
-        const int64_t blk = (int64_t)qt * p.G + g;
-        wu[i] = p.q_up[blk * 64 + lane];
-        su[i] = *(const uint2*)(p.s_up + blk * 16 + 4 * q);
-        if (p.n_up == 2) {
-          wg[i] = p.q_gate[blk * 64 + lane];
-          sg[i] = *(const uint2*)(p.s_gate + blk * 16 + 4 * q);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < GPW; ++i) {
-        const int g = wave * GPW + i;
-        if (g >= p.G) continue;
-        const float corr = 136.f * xsum[i];
-        {
-          f32x4_t raw = {0.f, 0.f, 0.f, 0.f};
-          const uint32_t w4[4] = {wu[i].x, wu[i].y, wu[i].z, wu[i].w};
-#pragma unroll
-          for (int st = 0; st < 4; ++st)
-            raw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8(w4[st]).v, xr[i][st].v, raw, 0, 0, 0);
-          const uint16_t sb[4] = {(uint16_t)(su[i].x & 0xffff), (uint16_t)(su[i].x >> 16),
-                                  (uint16_t)(su[i].y & 0xffff), (uint16_t)(su[i].y >> 16)};
-#pragma unroll
-          for (int r = 0; r < 4; ++r) au[r] = fmaf(half_bits_to_f32(sb[r]), raw[r] - corr, au[r]);
-        }
-        if (p.n_up == 2) {
-          f32x4_t raw = {0.f, 0.f, 0.f, 0.f};
-          const uint32_t w4[4] = {wg[i].x, wg[i].y, wg[i].z, wg[i].w};
-#pragma unroll
-          for (int st = 0; st < 4; ++st)
-            raw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8(w4[st]).v, xr[i][st].v, raw, 0, 0, 0);
-          const uint16_t sb[4] = {(uint16_t)(sg[i].x & 0xffff), (uint16_t)(sg[i].x >> 16),
-                                  (uint16_t)(sg[i].y & 0xffff), (uint16_t)(sg[i].y >> 16)};
-#pragma unroll
-          for (int r = 0; r < 4; ++r) ag[r] = fmaf(half_bits_to_f32(sb[r]), raw[r] - corr, ag[r]);
-        }
-      }
-    }
-    // lane holds neurons 4 q + r (r = 0..3) of the tile for token n
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      red[par][wave][0][lane * 4 + r] = au[r];
-      red[par][wave][1][lane * 4 + r] = ag[r];
-    }
+  // cross-wave sum of `nt` tiles' partials, activation, store of h (bf16 pairs)
+  auto finish = [&](int nt, int col0, int col_step) {
     __syncthreads();
-    if (tid < 256) {
-      float u = 0.f, g = 0.f;
+    const int t = tid >> 7, pair = tid & 127;
+    if (t < nt) {
+      float u0 = 0.f, g0 = 0.f, u1 = 0.f, g1 = 0.f;
 #pragma unroll
       for (int w = 0; w < 8; ++w) {
-        u += red[par][w][0][tid];
-        g += red[par][w][1][tid];
+        u0 += red[t][w][0][2 * pair]; g0 += red[t][w][1][2 * pair];
+        u1 += red[t][w][0][2 * pair + 1]; g1 += red[t][w][1][2 * pair + 1];
       }
-      const int l = tid >> 2, r = tid & 3;
+      const int l = pair >> 1, r = (pair & 1) * 2;
       const int tok = l & 15, neuron = 4 * (l >> 4) + r;
-      const float hv = p.n_up == 2 ? silu_f(g) * u : gelu_f(u);
-      if (tok < p.T) p.h[(int64_t)tok * p.hl + hcol + neuron] = hv;
+      const float h0 = p.n_up == 2 ? silu_f(g0) * u0 : gelu_f(u0);
+      const float h1 = p.n_up == 2 ? silu_f(g1) * u1 : gelu_f(u1);
+      if (tok < p.T)
+        *(uint32_t*)(p.h + (int64_t)tok * p.hl + col0 + t * col_step + neuron) = pack_bf16x2(h0, h1);
     }
+  };
+
+  if (heavy) {
+    f32x4_t au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int half = 0; half * HG < GPW; ++half) {
+#pragma unroll
+      for (int ii = 0; ii < HG; ++ii) {
+        const int i = half * HG + ii;
+        if (i >= GPW || wave * GPW + i >= p.G) continue;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          VFrag a, b;
+          a.u = R[(ii * 4 + st) * 2];
+          au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xr[i][st].v, au, 0, 0, 0);
+          if (p.n_up == 2) {
+            b.u = R[(ii * 4 + st) * 2 + 1];
+            ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.v, xr[i][st].v, ag, 0, 0, 0);
+          }
+        }
+      }
+      if ((half + 1) * HG < GPW) load_h(half + 1);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      red[0][wave][0][lane * 4 + r] = au[r];
+      red[0][wave][1][lane * 4 + r] = ag[r];
+    }
+    finish(1, wg * 16, 0);
+    return;
+  }
+
+  for (int qb = qt0; qb < qt_end; qb += P1_MAXT) {
+    const int nt = min(P1_MAXT, qt_end - qb);
+#pragma unroll
+    for (int t = 0; t < P1_MAXT; ++t) {
+      f32x4_t au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
+      if (t < nt) {
+#pragma unroll
+        for (int i = 0; i < GPW; ++i) {
+          if (wave * GPW + i >= p.G) continue;
+          const float corr = 136.f * xsum[i];
+          {
+            f32x4_t raw = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+              raw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(R[(t * GPW + i) * 2][st]).v, xr[i][st].v, raw, 0, 0, 0);
+            const uint32_t sb[4] = {su[t][i][0] & 0xffffu, su[t][i][0] >> 16, su[t][i][1] & 0xffffu, su[t][i][1] >> 16};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) au[r] = fmaf(half_bits_to_f32((uint16_t)sb[r]), raw[r] - corr, au[r]);
+          }
+          if (p.n_up == 2) {
+            f32x4_t raw = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+              raw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(R[(t * GPW + i) * 2 + 1][st]).v, xr[i][st].v, raw, 0, 0, 0);
+            const uint32_t sb[4] = {sg[t][i][0] & 0xffffu, sg[t][i][0] >> 16, sg[t][i][1] & 0xffffu, sg[t][i][1] >> 16};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ag[r] = fmaf(half_bits_to_f32((uint16_t)sb[r]), raw[r] - corr, ag[r]);
+          }
+          __builtin_amdgcn_sched_barrier(0);   // one group at a time: keeps the dequantised operands few
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        red[t][wave][0][lane * 4 + r] = au[r];
+        red[t][wave][1][lane * 4 + r] = ag[r];
+      }
+    }
+    // the next batch's weights are requested before this batch is reduced
+    const int qn = qb + P1_MAXT;
+#pragma unroll
+    for (int t = 0; t < P1_MAXT; ++t)
+      if (qn + t < qt_end) load_q(t, qn + t);
+    finish(nt, p.h_off_q + qb * 16, 16);
+    if (qn < qt_end) __syncthreads();   // red is reused
   }
 }
 
-// ---------------------------------------------------------------- decode, phase 2
-// y[t, c] = sum_j h[t, j] * down[j, c].  Workgroup (cg, split) owns 128 outputs c
-// and a range of 128-neuron blocks; its 4 wavefronts take blocks round-robin and
-// are added in a fixed order; per-split partial sums go to `part`.
-
 struct Phase2Args {
-  const float* h;        // [16, hl]
-  int T, d, hl;
-  int heavy;             // 1: bf16 heavy blocks, 0: int4 blocks
-  const uint4* w;        // blocks
-  const uint16_t* sc;    // int4: [cg][jp128] fp16
-  int JB, jp128;         // neuron blocks of 128; scale row length
-  int h_off;             // first h column of this part
-  int n_split;
-  float* part;           // [n_split, 16, d] fp32 (this part's slice)
+  const bf16_t* h;         // [16, hl]
+  int T, d, hl, h_off_q, S;
+  const u32x4_t* hv_down;  // [cg][JBh][8 ct][4 steps][64]
+  int JBh;
+  const u32x4_t* q_down;   // [cg][JBr][8 ct][64]
+  const uint16_t* s_down;  // [cg][jp128] fp16
+  int JBr, jp128;
+  float* part;             // [G][S][2][16][128] fp32 (heavy, remainder)
+  unsigned* counters;      // [G] arrivals, zero on entry
+  bf16_t* Y;
+  bf16_t* Yh;
+  bf16_t* Yr;
 };
 
-__global__ void __launch_bounds__(256) int4_phase2_kernel(const Phase2Args p) {
-  __shared__ float red[4][8][256];
+constexpr int P2_MAXJ = 8;   // int4 neuron blocks per workgroup and pass
+constexpr int P2_MAXH = 4;   // heavy 32-neuron steps per workgroup and pass
+constexpr int P2_STEPS = P2_MAXJ * 4 + P2_MAXH;
+
+__global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
+  __shared__ u32x4_t hop[P2_STEPS][64];
+  __shared__ float hsum_s[8][16];
+  __shared__ int flag_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
   const int cg = blockIdx.x, sp = blockIdx.y;
-  const int per = (p.JB + p.n_split - 1) / p.n_split;
-  const int jb0 = sp * per, jb1 = min(p.JB, jb0 + per);
 
-  f32x4_t acc[8];
+  const int NJ = p.JBr > sp ? (p.JBr - sp + p.S - 1) / p.S : 0;           // int4 blocks sp, sp+S, ...
+  const int NHq = p.JBh * 4 > sp ? (p.JBh * 4 - sp + p.S - 1) / p.S : 0;  // heavy steps sp, sp+S, ...
+  u32x4_t w2[P2_MAXJ], wh[P2_MAXH];
+  auto load_down = [&](int pass) {
 #pragma unroll
-  for (int ct = 0; ct < 8; ++ct) acc[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float hsum = 0.f;
-
-  for (int jb = jb0 + wave; jb < jb1; jb += 4) {
-    // activations of this block's 128 neurons for token n, scaled per neuron (int4)
-    Frag hb[4];
+    for (int i = 0; i < P2_MAXJ; ++i) {
+      const int ii = pass * P2_MAXJ + i;
+      if (ii < NJ) w2[i] = p.q_down[(((int64_t)cg * p.JBr + sp + ii * p.S) * 8 + wave) * 64 + lane];
+    }
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      const int j = jb * 128 + 32 * st + 8 * q;
-      float hv[8];
-      if (n < p.T) {
-        const float4 a = *(const float4*)(p.h + (int64_t)n * p.hl + p.h_off + j);
-        const float4 b = *(const float4*)(p.h + (int64_t)n * p.hl + p.h_off + j + 4);
-        hv[0] = a.x; hv[1] = a.y; hv[2] = a.z; hv[3] = a.w; hv[4] = b.x; hv[5] = b.y; hv[6] = b.z; hv[7] = b.w;
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) hv[e] = 0.f;
+    for (int i = 0; i < P2_MAXH; ++i) {
+      const int ii = pass * P2_MAXH + i;
+      if (ii < NHq) {
+        const int hq = sp + ii * p.S;
+        wh[i] = p.hv_down[((((int64_t)cg * p.JBh + (hq >> 2)) * 8 + wave) * 4 + (hq & 3)) * 64 + lane];
       }
-      if (!p.heavy) {
-        const uint4 sv = *(const uint4*)(p.sc + (int64_t)cg * p.jp128 + j);
-        const uint32_t s4[4] = {sv.x, sv.y, sv.z, sv.w};
+    }
+  };
+  load_down(0);
+
+  f32x4_t acc_r = {0.f, 0.f, 0.f, 0.f}, acc_h = {0.f, 0.f, 0.f, 0.f};
+  float hsum = 0.f;
+  const int n_pass_j = (NJ + P2_MAXJ - 1) / P2_MAXJ, n_pass_h = (NHq + P2_MAXH - 1) / P2_MAXH;
+  const int n_pass = n_pass_j > n_pass_h ? n_pass_j : n_pass_h;
+  for (int pass = 0; pass < n_pass; ++pass) {
+    if (pass > 0) {
+      __syncthreads();   // hop is reused
+      load_down(pass);
+    }
+    const int nj = max(0, min(P2_MAXJ, NJ - pass * P2_MAXJ));
+    const int nh = max(0, min(P2_MAXH, NHq - pass * P2_MAXH));
+    const int n_steps = nj * 4 + nh;
+    // operands: step sigma < 4 nj is (int4 block sigma / 4, 32-neuron step sigma % 4), the rest heavy
+    for (int sgm = wave; sgm < n_steps; sgm += 8) {
+      int j0, hv;
+      if (sgm < nj * 4) {
+        const int jb = sp + (pass * P2_MAXJ + (sgm >> 2)) * p.S;
+        j0 = jb * 128 + 32 * (sgm & 3) + 8 * q;
+        hv = 0;
+      } else {
+        const int hq = sp + (pass * P2_MAXH + (sgm - nj * 4)) * p.S;
+        j0 = (hq >> 2) * 128 + 32 * (hq & 3) + 8 * q;
+        hv = 1;
+      }
+      VFrag f;
+      f.u = u32x4_t{0, 0, 0, 0};
+      if (n < p.T) f.u = *(const u32x4_t*)(p.h + (int64_t)n * p.hl + (hv ? 0 : p.h_off_q) + j0);
+      if (!hv) {
+        // the down row of a neuron is quantised in groups along the outputs: its scale for this
+        // column group multiplies the neuron's activation
+        const u32x4_t sv = *(const u32x4_t*)(p.s_down + (int64_t)cg * p.jp128 + j0);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          hv[2 * e] *= half_bits_to_f32((uint16_t)(s4[e] & 0xffff));
-          hv[2 * e + 1] *= half_bits_to_f32((uint16_t)(s4[e] >> 16));
+          const float lo = __uint_as_float(f.w[e] << 16) * half_bits_to_f32((uint16_t)(sv[e] & 0xffffu));
+          const float hi = __uint_as_float(f.w[e] & 0xffff0000u) * half_bits_to_f32((uint16_t)(sv[e] >> 16));
+          f.w[e] = pack_bf16x2(lo, hi);
+          hsum += __uint_as_float(f.w[e] << 16) + __uint_as_float(f.w[e] & 0xffff0000u);
         }
       }
+      hop[sgm][lane] = f.u;
+    }
+    __syncthreads();
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        hb[st].w[e] = pack_bf16x2(hv[2 * e], hv[2 * e + 1]);
-        hsum += __uint_as_float(hb[st].w[e] << 16) + __uint_as_float(hb[st].w[e] & 0xffff0000u);
+    for (int i = 0; i < P2_MAXJ; ++i) {
+      if (i < nj) {
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          VFrag b;
+          b.u = hop[i * 4 + st][lane];
+          acc_r = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(w2[i][st]).v, b.v, acc_r, 0, 0, 0);
+        }
       }
     }
-    if (p.heavy) {
-      const int64_t base = ((((int64_t)cg * p.JB + jb) * 8) * 4) * 64 + lane;
 #pragma unroll
-      for (int ct = 0; ct < 8; ++ct) {
-        Frag w[4];
-#pragma unroll
-        for (int st = 0; st < 4; ++st) w[st].u = p.w[base + (ct * 4 + st) * 64];
-#pragma unroll
-        for (int st = 0; st < 4; ++st)
-          acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[st].v, hb[st].v, acc[ct], 0, 0, 0);
-      }
-    } else {
-      const int64_t base = (((int64_t)cg * p.JB + jb) * 8) * 64 + lane;
-      uint4 w[8];
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) w[ct] = p.w[base + ct * 64];
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) {
-        const uint32_t w4[4] = {w[ct].x, w[ct].y, w[ct].z, w[ct].w};
-#pragma unroll
-        for (int st = 0; st < 4; ++st)
-          acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8(w4[st]).v, hb[st].v, acc[ct], 0, 0, 0);
+    for (int i = 0; i < P2_MAXH; ++i) {
+      if (i < nh) {
+        VFrag a, b;
+        a.u = wh[i];
+        b.u = hop[nj * 4 + i][lane];
+        acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc_h, 0, 0, 0);
       }
     }
   }
-  if (!p.heavy) {
-    hsum += __shfl_xor(hsum, 16);
-    hsum += __shfl_xor(hsum, 32);
-    const float corr = 136.f * hsum;
-#pragma unroll
-    for (int ct = 0; ct < 8; ++ct)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[ct][r] -= corr;
-  }
-#pragma unroll
-  for (int ct = 0; ct < 8; ++ct)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) red[wave][ct][lane * 4 + r] = acc[ct][r];
+  // the constant 136 of the offset-binary codes: subtract 136 * (sum of this workgroup's scaled activations)
+  hsum += __shfl_xor(hsum, 16);
+  hsum += __shfl_xor(hsum, 32);
+  if (q == 0) hsum_s[wave][n] = hsum;
   __syncthreads();
-  // 8 tiles x 256 values; thread handles value `tid` of every tile
+  {
+    float tot = 0.f;
 #pragma unroll
-  for (int ct = 0; ct < 8; ++ct) {
-    const float v = ((red[0][ct][tid] + red[1][ct][tid]) + red[2][ct][tid]) + red[3][ct][tid];
-    const int l = tid >> 2, r = tid & 3;
-    const int tok = l & 15, c = cg * 128 + ct * 16 + 4 * (l >> 4) + r;
-    if (tok < p.T) p.part[((int64_t)sp * 16 + tok) * p.d + c] = v;
+    for (int w = 0; w < 8; ++w) tot += hsum_s[w][n];
+    const float corr = 136.f * tot;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc_r[r] -= corr;
+  }
+  // lane holds outputs c = 16 wave + 4 q + r of token n
+  float* pw = p.part + ((int64_t)(cg * p.S + sp) * 2) * 16 * 128;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    st_dev(&pw[n * 128 + wave * 16 + 4 * q + r], acc_h[r]);
+    st_dev(&pw[16 * 128 + n * 128 + wave * 16 + 4 * q + r], acc_r[r]);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's device-scope stores are done
+  __syncthreads();
+  if (tid == 0) flag_s = atomicAdd(&p.counters[cg], 1u) == (unsigned)(p.S - 1);
+  __syncthreads();
+  if (!flag_s) return;
+  for (int o = tid; o < 16 * 128; o += 512) {
+    const int tok = o >> 7, c = o & 127;
+    if (tok >= p.T) continue;
+    // all loads first (independent), then the fixed-order sum
+    float va[16], vb[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      va[s] = 0.f; vb[s] = 0.f;
+      if (s < p.S) {
+        const float* ps = p.part + ((int64_t)(cg * p.S + s) * 2) * 16 * 128;
+        va[s] = ld_dev(ps + o);
+        vb[s] = ld_dev(ps + 16 * 128 + o);
+      }
+    }
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) { a += va[s]; b += vb[s]; }
+    const int64_t oi = (int64_t)tok * p.d + cg * 128 + c;
+    p.Y[oi] = f32_to_bf16(a + b);
+    if (p.Yh) p.Yh[oi] = f32_to_bf16(a);
+    if (p.Yr) p.Yr[oi] = f32_to_bf16(b);
   }
 }
 
-// Y = bf16(sum of heavy partials + sum of remainder partials), fixed order
-__global__ void int4_final_kernel(const float* part_h, int nh, const float* part_r, int nr, int T, int d,
-                                  bf16_t* Y, bf16_t* Yh, bf16_t* Yr) {
-  const int id = blockIdx.x * blockDim.x + threadIdx.x;
-  if (id >= T * d) return;
-  const int t = id / d, c = id % d;
-  float a = 0.f, b = 0.f;
-  for (int s = 0; s < nh; ++s) a += part_h[((int64_t)s * 16 + t) * d + c];
-  for (int s = 0; s < nr; ++s) b += part_r[((int64_t)s * 16 + t) * d + c];
-  Y[id] = f32_to_bf16(a + b);
-  if (Yh) Yh[id] = f32_to_bf16(a);
-  if (Yr) Yr[id] = f32_to_bf16(b);
+static int phase2_splits(int G) {
+  int S = 256 / (G > 0 ? G : 1);   // about one 8-wave workgroup per CU
+  if (S > 16) S = 16;
+  if (S < 1) S = 1;
+  return S;
 }
 
 FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   FwdWs w = {};
-  const int m = d.d_ff - d.k;
   if (d.rem_kind == FFSPLIT_REM_INT4) {
     const int hl = L.kp128 + L.jp128;
-    w.off_h = 0;
-    size_t off = align256((size_t)16 * (hl > 0 ? hl : 1) * 4);
-    const int JBh = L.kp128 / 128, JBr = m > 0 ? L.jp128 / 128 : 0;
-    const int sh = (JBh + 1) / 2, sr = (JBr + 7) / 8;
-    w.n_split = sh + sr;
-    w.off_part = off;
-    off += align256((size_t)(w.n_split > 0 ? w.n_split : 1) * 16 * d.d_model * 4);
+    const int S = phase2_splits(L.groups);
+    size_t off = 0;
+    // h and the arrival counters are adjacent: one fill zeroes both
+    w.off_h = off; off = align256(off + (size_t)16 * (hl > 0 ? hl : 1) * 2);
+    w.off_cnt = off; off = align256(off + (size_t)L.groups * 4);
+    w.off_part = off; off = align256(off + (size_t)L.groups * S * 2 * 16 * 128 * 4);
+    w.n_split = S;
     w.total_bytes = off;
     return w;
   }
@@ -581,6 +722,7 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     int sp = 512 / (tiles > 0 ? tiles : 1);
     const int max_sp = L.mp / 256 > 0 ? L.mp / 256 : 1;   // keep >= 8 slabs of 32 per split
     if (sp > max_sp) sp = max_sp;
+    if (getenv("FFS_G3SPLIT")) sp = atoi(getenv("FFS_G3SPLIT"));
     if (sp > 16) sp = 16;
     if (sp < 1) sp = 1;
     w.g3_split = sp;
@@ -600,58 +742,56 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
                  void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st) {
   const int m = d.d_ff - d.k, dm = d.d_model, G = L.groups;
   const int hl = L.kp128 + L.jp128;
-  float* h = (float*)(ws + w.off_h);
-  float* part = (float*)(ws + w.off_part);
-  const int JBh = L.kp128 / 128, JBr = m > 0 ? L.jp128 / 128 : 0;
-  const int sh = (JBh + 1) / 2, sr = (JBr + 7) / 8;
+  const int S = w.n_split;
   const int gpw = (G + 7) / 8;
   if (gpw > 8) return -2;
+  const int n_h = L.kp / 16, n_q = m > 0 ? L.jp16 / 16 : 0;
+  // int4 tiles per workgroup: about one 8-wave workgroup per CU in total, so that the tokens'
+  // activations are fetched once per CU rather than once per tile
+  const int slots = 256 - n_h > 32 ? 256 - n_h : 32;
+  int tpw = n_q > 0 ? (n_q + slots - 1) / slots : 1;
+  if (getenv("FFS_TPW")) tpw = atoi(getenv("FFS_TPW"));
+  if (tpw < 1) tpw = 1;
+  const int grid1 = n_h + (n_q + tpw - 1) / tpw;
   for (int t0 = 0; t0 < M; t0 += 16) {
     const int T = M - t0 < 16 ? M - t0 : 16;
-    // h columns that no neuron writes (padding up to the 128-blocks) must read as zero
-    if (launch_fill_zero(h, align256((size_t)16 * hl * 4), st)) return -1;
+    // h columns no neuron writes (padding up to whole 128-blocks) must read as zero and the
+    // arrival counters start at zero: they are adjacent, one fill covers both
+    if (launch_fill_zero(ws + w.off_h, w.off_part - w.off_h, st)) return -1;
     Phase1Args a = {};
     a.X = (const bf16_t*)X + (int64_t)t0 * dm;
     a.T = T; a.d = dm; a.G = G; a.n_up = L.n_up;
-    a.hv_up = (const uint4*)(split + L.off_hv[0]);
-    a.hv_gate = (const uint4*)(split + L.off_hv[1]);
-    a.n_htiles = L.kp / 16;
-    a.q_up = (const uint4*)(split + L.off_i4[0]);
-    a.q_gate = (const uint4*)(split + L.off_i4[1]);
+    a.hv_up = (const u32x4_t*)(split + L.off_hv[0]);
+    a.hv_gate = (const u32x4_t*)(split + L.off_hv[1]);
+    a.n_htiles = n_h;
+    a.q_up = (const u32x4_t*)(split + L.off_i4[0]);
+    a.q_gate = (const u32x4_t*)(split + L.off_i4[1]);
     a.s_up = (const uint16_t*)(split + L.off_s4[0]);
     a.s_gate = (const uint16_t*)(split + L.off_s4[1]);
-    a.n_qtiles = m > 0 ? L.jp16 / 16 : 0;
-    a.h = h; a.hl = hl; a.h_off_q = L.kp128;
-    const int n_tiles = a.n_htiles + a.n_qtiles;
-    if (n_tiles > 0) {
-      const int grid = n_tiles < 512 ? n_tiles : 512;
+    a.n_qtiles = n_q; a.tpw = tpw;
+    a.h = (bf16_t*)(ws + w.off_h); a.hl = hl; a.h_off_q = L.kp128;
+    if (grid1 > 0) {
       int rc;
-      if (gpw <= 1) rc = launch_phase1<1>(a, grid, st);
-      else if (gpw <= 2) rc = launch_phase1<2>(a, grid, st);
-      else if (gpw <= 4) rc = launch_phase1<4>(a, grid, st);
-      else rc = launch_phase1<8>(a, grid, st);
+      if (gpw <= 1) rc = launch_phase1<1>(a, grid1, st);
+      else if (gpw <= 2) rc = launch_phase1<2>(a, grid1, st);
+      else if (gpw <= 4) rc = launch_phase1<4>(a, grid1, st);
+      else rc = launch_phase1<8>(a, grid1, st);
       if (rc) return rc;
     }
     Phase2Args b = {};
-    b.h = h; b.T = T; b.d = dm; b.hl = hl;
-    if (JBh > 0) {
-      b.heavy = 1; b.w = (const uint4*)(split + L.off_hv[2]); b.sc = nullptr; b.JB = JBh; b.jp128 = 0;
-      b.h_off = 0; b.n_split = sh; b.part = part;
-      hipLaunchKernelGGL(int4_phase2_kernel, dim3(G, sh), dim3(256), 0, st, b);
-      if (hipGetLastError() != hipSuccess) return -1;
-    }
-    if (JBr > 0) {
-      b.heavy = 0; b.w = (const uint4*)(split + L.off_i4[2]); b.sc = (const uint16_t*)(split + L.off_s4[2]);
-      b.JB = JBr; b.jp128 = L.jp128; b.h_off = L.kp128; b.n_split = sr;
-      b.part = part + (size_t)sh * 16 * dm;
-      hipLaunchKernelGGL(int4_phase2_kernel, dim3(G, sr), dim3(256), 0, st, b);
-      if (hipGetLastError() != hipSuccess) return -1;
-    }
-    const int n = T * dm;
-    hipLaunchKernelGGL(int4_final_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, sh,
-                       part + (size_t)sh * 16 * dm, sr, T, dm, (bf16_t*)Y + (int64_t)t0 * dm,
-                       Y_heavy ? (bf16_t*)Y_heavy + (int64_t)t0 * dm : nullptr,
-                       Y_rem ? (bf16_t*)Y_rem + (int64_t)t0 * dm : nullptr);
+    b.h = a.h; b.T = T; b.d = dm; b.hl = hl; b.h_off_q = L.kp128; b.S = S;
+    b.hv_down = (const u32x4_t*)(split + L.off_hv[2]);
+    b.JBh = L.kp128 / 128;
+    b.q_down = (const u32x4_t*)(split + L.off_i4[2]);
+    b.s_down = (const uint16_t*)(split + L.off_s4[2]);
+    b.JBr = m > 0 ? L.jp128 / 128 : 0;
+    b.jp128 = L.jp128;
+    b.part = (float*)(ws + w.off_part);
+    b.counters = (unsigned*)(ws + w.off_cnt);
+    b.Y = (bf16_t*)Y + (int64_t)t0 * dm;
+    b.Yh = Y_heavy ? (bf16_t*)Y_heavy + (int64_t)t0 * dm : nullptr;
+    b.Yr = Y_rem ? (bf16_t*)Y_rem + (int64_t)t0 * dm : nullptr;
+    hipLaunchKernelGGL(int4_phase2_kernel, dim3(G, S), dim3(512), 0, st, b);
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;

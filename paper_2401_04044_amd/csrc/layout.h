@@ -109,7 +109,7 @@ struct FwdWs {
   int t_pad;       // rows of the intermediates (T, padded to 32 when tiled)
   int g3_split;    // split-K factor of the h2 * P2 product
   // INT4 decode scratch
-  size_t off_h, off_part;
+  size_t off_h, off_part, off_cnt;
   int n_split;
   size_t total_bytes;
 };
