@@ -4,7 +4,6 @@
 #include "layout.h"
 #include "prep.h"
 #include "int4.h"
-#include <cstdlib>
 
 using namespace ffsplit;
 
@@ -32,12 +31,6 @@ int check_desc(const ffsplit_desc_t* d, bool need_split_fields) {
     if (d->group != 128 || d->d_model % 128 != 0) return FFSPLIT_E_UNSUPPORTED;
   }
   return FFSPLIT_OK;
-}
-
-// development knob (integer from the environment, else the default)
-inline int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  return v ? atoi(v) : dflt;
 }
 
 inline int act_of(const ffsplit_desc_t* d) { return d->act == FFSPLIT_ACT_SWIGLU ? ACT_GLU : ACT_GELU; }
@@ -325,7 +318,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     g.split_col = acted;
     g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
     g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
-    g.group_m = env_int("FFS_GM1", 1);   // X is the large operand: its row tiles stay within one XCD
+    g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
     FFS_TRY(run(g, act, (big_m && L.n1 >= 4096) ? 5 : 4, 1));
   }
   if (rem_lr) {
@@ -344,7 +337,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     g.Bt = sp + L.off_p2; g.ldb = L.mp;
     g.M = M; g.N = L.rp; g.K = L.mp;
     g.split_col = L.rp;
-    g.group_m = env_int("FFS_GM3", 1);   // h2 is the large operand
+    g.group_m = 1;   // h2 is the large operand
     if (bf16 && w.g3_split > 1) {
       float* part = (float*)(ws + w.off_kpart);
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;

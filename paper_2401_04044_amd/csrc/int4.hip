@@ -22,7 +22,6 @@
 // Heavy bf16 weights use the same block order with 4 KiB blocks (one 16-byte
 // MFMA operand per lane and 32-element step).
 #include "int4.h"
-#include <cstdlib>
 
 namespace ffsplit {
 
@@ -544,7 +543,7 @@ struct Phase2Args {
   bf16_t* Yr;
 };
 
-constexpr int P2_MAXJ = 8;   // int4 neuron blocks per workgroup and pass
+constexpr int P2_MAXJ = 12;  // int4 neuron blocks per workgroup and pass
 constexpr int P2_MAXH = 4;   // heavy 32-neuron steps per workgroup and pass
 constexpr int P2_STEPS = P2_MAXJ * 4 + P2_MAXH;
 
@@ -717,12 +716,12 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   w.g3_split = 1;
   w.off_kpart = off;
   if (L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
-    // split the long reduction of h2 * P2 until about two workgroups per CU exist
+    // split the long reduction of h2 * P2 until about one workgroup per CU exists (more splits
+    // cost more partial-sum traffic than they gain: measured)
     const int tiles = (int)((T + 255) / 256) * ((L.rp + 127) / 128);
-    int sp = 512 / (tiles > 0 ? tiles : 1);
+    int sp = 256 / (tiles > 0 ? tiles : 1);
     const int max_sp = L.mp / 256 > 0 ? L.mp / 256 : 1;   // keep >= 8 slabs of 32 per split
     if (sp > max_sp) sp = max_sp;
-    if (getenv("FFS_G3SPLIT")) sp = atoi(getenv("FFS_G3SPLIT"));
     if (sp > 16) sp = 16;
     if (sp < 1) sp = 1;
     w.g3_split = sp;
@@ -750,7 +749,6 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
   // activations are fetched once per CU rather than once per tile
   const int slots = 256 - n_h > 32 ? 256 - n_h : 32;
   int tpw = n_q > 0 ? (n_q + slots - 1) / slots : 1;
-  if (getenv("FFS_TPW")) tpw = atoi(getenv("FFS_TPW"));
   if (tpw < 1) tpw = 1;
   const int grid1 = n_h + (n_q + tpw - 1) / tpw;
   for (int t0 = 0; t0 < M; t0 += 16) {
