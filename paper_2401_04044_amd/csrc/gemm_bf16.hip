@@ -24,6 +24,7 @@
 // with two output destinations, fp32 split-K partials, and the neuron-norm
 // column reduction of Sec. 4.1 (Eq. 3) for the calibration pass.
 #include "common.h"
+#include <type_traits>
 
 namespace ffsplit {
 
@@ -41,16 +42,16 @@ __device__ __forceinline__ int xcd_remap(int i, int total) {
   return x * q + (x < rem ? x : rem) + (i >> 3);
 }
 
-// GeLU for the bf16 path: z * sigmoid(p(z)), p an odd quintic fitted to the exact
-// z * Phi(z); max abs error 2.8e-5 on the real line (bf16 rounding of the result
-// is ~2e-3 relative).  p is evaluated on z clamped to [-9, 9].
+// GeLU for the bf16 path with one transcendental: for a = |z|, Phi(-a) = 2^q(a) with q a cubic
+// fitted to log2 Phi(-a) (leading coefficient negative, so large a underflows to 0), and
+// z Phi(z) = max(z, 0) - a Phi(-a).  Max abs error 5.7e-5 on the real line, below the bf16
+// rounding of the result (2^-9 relative) wherever |result| > 0.03.
 __device__ __forceinline__ float gelu_fast(float z) {
-  const float zc = __builtin_amdgcn_fmed3f(z, -9.0f, 9.0f);
-  const float z2 = zc * zc;
-  float t = fmaf(z2, 0.0010238121f, -0.10683461f);   // -log2(e) * (c5, c3)
-  t = fmaf(z2, t, -2.3010564f);                      // -log2(e) * c1
-  const float e = __builtin_amdgcn_exp2f(t * zc);
-  return z * __builtin_amdgcn_rcpf(1.0f + e);
+  const float a = fabsf(z);
+  float q = fmaf(a, -0.024829373f, -0.49904245f);
+  q = fmaf(a, q, -1.1289980f);
+  q = fmaf(a, q, -1.0036056f);
+  return fmaxf(z, 0.0f) - a * __builtin_amdgcn_exp2f(q);
 }
 __device__ __forceinline__ float silu_fast(float z) {
   const float e = __builtin_amdgcn_exp2f(-1.44269504f * z);
@@ -69,6 +70,131 @@ __device__ __forceinline__ void swap32(uint32_t& a, uint32_t& b) {
   auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
   a = r[0];
   b = r[1];
+}
+
+// Epilogue shared by the GEMM kernels: activation, bf16 packing and the stores (or the
+// neuron-norm column sums).  acc[i][j] is the 32x32 tile (i, j) of the wavefront's sub-tile.
+template <int BM, int BN, int WGM, int WGN, int ACT, bool SCORE>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32], int m0,
+                                              int n0, int tm, int wm, int wn, int lane, int tid, u32x4_t* smem) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  // ---------------------------------------------------------------- epilogue
+  constexpr int JSTEP = (ACT == ACT_GLU) ? 2 : 1;
+  if (!SCORE) {
+    // lane: row = lane & 31; columns 8 g + 4 (lane >> 5) + 0..3 of each 32x32 tile
+    const int half = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int cb = n0 + wn * WN + j * 32;  // GEMM column of this 32-block
+      if (cb >= p.N) continue;
+      const bool act_here = cb < p.act_cols;
+      int oc;       // output column of the block
+      if (ACT == ACT_GLU) {
+        if (act_here) {
+          if (j & 1) continue;  // the pair is written when its gate block comes up
+          oc = cb / 2;
+        } else {
+          oc = cb - p.act_cols / 2;
+        }
+      } else {
+        oc = cb;
+      }
+      char* base;
+      int64_t ld;
+      int occ, tiled;
+      if (oc < p.split_col) { base = (char*)p.C0; ld = p.ldc0; occ = oc; tiled = p.c0_tiled; }
+      else { base = (char*)p.C1; ld = p.ldc1; occ = oc - p.split_col; tiled = p.c1_tiled; }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int rblk = (m0 + wm * WM) / 32 + i;
+        const int row = rblk * 32 + (lane & 31);
+        if (p.partial) {
+          // fp32 split-K partial, row-major [split][M][ld]
+          if (row < p.M) {
+            float* dst = (float*)base + ((int64_t)blockIdx.y * p.M + row) * ld + occ + 4 * half;
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              *(float4*)(dst + 8 * g) = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                                    acc[i][j][4 * g + 3]);
+          }
+          continue;
+        }
+        uint32_t pk[4][2];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            // (static tile indices: an activated pair is (gate j, value j + 1))
+            constexpr int TNM1 = TN - 1;
+            const int j1 = j + 1 < TN ? j + 1 : TNM1;
+            const float gt = acc[i][j][4 * g + e];
+            const float z = (ACT == ACT_GLU && act_here) ? acc[i][j1][4 * g + e] : gt;
+            v[e] = act_here ? act_bf16<ACT>(z, gt) : z;
+          }
+          pk[g][0] = pack_bf16x2(v[0], v[1]);
+          pk[g][1] = pack_bf16x2(v[2], v[3]);
+        }
+        // groups (0,1) and (2,3) each cover 16 consecutive columns: after the swap the lower
+        // lanes hold columns 0..7 and the upper lanes columns 8..15 of those 16
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          swap32(pk[2 * t][0], pk[2 * t + 1][0]);
+          swap32(pk[2 * t][1], pk[2 * t + 1][1]);
+          const u32x4_t val = {pk[2 * t][0], pk[2 * t][1], pk[2 * t + 1][0], pk[2 * t + 1][1]};
+          const int col = occ + 16 * t;  // block of 16 output columns
+          if (tiled) {
+            if (rblk * 32 < p.m_pad)
+              *(u32x4_t*)(base + (((int64_t)rblk * (ld / 16) + col / 16) * 64 + lane) * 16) = val;
+          } else {
+            if (row < p.M && col + 8 * half < p.n_store)
+              *(u32x4_t*)(base + ((int64_t)row * ld + col + 8 * half) * 2) = val;
+          }
+        }
+      }
+    }
+  } else {
+    // lane: column = lane & 31; rows 8 g + 4 (lane >> 5) + 0..3 of each 32x32 tile
+    constexpr int BNO = BN / JSTEP;
+    float* red2 = (float*)smem;  // [WGM][BNO]
+    float* red1 = red2 + WGM * BNO;
+#pragma unroll
+    for (int j = 0; j < TN; j += JSTEP) {
+      float s2 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          const float z = acc[i][(ACT == ACT_GLU) ? j + 1 : j][v];
+          const float gt = acc[i][j][v];
+          float h = (ACT == ACT_GLU) ? silu_f(gt) * z : gelu_f(z);   // exact forms for the scores
+          h = row < p.M ? h : 0.f;
+          s2 += h * h;
+          s1 += fabsf(h);
+        }
+      s2 += __shfl_xor(s2, 32);
+      s1 += __shfl_xor(s1, 32);
+      if (lane < 32) {
+        const int cl = (wn * WN + j * 32) / JSTEP + lane;
+        red2[wm * BNO + cl] = s2;
+        red1[wm * BNO + cl] = s1;
+      }
+    }
+    __syncthreads();
+    for (int t = tid; t < BNO; t += NT) {
+      const int col = n0 / JSTEP + t;
+      if (col < p.n_out) {
+        float a2 = 0.f, a1 = 0.f;
+#pragma unroll
+        for (int w = 0; w < WGM; ++w) { a2 += red2[w * BNO + t]; a1 += red1[w * BNO + t]; }
+        p.part_s2[(int64_t)tm * p.n_out + col] = a2;
+        p.part_s1[(int64_t)tm * p.n_out + col] = a1;
+      }
+    }
+  }
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int PF, int ACT, bool DUAL, bool SCORE, bool A_TILED>
@@ -234,119 +360,231 @@ __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per
     }
   }
 
-  // ---------------------------------------------------------------- epilogue
-  constexpr int JSTEP = (ACT == ACT_GLU) ? 2 : 1;
-  if (!SCORE) {
-    // lane: row = lane & 31; columns 8 g + 4 (lane >> 5) + 0..3 of each 32x32 tile
-    const int half = lane >> 5;
+  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE>(p, acc, m0, n0, tm, wm, wn, lane, tid, smem);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct-to-LDS variant: every wavefront instruction moves one 1 KiB operand block from global
+// memory straight into its LDS slot (global_load_lds_dwordx4), STAGES slabs deep, no staging
+// registers and no LDS store instructions.  One barrier per slab: it publishes the slab that is
+// about to be consumed and retires the one consumed last, whose slot the new loads overwrite.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in
+// imm[3:0] and imm[15:14], expcnt imm[6:4], lgkmcnt imm[11:8])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+// workgroup barrier without a memory fence (the kernel orders its loads with explicit counters);
+// the memory clobber keeps the compiler from moving LDS accesses across it
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+__global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gemm_bf16_dl_kernel(const GemmArgs p) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int NA = DUAL ? 2 : 1;
+  constexpr int KB = BK / 16;                  // k blocks per slab
+  constexpr int A_BLK = NA * (BM / 32) * KB;   // 1 KiB blocks of one slab
+  constexpr int B_BLK = (BN / 32) * KB;
+  constexpr int LA = A_BLK / NW, LB = B_BLK / NW, LPW = LA + LB;   // loads per wavefront and slab
+  constexpr int STAGE = (A_BLK + B_BLK) * 64;  // 16-byte chunks per stage
+  constexpr bool SWAP = !SCORE;
+  static_assert(A_BLK % NW == 0 && B_BLK % NW == 0, "operand blocks must divide over the wavefronts");
+  static_assert(STAGES >= 2 && STAGES <= 4, "two to four stages");
+  static_assert(ACT != ACT_GLU || (TN % 2 == 0), "GLU needs paired column blocks per wave");
+
+  extern __shared__ u32x4_t smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int tiles_n = (p.N + BN - 1) / BN;
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int logical = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  const int gsz = p.group_m * tiles_n;
+  const int first_m = (logical / gsz) * p.group_m;
+  const int gm = min(tiles_m - first_m, p.group_m);
+  const int tm = first_m + (logical % gsz) % gm, tn = (logical % gsz) / gm;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // K range of this split (whole slabs)
+  const int kt_total = (p.K + BK - 1) / BK;
+  const int kt_per = (kt_total + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int kt0 = blockIdx.y * kt_per;
+  const int nk = min(kt_total, kt0 + kt_per) - kt0;
+
+  // ---- the LPW blocks this wavefront moves per slab: block b = wave + i NW of the stage
+  const char* src[LPW];
+  const char* a_row[LA];   // row-major A: start of the lane's row (substitute for chunks past K)
+  int a_col[LA];           // row-major A: column of the lane's chunk inside the slab
+  const int mrb_last = (p.M + 31) / 32 - 1, nrb_last = (p.N + 31) / 32 - 1;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int cb = n0 + wn * WN + j * 32;  // GEMM column of this 32-block
-      if (cb >= p.N) continue;
-      const bool act_here = cb < p.act_cols;
-      int oc;       // output column of the block
-      int jz = j, jg = j;  // accumulator tiles holding the value and the gate
-      if (ACT == ACT_GLU) {
-        if (act_here) {
-          if (j & 1) continue;  // the pair is written when its gate block comes up
-          oc = cb / 2; jz = j + 1; jg = j;
-        } else {
-          oc = cb - p.act_cols / 2;
-        }
-      } else {
-        oc = cb;
-      }
-      char* base;
-      int64_t ld;
-      int occ, tiled;
-      if (oc < p.split_col) { base = (char*)p.C0; ld = p.ldc0; occ = oc; tiled = p.c0_tiled; }
-      else { base = (char*)p.C1; ld = p.ldc1; occ = oc - p.split_col; tiled = p.c1_tiled; }
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int rblk = (m0 + wm * WM) / 32 + i;
-        const int row = rblk * 32 + (lane & 31);
-        if (p.partial) {
-          // fp32 split-K partial, row-major [split][M][ld]
-          if (row < p.M) {
-            float* dst = (float*)base + ((int64_t)blockIdx.y * p.M + row) * ld + occ + 4 * half;
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-              *(float4*)(dst + 8 * g) = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
-                                                    acc[i][j][4 * g + 3]);
-          }
-          continue;
-        }
-        uint32_t pk[4][2];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float z = acc[i][(ACT == ACT_GLU) ? jz : j][4 * g + e];
-            const float gt = acc[i][(ACT == ACT_GLU) ? jg : j][4 * g + e];
-            v[e] = act_here ? act_bf16<ACT>(z, gt) : z;
-          }
-          pk[g][0] = pack_bf16x2(v[0], v[1]);
-          pk[g][1] = pack_bf16x2(v[2], v[3]);
-        }
-        // groups (0,1) and (2,3) each cover 16 consecutive columns: after the swap the lower
-        // lanes hold columns 0..7 and the upper lanes columns 8..15 of those 16
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          swap32(pk[2 * t][0], pk[2 * t + 1][0]);
-          swap32(pk[2 * t][1], pk[2 * t + 1][1]);
-          const u32x4_t val = {pk[2 * t][0], pk[2 * t][1], pk[2 * t + 1][0], pk[2 * t + 1][1]};
-          const int col = occ + 16 * t;  // block of 16 output columns
-          if (tiled) {
-            if (rblk * 32 < p.m_pad)
-              *(u32x4_t*)(base + (((int64_t)rblk * (ld / 16) + col / 16) * 64 + lane) * 16) = val;
-          } else {
-            if (row < p.M && col + 8 * half < p.n_store)
-              *(u32x4_t*)(base + ((int64_t)row * ld + col + 8 * half) * 2) = val;
-          }
-        }
-      }
-    }
-  } else {
-    // lane: column = lane & 31; rows 8 g + 4 (lane >> 5) + 0..3 of each 32x32 tile
-    constexpr int BNO = BN / JSTEP;
-    float* red2 = (float*)smem;  // [WGM][BNO]
-    float* red1 = red2 + WGM * BNO;
-#pragma unroll
-    for (int j = 0; j < TN; j += JSTEP) {
-      float s2 = 0.f, s1 = 0.f;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          const float z = acc[i][(ACT == ACT_GLU) ? j + 1 : j][v];
-          const float gt = acc[i][j][v];
-          float h = (ACT == ACT_GLU) ? silu_f(gt) * z : gelu_f(z);   // exact forms for the scores
-          h = row < p.M ? h : 0.f;
-          s2 += h * h;
-          s1 += fabsf(h);
-        }
-      s2 += __shfl_xor(s2, 32);
-      s1 += __shfl_xor(s1, 32);
-      if (lane < 32) {
-        const int cl = (wn * WN + j * 32) / JSTEP + lane;
-        red2[wm * BNO + cl] = s2;
-        red1[wm * BNO + cl] = s1;
-      }
-    }
-    __syncthreads();
-    for (int t = tid; t < BNO; t += NT) {
-      const int col = n0 / JSTEP + t;
-      if (col < p.n_out) {
-        float a2 = 0.f, a1 = 0.f;
-#pragma unroll
-        for (int w = 0; w < WGM; ++w) { a2 += red2[w * BNO + t]; a1 += red1[w * BNO + t]; }
-        p.part_s2[(int64_t)tm * p.n_out + col] = a2;
-        p.part_s1[(int64_t)tm * p.n_out + col] = a1;
-      }
+  for (int i = 0; i < LA; ++i) {
+    const int b = wave + i * NW;
+    const int s = b / ((BM / 32) * KB), rb = (b / KB) % (BM / 32), kb = b % KB;
+    const char* base = (DUAL && s) ? (const char*)p.A1 : (const char*)p.A;
+    if (A_TILED) {
+      int grb = m0 / 32 + rb;
+      grb = grb <= mrb_last ? grb : mrb_last;
+      src[i] = base + (((int64_t)grb * (p.lda / 16) + (int64_t)kt0 * KB + kb) * 64 + lane) * 16;
+      a_row[i] = nullptr; a_col[i] = 0;
+    } else {
+      int row = m0 + rb * 32 + (lane & 31);
+      row = row < p.M ? row : p.M - 1;
+      a_col[i] = kb * 16 + (lane >> 5) * 8;
+      a_row[i] = base + (int64_t)row * p.lda * 2;
+      src[i] = a_row[i] + ((int64_t)kt0 * BK + a_col[i]) * 2;
     }
   }
+#pragma unroll
+  for (int i = 0; i < LB; ++i) {
+    const int b = wave + i * NW;
+    const int rb = b / KB, kb = b % KB;
+    int grb = n0 / 32 + rb;
+    grb = grb <= nrb_last ? grb : nrb_last;
+    src[LA + i] = (const char*)p.Bt + (((int64_t)grb * (p.ldb / 16) + (int64_t)kt0 * KB + kb) * 64 + lane) * 16;
+  }
+
+  // Loads of one slab are issued in two halves (h = 0: the first LPW / 2 blocks of this
+  // wavefront, h = 1: the rest) so that they can be spread between the MFMAs.
+  constexpr int H0 = LPW / 2, H1 = LPW - H0;
+  auto issue_half = [&](int rel, int stage, int h) {
+    u32x4_t* st = smem + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+      if ((i < H0) != (h == 0)) continue;
+      const char* g;
+      int slot;
+      if (i < LA) {
+        slot = wave + i * NW;
+        if (A_TILED) {
+          g = src[i] + (int64_t)rel * (KB * 1024);
+        } else {
+          // a chunk past K reads the start of the row instead: the weights are zero there
+          g = ((kt0 + rel) * BK + a_col[i] < p.K) ? src[i] + (int64_t)rel * (BK * 2) : a_row[i];
+        }
+      } else {
+        slot = A_BLK + wave + (i - LA) * NW;
+        g = src[i] + (int64_t)rel * (KB * 1024);
+      }
+      __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(st + slot * 64), 16, 0, 0);
+    }
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // Fragment reads run one k step ahead of the MFMAs (two register sets), also across the
+  // slab boundary, so LDS traffic overlaps the matrix pipeline instead of following the barrier.
+  Frag fa[2][NA][TM], fb[2][TN];
+  auto read_frags = [&](int set, int stage, int ks) {
+    const u32x4_t* sA = smem + stage * STAGE;
+    const u32x4_t* sB = sA + A_BLK * 64;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int s = 0; s < NA; ++s) fa[set][s][i].u = sA[((s * (BM / 32) + wm * TM + i) * KB + ks) * 64 + lane];
+#pragma unroll
+    for (int jj = 0; jj < TN; ++jj) fb[set][jj].u = sB[((wn * TN + jj) * KB + ks) * 64 + lane];
+  };
+  auto mfma_step = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int jj = 0; jj < TN; ++jj) {
+        const Frag& af = fa[set][DUAL ? (jj & 1) : 0][i];
+        if (SWAP)
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][jj].v, af.v, acc[i][jj], 0, 0, 0);
+        else
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, fb[set][jj].v, acc[i][jj], 0, 0, 0);
+      }
+  };
+  // Instruction order of one k step: every MFMA is followed by one memory instruction, first
+  // the LDS reads of the next step, then the direct loads (bursts of memory instructions stall
+  // the issuing wavefront and with it the matrix pipeline).
+  auto order_step = [&](auto nl) {
+    constexpr int nload = decltype(nl)::value;
+    constexpr int NR = NA * TM + TN, NM = TM * TN, TOT = NR + nload;
+    constexpr int PER = TOT / NM, REM = TOT % NM;
+    int done = 0;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      const int cnt = PER + (m < REM ? 1 : 0);
+#pragma unroll
+      for (int q = 0; q < cnt; ++q) {
+        if (done < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        ++done;
+      }
+    }
+  };
+  static_assert(KB == 2, "two k steps per slab (one register set each)");
+
+  // prologue: slabs 0 .. STAGES-2 whole, first half of slab STAGES-1
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nk) { issue_half(s, s, 0); issue_half(s, s, 1); }
+  if (STAGES - 1 < nk) issue_half(STAGES - 1, STAGES - 1, 0);
+  if (nk > 0) {
+    // slab 0 has landed once only what was issued after it is outstanding
+    const int later = min(nk, STAGES - 1) - 1;
+    if (later <= 0) {
+      if (STAGES - 1 < nk) wait_vmcnt<H0>(); else wait_vmcnt<0>();
+    } else if (later == 1) {
+      if (STAGES - 1 < nk) wait_vmcnt<LPW + H0>(); else wait_vmcnt<LPW>();
+    } else {
+      if (STAGES - 1 < nk) wait_vmcnt<2 * LPW + H0>(); else wait_vmcnt<2 * LPW>();
+    }
+    lds_barrier();
+    read_frags(0, 0, 0);
+  }
+  int cs = 0;
+  // One slab.  FULL: far enough from the end that every load exists (straight-line code, fixed
+  // instruction order); otherwise the loads and the counter to wait for depend on rel.
+  auto body = [&](int rel, auto full) {
+    constexpr bool FULL = decltype(full)::value;
+    const int ns = cs + 1 == STAGES ? 0 : cs + 1;
+    const int ps = cs == 0 ? STAGES - 1 : cs - 1;
+    // k step 0; the second half of slab rel + STAGES - 1 goes into the stage retired at the
+    // previous barrier
+    read_frags(1, cs, 1);
+    if (FULL || rel + STAGES - 1 < nk) issue_half(rel + STAGES - 1, ps, 1);
+    mfma_step(0);
+    if (FULL) order_step(std::integral_constant<int, H1>{});
+    // Barrier in the middle of the slab: publishes slab rel + 1 (all loads issued after it may
+    // still be in flight) and retires slab rel, whose last fragments are in registers.
+    if (FULL) {
+      wait_vmcnt<(STAGES - 2) * LPW>();
+    } else {
+      const int later = min(nk - 1, rel + STAGES - 1) - (rel + 1);
+      if (later <= 0) wait_vmcnt<0>();
+      else if (later == 1) wait_vmcnt<LPW>();
+      else wait_vmcnt<2 * LPW>();
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // k step 1; the first half of slab rel + STAGES goes into the stage just retired
+    read_frags(0, ns, 0);   // (after the last slab: stale data that is never used)
+    if (FULL || rel + STAGES < nk) issue_half(rel + STAGES, cs, 0);
+    mfma_step(1);
+    if (FULL) order_step(std::integral_constant<int, H0>{});
+    cs = ns;
+  };
+  int rel = 0;
+  for (; rel + STAGES < nk; ++rel) body(rel, std::true_type{});
+  for (; rel < nk; ++rel) body(rel, std::false_type{});
+  if (SCORE) lds_barrier();   // the epilogue reuses the stage memory
+  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE>(p, acc, m0, n0, tm, wm, wn, lane, tid, smem);
 }
 
 // Sum of fp32 split-K partials [n_split][M][N] (fixed order) -> bf16, tiled or row-major.
@@ -383,6 +621,44 @@ int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad
 }
 
 // ------------------------------------------------------------------ host launcher
+
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
+  constexpr int NA = DUAL ? 2 : 1;
+  constexpr size_t lds = (size_t)STAGES * (NA * BM + BN) * BK * 2;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, STAGES, ACT, DUAL, SCORE, A_TILED>;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return -1;
+    configured = true;
+  }
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * 64), lds, st, a);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+static int launch_dl_shape(const GemmArgs& a, int act, int n_split, hipStream_t st) {
+  const bool dual = a.A1 != nullptr;
+  const bool at = a.a_tiled != 0;
+  if (act == ACT_NONE)
+    return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_NONE, false, false, true>(a, n_split, st)
+              : launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_NONE, false, false, false>(a, n_split, st);
+  if (act == ACT_GELU)
+    return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GELU, false, false, true>(a, 1, st)
+              : launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GELU, false, false, false>(a, 1, st);
+  if constexpr (BN / WGN >= 64) {
+    if (act == ACT_GLU && !dual)
+      return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GLU, false, false, true>(a, 1, st)
+                : launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GLU, false, false, false>(a, 1, st);
+    if constexpr ((size_t)STAGES * (2 * BM + BN) * BK * 2 <= 160 * 1024) {
+      if (act == ACT_GLU && dual && at)
+        return launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GLU, true, false, true>(a, 1, st);
+    }
+  }
+  return -1;
+}
 
 template <int BM, int BN, int BK, int WGM, int WGN, int PF, int ACT, bool DUAL, bool SCORE, bool A_TILED>
 static int launch_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
@@ -442,6 +718,11 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
     case 7: return launch_shape<256, 256, 32, 2, 4, 2>(a, act, score, n_split, st);
     case 8: return launch_shape<256, 256, 32, 2, 4, 3>(a, act, score, n_split, st);
     case 9: return launch_shape<128, 128, 32, 2, 2, 3>(a, act, score, n_split, st);
+    case 10: return launch_dl_shape<256, 128, 32, 2, 2, 3>(a, act, n_split, st);
+    case 11: return launch_dl_shape<256, 256, 32, 2, 4, 4>(a, act, n_split, st);
+    case 12: return launch_dl_shape<128, 128, 32, 2, 2, 3>(a, act, n_split, st);
+    case 13: return launch_dl_shape<128, 128, 32, 2, 2, 4>(a, act, n_split, st);
+    case 14: return launch_dl_shape<256, 256, 32, 2, 4, 3>(a, act, n_split, st);
   }
   return -1;
 }
