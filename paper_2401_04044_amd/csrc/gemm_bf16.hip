@@ -381,28 +381,37 @@ __device__ __forceinline__ void wait_vmcnt() {
 // the memory clobber keeps the compiler from moving LDS accesses across it
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
-__global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// KG > 1 splits the reduction inside the workgroup: KG groups of WGM x WGN wavefronts each take
+// every KG-th part of a slab for the same output tile; the groups' accumulators are summed through
+// LDS in a fixed order before the epilogue.  This gives small products (few tiles, long K)
+// more wavefronts per CU without partial sums in global memory.
+template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+__global__ void __launch_bounds__(WGM* WGN* KG * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gemm_bf16_dl_kernel(const GemmArgs p) {
-  constexpr int NW = WGM * WGN;
+  constexpr int NWT = WGM * WGN;               // wavefronts per k group
+  constexpr int NW = NWT * KG;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int NA = DUAL ? 2 : 1;
   constexpr int KB = BK / 16;                  // k blocks per slab
+  constexpr int KS = KB / KG;                  // k steps of a slab per wavefront
   constexpr int A_BLK = NA * (BM / 32) * KB;   // 1 KiB blocks of one slab
   constexpr int B_BLK = (BN / 32) * KB;
   constexpr int LA = A_BLK / NW, LB = B_BLK / NW, LPW = LA + LB;   // loads per wavefront and slab
   constexpr int STAGE = (A_BLK + B_BLK) * 64;  // 16-byte chunks per stage
   constexpr bool SWAP = !SCORE;
   static_assert(A_BLK % NW == 0 && B_BLK % NW == 0, "operand blocks must divide over the wavefronts");
-  static_assert(STAGES >= 2 && STAGES <= 4, "two to four stages");
+  static_assert(KB % KG == 0 && (KS == 1 || KS == 2), "one or two k steps per wavefront and slab");
+  static_assert(STAGES >= 2 && (STAGES - 1) * LPW + LPW <= 63, "loads in flight must fit the counter");
   static_assert(ACT != ACT_GLU || (TN % 2 == 0), "GLU needs paired column blocks per wave");
+  static_assert(!(SCORE && KG > 1), "the score epilogue has no in-workgroup split");
 
   extern __shared__ u32x4_t smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WGN, wn = wave % WGN;
+  const int kg = wave / NWT, wloc = wave % NWT;
+  const int wm = wloc / WGN, wn = wloc % WGN;
   const int tiles_n = (p.N + BN - 1) / BN;
   const int tiles_m = (p.M + BM - 1) / BM;
   const int logical = xcd_remap(blockIdx.x, tiles_m * tiles_n);
@@ -450,14 +459,12 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
     src[LA + i] = (const char*)p.Bt + (((int64_t)grb * (p.ldb / 16) + (int64_t)kt0 * KB + kb) * 64 + lane) * 16;
   }
 
-  // Loads of one slab are issued in two halves (h = 0: the first LPW / 2 blocks of this
-  // wavefront, h = 1: the rest) so that they can be spread between the MFMAs.
-  constexpr int H0 = LPW / 2, H1 = LPW - H0;
-  auto issue_half = [&](int rel, int stage, int h) {
+  // Part q of KS of the loads of slab rel (spread over the k steps, between the MFMAs)
+  auto issue_part = [&](int rel, int stage, int q) {
     u32x4_t* st = smem + stage * STAGE;
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
-      if ((i < H0) != (h == 0)) continue;
+      if (i * KS / LPW != q) continue;
       const char* g;
       int slot;
       if (i < LA) {
@@ -485,9 +492,10 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // Fragment reads run one k step ahead of the MFMAs (two register sets), also across the
-  // slab boundary, so LDS traffic overlaps the matrix pipeline instead of following the barrier.
+  // slab boundary, so LDS traffic overlaps the matrix pipeline instead of following a barrier.
   Frag fa[2][NA][TM], fb[2][TN];
-  auto read_frags = [&](int set, int stage, int ks) {
+  auto read_frags = [&](int set, int stage, int ls) {
+    const int ks = kg * KS + ls;   // this wavefront's k block of the slab
     const u32x4_t* sA = smem + stage * STAGE;
     const u32x4_t* sB = sA + A_BLK * 64;
 #pragma unroll
@@ -509,9 +517,9 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
           acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, fb[set][jj].v, acc[i][jj], 0, 0, 0);
       }
   };
-  // Instruction order of one k step: every MFMA is followed by one memory instruction, first
-  // the LDS reads of the next step, then the direct loads (bursts of memory instructions stall
-  // the issuing wavefront and with it the matrix pipeline).
+  // Instruction order of one k step: the memory instructions (first the LDS reads of the next
+  // step, then the direct loads) are dealt out evenly between the MFMAs; bursts of memory
+  // instructions stall the issuing wavefront and with it the matrix pipeline.
   auto order_step = [&](auto nl) {
     constexpr int nload = decltype(nl)::value;
     constexpr int NR = NA * TM + TN, NM = TM * TN, TOT = NR + nload;
@@ -529,62 +537,135 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
       }
     }
   };
-  static_assert(KB == 2, "two k steps per slab (one register set each)");
-
-  // prologue: slabs 0 .. STAGES-2 whole, first half of slab STAGES-1
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s)
-    if (s < nk) { issue_half(s, s, 0); issue_half(s, s, 1); }
-  if (STAGES - 1 < nk) issue_half(STAGES - 1, STAGES - 1, 0);
-  if (nk > 0) {
-    // slab 0 has landed once only what was issued after it is outstanding
-    const int later = min(nk, STAGES - 1) - 1;
-    if (later <= 0) {
-      if (STAGES - 1 < nk) wait_vmcnt<H0>(); else wait_vmcnt<0>();
-    } else if (later == 1) {
-      if (STAGES - 1 < nk) wait_vmcnt<LPW + H0>(); else wait_vmcnt<LPW>();
-    } else {
-      if (STAGES - 1 < nk) wait_vmcnt<2 * LPW + H0>(); else wait_vmcnt<2 * LPW>();
-    }
-    lds_barrier();
-    read_frags(0, 0, 0);
-  }
-  int cs = 0;
-  // One slab.  FULL: far enough from the end that every load exists (straight-line code, fixed
-  // instruction order); otherwise the loads and the counter to wait for depend on rel.
-  auto body = [&](int rel, auto full) {
-    constexpr bool FULL = decltype(full)::value;
-    const int ns = cs + 1 == STAGES ? 0 : cs + 1;
-    const int ps = cs == 0 ? STAGES - 1 : cs - 1;
-    // k step 0; the second half of slab rel + STAGES - 1 goes into the stage retired at the
-    // previous barrier
-    read_frags(1, cs, 1);
-    if (FULL || rel + STAGES - 1 < nk) issue_half(rel + STAGES - 1, ps, 1);
-    mfma_step(0);
-    if (FULL) order_step(std::integral_constant<int, H1>{});
-    // Barrier in the middle of the slab: publishes slab rel + 1 (all loads issued after it may
-    // still be in flight) and retires slab rel, whose last fragments are in registers.
-    if (FULL) {
+  // slab s has landed once at most the loads of the slabs issued after it are outstanding;
+  // `last` is the last slab issued so far
+  auto wait_landed = [&](int s, int last, auto full) {
+    if (decltype(full)::value) {
       wait_vmcnt<(STAGES - 2) * LPW>();
     } else {
-      const int later = min(nk - 1, rel + STAGES - 1) - (rel + 1);
+      const int later = min(nk - 1, last) - s;
       if (later <= 0) wait_vmcnt<0>();
       else if (later == 1) wait_vmcnt<LPW>();
-      else wait_vmcnt<2 * LPW>();
+      else if (later == 2) wait_vmcnt<2 * LPW>();
+      else if (later == 3) wait_vmcnt<3 * LPW>();
+      else if (later == 4) wait_vmcnt<4 * LPW>();
+      else if (later == 5) wait_vmcnt<5 * LPW>();
+      else wait_vmcnt<6 * LPW>();
     }
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    // k step 1; the first half of slab rel + STAGES goes into the stage just retired
-    read_frags(0, ns, 0);   // (after the last slab: stale data that is never used)
-    if (FULL || rel + STAGES < nk) issue_half(rel + STAGES, cs, 0);
-    mfma_step(1);
-    if (FULL) order_step(std::integral_constant<int, H0>{});
-    cs = ns;
   };
-  int rel = 0;
-  for (; rel + STAGES < nk; ++rel) body(rel, std::true_type{});
-  for (; rel < nk; ++rel) body(rel, std::false_type{});
+  static_assert(STAGES <= 8, "wait_landed covers up to six slabs in flight behind the awaited one");
+
+  // The wavefront's local k steps n = 0, 1, ... (slab n / KS, step n % KS).  During step n the
+  // fragments of step n + 1 are read.  Right after the reads of a slab's last step are issued
+  // comes that slab's barrier: it publishes the next slab (whose first read follows) and
+  // retires this one, whose stage the loads issued from then on refill STAGES slabs ahead.
+  const int nsteps = nk * KS;
+  // prologue: with one step per slab all STAGES stages are filled; with two, the last stage gets
+  // its first part only (its second part goes out with step 0, like every later slab's)
+#pragma unroll
+  for (int s = 0; s < STAGES; ++s)
+    if (s < nk) {
+#pragma unroll
+      for (int q = 0; q < KS; ++q)
+        if (KS == 1 || s < STAGES - 1 || q == 0) issue_part(s, s, q);
+    }
+  if (nk > 0) {
+    wait_landed(0, KS == 1 ? STAGES - 1 : STAGES - 2, std::false_type{});
+    lds_barrier();
+    read_frags(0, 0, 0);
+    if (KS == 1) {
+      // slab 0 is already retired by that read: its barrier
+      wait_landed(1, STAGES - 1, std::false_type{});
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+  }
+  // One unrolled group of U steps starting at step n0 (n0 % U == 0 keeps register sets and
+  // slab-local step numbers static).  FULL: every load referred to exists.
+  constexpr int U = 2;
+  int slab = 0, stage = 0;   // slab and stage of step n0
+  auto group = [&](int n0, auto full) {
+    constexpr bool FULL = decltype(full)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ls = KS == 1 ? 0 : u;                 // step inside its slab
+      const bool last_of_slab = (ls == KS - 1);
+      const int nstage = stage + 1 == STAGES ? 0 : stage + 1;
+      // the step being prefetched: (slab, ls + 1) or (slab + 1, 0)
+      const int pslab = last_of_slab ? slab + 1 : slab;
+      const int pstage = last_of_slab ? nstage : stage;
+      const int pls = last_of_slab ? 0 : ls + 1;
+      if (FULL || n0 + u < nsteps) {
+        read_frags((u + 1) & 1, pstage, pls);   // (past the end: stale data that is never used)
+        // Loads: the latest barrier before this step retired slab r (with two steps per slab,
+        // r = slab - 1 at step 0, where stage "r = -1" is the last, still empty one); the parts
+        // of slab r + STAGES go out with the steps that follow that barrier.
+        {
+          const int r = KS == 1 ? slab : (ls == 0 ? slab - 1 : slab);
+          const int rstage = KS == 1 ? stage : (ls == 0 ? (stage == 0 ? STAGES - 1 : stage - 1) : stage);
+          const int q = KS == 1 ? 0 : (ls == 0 ? 1 : 0);
+          if (FULL || r + STAGES < nk) issue_part(r + STAGES, rstage, q);
+        }
+        mfma_step(u & 1);
+        if (FULL) {
+          if (KS == 1) order_step(std::integral_constant<int, LPW>{});
+          else if (ls == 0) order_step(std::integral_constant<int, LPW - (LPW + 1) / 2>{});   // part 1
+          else order_step(std::integral_constant<int, (LPW + 1) / 2>{});                        // part 0
+        }
+        // barrier of slab pslab once the reads of its last step are issued
+        if (pls == KS - 1) {
+          wait_landed(pslab + 1, pslab + STAGES - 1, full);
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+      }
+      if (last_of_slab) { slab += 1; stage = nstage; }
+    }
+  };
+  int n = 0;
+  // FULL while the group's last retired slab r satisfies r + STAGES < nk and the prefetched slab
+  // + STAGES - 1 <= nk - 1 (so the fixed wait count is right)
+  for (; (n + U - 1) / KS + 1 + STAGES < nk; n += U) group(n, std::true_type{});
+  for (; n < nsteps; n += U) group(n, std::false_type{});
+
+  if (KG > 1) {
+    // Sum the k groups' accumulators: groups 1 .. KG-1 park theirs in LDS (a lane's 16 bytes of
+    // one 32x32 tile quarter, contiguous per wavefront instruction), group 0 adds them in order.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    constexpr int PER_WAVE = TM * TN * 4 * 64;   // 16-byte chunks parked per wavefront
+#pragma unroll 1
+    for (int g = 1; g < KG; ++g) {
+      if (kg == g) {
+        u32x4_t* dst = smem + wloc * PER_WAVE + lane;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const u32x4_t v = {__float_as_uint(acc[i][j][4 * q]), __float_as_uint(acc[i][j][4 * q + 1]),
+                                 __float_as_uint(acc[i][j][4 * q + 2]), __float_as_uint(acc[i][j][4 * q + 3])};
+              dst[((i * TN + j) * 4 + q) * 64] = v;
+            }
+      }
+      __syncthreads();
+      if (kg == 0) {
+        const u32x4_t* srcp = smem + wloc * PER_WAVE + lane;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const u32x4_t v = srcp[((i * TN + j) * 4 + q) * 64];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += __uint_as_float(v[e]);
+            }
+      }
+      if (g + 1 < KG) __syncthreads();
+    }
+    if (kg != 0) return;
+  }
   if (SCORE) lds_barrier();   // the epilogue reuses the stage memory
-  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE>(p, acc, m0, n0, tm, wm, wn, lane, tid, smem);
+  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE>(p, acc, m0, n0, tm, wm, wn, lane, tid & (NWT * 64 - 1), smem);
 }
 
 // Sum of fp32 split-K partials [n_split][M][N] (fixed order) -> bf16, tiled or row-major.
@@ -622,11 +703,14 @@ int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad
 
 // ------------------------------------------------------------------ host launcher
 
-template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
 static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
   constexpr int NA = DUAL ? 2 : 1;
-  constexpr size_t lds = (size_t)STAGES * (NA * BM + BN) * BK * 2;
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, STAGES, ACT, DUAL, SCORE, A_TILED>;
+  constexpr size_t ring = (size_t)STAGES * (NA * BM + BN) * BK * 2;
+  constexpr size_t park = KG > 1 ? (size_t)BM * BN * 4 : 0;   // one k group's accumulators
+  constexpr size_t lds = ring > park ? ring : park;
+  static_assert(lds <= 160 * 1024, "LDS budget of a CU");
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, KG, STAGES, ACT, DUAL, SCORE, A_TILED>;
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -634,27 +718,27 @@ static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
     configured = true;
   }
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * 64), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * KG * 64), lds, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES>
 static int launch_dl_shape(const GemmArgs& a, int act, int n_split, hipStream_t st) {
   const bool dual = a.A1 != nullptr;
   const bool at = a.a_tiled != 0;
   if (act == ACT_NONE)
-    return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_NONE, false, false, true>(a, n_split, st)
-              : launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_NONE, false, false, false>(a, n_split, st);
+    return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_NONE, false, false, true>(a, n_split, st)
+              : launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_NONE, false, false, false>(a, n_split, st);
   if (act == ACT_GELU)
-    return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GELU, false, false, true>(a, 1, st)
-              : launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GELU, false, false, false>(a, 1, st);
+    return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GELU, false, false, true>(a, 1, st)
+              : launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GELU, false, false, false>(a, 1, st);
   if constexpr (BN / WGN >= 64) {
     if (act == ACT_GLU && !dual)
-      return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GLU, false, false, true>(a, 1, st)
-                : launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GLU, false, false, false>(a, 1, st);
-    if constexpr ((size_t)STAGES * (2 * BM + BN) * BK * 2 <= 160 * 1024) {
+      return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, false, false, true>(a, 1, st)
+                : launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, false, false, false>(a, 1, st);
+    if constexpr ((size_t)STAGES * (2 * BM + BN) * BK * 2 <= 160 * 1024 && (2 * (BM / 32) * (BK / 16)) % (WGM * WGN * KG) == 0) {
       if (act == ACT_GLU && dual && at)
-        return launch_dl_cfg<BM, BN, BK, WGM, WGN, STAGES, ACT_GLU, true, false, true>(a, 1, st);
+        return launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, true, false, true>(a, 1, st);
     }
   }
   return -1;
@@ -718,11 +802,18 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
     case 7: return launch_shape<256, 256, 32, 2, 4, 2>(a, act, score, n_split, st);
     case 8: return launch_shape<256, 256, 32, 2, 4, 3>(a, act, score, n_split, st);
     case 9: return launch_shape<128, 128, 32, 2, 2, 3>(a, act, score, n_split, st);
-    case 10: return launch_dl_shape<256, 128, 32, 2, 2, 3>(a, act, n_split, st);
-    case 11: return launch_dl_shape<256, 256, 32, 2, 4, 4>(a, act, n_split, st);
-    case 12: return launch_dl_shape<128, 128, 32, 2, 2, 3>(a, act, n_split, st);
-    case 13: return launch_dl_shape<128, 128, 32, 2, 2, 4>(a, act, n_split, st);
-    case 14: return launch_dl_shape<256, 256, 32, 2, 4, 3>(a, act, n_split, st);
+    case 10: return launch_dl_shape<256, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
+    case 11: return launch_dl_shape<256, 256, 32, 2, 4, 1, 4>(a, act, n_split, st);
+    case 12: return launch_dl_shape<128, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
+    case 13: return launch_dl_shape<128, 128, 32, 2, 2, 1, 4>(a, act, n_split, st);
+    case 14: return launch_dl_shape<256, 256, 32, 2, 4, 1, 3>(a, act, n_split, st);
+    case 15: return launch_dl_shape<256, 128, 32, 2, 2, 2, 5>(a, act, n_split, st);
+    case 16: return launch_dl_shape<128, 128, 32, 2, 2, 2, 8>(a, act, n_split, st);
+    case 17: return launch_dl_shape<128, 128, 64, 2, 2, 2, 4>(a, act, n_split, st);
+    case 18: return launch_dl_shape<256, 128, 64, 2, 2, 2, 3>(a, act, n_split, st);
+    case 19: return launch_dl_shape<128, 128, 32, 2, 2, 1, 8>(a, act, n_split, st);
+    case 20: return launch_dl_shape<256, 128, 32, 2, 2, 1, 6>(a, act, n_split, st);
+    case 21: return launch_dl_shape<128, 128, 32, 2, 2, 1, 6>(a, act, n_split, st);
   }
   return -1;
 }

@@ -716,11 +716,11 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   w.g3_split = 1;
   w.off_kpart = off;
   if (L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
-    // split the long reduction of h2 * P2 until about one workgroup per CU exists (more splits
-    // cost more partial-sum traffic than they gain: measured)
-    const int tiles = (int)((T + 255) / 256) * ((L.rp + 127) / 128);
+    // split the long reduction of h2 * P2 (128x128 tiles) until about one workgroup per CU exists
+    // (more splits cost more partial-sum traffic than they gain: measured)
+    const int tiles = (int)((T + 127) / 128) * ((L.rp + 127) / 128);
     int sp = 256 / (tiles > 0 ? tiles : 1);
-    const int max_sp = L.mp / 256 > 0 ? L.mp / 256 : 1;   // keep >= 8 slabs of 32 per split
+    const int max_sp = L.mp / 512 > 0 ? L.mp / 512 : 1;   // keep >= 8 slabs of 64 per split
     if (sp > max_sp) sp = max_sp;
     if (sp > 16) sp = 16;
     if (sp < 1) sp = 1;
