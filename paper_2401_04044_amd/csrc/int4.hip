@@ -22,6 +22,10 @@
 // Heavy bf16 weights use the same block order with 4 KiB blocks (one 16-byte
 // MFMA operand per lane and 32-element step).
 #include "int4.h"
+#include <type_traits>
+#ifdef FFS_TRACE
+#include <cstdlib>
+#endif
 
 namespace ffsplit {
 
@@ -331,6 +335,15 @@ __device__ __forceinline__ void st_dev(float* p, float v) {
 __device__ __forceinline__ float ld_dev(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// two adjacent floats (8-byte aligned) in one device-scope access
+__device__ __forceinline__ void st_dev2(float* p, float a, float b) {
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store((unsigned long long*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_dev2(const float* p) {
+  const unsigned long long v = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+}
 
 struct Phase1Args {
   const bf16_t* X;        // [T, d]
@@ -346,61 +359,75 @@ struct Phase1Args {
   int n_qtiles, tpw;      // int4 tiles per workgroup
   bf16_t* h;              // [16, hl] bf16; heavy neurons at column 0, remainder at h_off_q
   int hl, h_off_q;
+  unsigned* counters;     // the second kernel's arrival counters, cleared here
+  int n_counters;
+#ifdef FFS_TRACE
+  unsigned long long* trace;
+#endif
 };
+#ifdef FFS_TRACE
+#define FFS_TR(k) do { if (tid == 0) p.trace[(int64_t)blockIdx.x * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define FFS_TR(k) do { } while (0)
+#endif
 
 
-template <int GPW>
-__global__ void __launch_bounds__(512) int4_phase1_kernel(const Phase1Args p) {
-  constexpr int P1_MAXT = GPW >= 4 ? 1 : 2;   // int4 tiles in flight per workgroup (register budget)
-  __shared__ float red[P1_MAXT][8][2][256];
+template <int GPW, int NWV, int NUP>
+__global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args p) {
+  // cross-wave partial sums of a tile: [tile][wave][up / gate][16 x 16]
+  __shared__ float red[1][NWV][2][256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
   const int wg = blockIdx.x;
   const bool heavy = wg < p.n_htiles;
+  FFS_TR(0);
 
-  // ---- weights first.  One register array serves both roles: an int4 workgroup holds
-  // P1_MAXT tiles (gate and up codes of GPW groups each), a heavy workgroup holds the bf16
-  // operands of half of its groups at a time (HG groups x 4 steps x (up, gate)).
-  constexpr int HG = GPW >= 4 ? GPW / 4 : 1;
-  constexpr int NR = (P1_MAXT * GPW * 2 > HG * 8) ? P1_MAXT * GPW * 2 : HG * 8;
-  u32x4_t R[NR];
-  u32x2_t su[P1_MAXT][GPW], sg[P1_MAXT][GPW];
+  // The first workgroup also clears what the second kernel expects to be zero: the arrival
+  // counters, and the columns of h that no neuron writes (padding up to whole 128-blocks).
+  if (wg == 0) {
+    for (int i = tid; i < p.n_counters; i += NWV * 64) p.counters[i] = 0u;
+    const int pad_h = p.h_off_q - p.n_htiles * 16, pad_q = p.hl - p.h_off_q - p.n_qtiles * 16;
+    for (int i = tid; i < 16 * (pad_h + pad_q); i += NWV * 64) {
+      const int row = i / (pad_h + pad_q), c = i % (pad_h + pad_q);
+      const int col = c < pad_h ? p.n_htiles * 16 + c : p.h_off_q + p.n_qtiles * 16 + (c - pad_h);
+      p.h[(int64_t)row * p.hl + col] = 0;
+    }
+  }
+
+  // ---- weights first.  One register buffer, refilled piecewise: as soon as the MFMAs of a
+  // quantisation group (int4) or of a 32-element step (heavy) are issued, the same registers
+  // are loaded with the corresponding piece of the next tile / group, so that about a tile's
+  // worth of this wavefront's weights is in flight while it computes.
+  constexpr int NRB = (GPW * 2 > 8) ? GPW * 2 : 8;   // 16-byte registers
+  u32x4_t R[NRB];
+  u32x2_t su[GPW], sg[GPW];
   const int qt0 = (wg - p.n_htiles) * p.tpw;
   const int qt_end = min(p.n_qtiles, qt0 + p.tpw);
-  auto load_q = [&](int t, int qt) {
-#pragma unroll
-    for (int i = 0; i < GPW; ++i) {
-      const int g = wave * GPW + i;
-      if (g >= p.G) continue;
-      const int64_t blk = (int64_t)qt * p.G + g;
-      R[(t * GPW + i) * 2] = p.q_up[blk * 64 + lane];
-      su[t][i] = *(const u32x2_t*)(p.s_up + blk * 16 + 4 * q);
-      if (p.n_up == 2) {
-        R[(t * GPW + i) * 2 + 1] = p.q_gate[blk * 64 + lane];
-        sg[t][i] = *(const u32x2_t*)(p.s_gate + blk * 16 + 4 * q);
-      }
+  // (a group past the end of the reduction reads the last group's weights: its activations
+  // are zero, so it adds nothing, and the code stays free of branches, which keeps the
+  // compiler's memory-counter waits exact)
+  auto load_q = [&](int i, int qt) {   // group i of this wavefront, tile qt
+    const int g = min(wave * GPW + i, p.G - 1);
+    const int64_t blk = (int64_t)qt * p.G + g;
+    R[i * 2] = p.q_up[blk * 64 + lane];
+    su[i] = *(const u32x2_t*)(p.s_up + blk * 16 + 4 * q);
+    if (NUP == 2) {
+      R[i * 2 + 1] = p.q_gate[blk * 64 + lane];
+      sg[i] = *(const u32x2_t*)(p.s_gate + blk * 16 + 4 * q);
     }
   };
-  auto load_h = [&](int half) {
-#pragma unroll
-    for (int ii = 0; ii < HG; ++ii) {
-      const int i = half * HG + ii;
-      const int g = wave * GPW + i;
-      if (i >= GPW || g >= p.G) continue;
-      const int64_t base = (((int64_t)wg * p.G + g) * 4) * 64 + lane;
-#pragma unroll
-      for (int st = 0; st < 4; ++st) {
-        R[(ii * 4 + st) * 2] = p.hv_up[base + st * 64];
-        if (p.n_up == 2) R[(ii * 4 + st) * 2 + 1] = p.hv_gate[base + st * 64];
-      }
-    }
+  auto load_h = [&](int st, int i) {   // step st of group i of this wavefront
+    const int g = min(wave * GPW + i, p.G - 1);
+    const int64_t at = (((int64_t)wg * p.G + g) * 4 + st) * 64 + lane;
+    R[st * 2] = p.hv_up[at];
+    if (NUP == 2) R[st * 2 + 1] = p.hv_gate[at];
   };
   if (heavy) {
-    load_h(0);
-  } else {
 #pragma unroll
-    for (int t = 0; t < P1_MAXT; ++t)
-      if (qt0 + t < qt_end) load_q(t, qt0 + t);
+    for (int st = 0; st < 4; ++st) load_h(st, 0);
+  } else if (qt0 < qt_end) {
+#pragma unroll
+    for (int i = 0; i < GPW; ++i) load_q(i, qt0);
   }
 
   // ---- tokens' activations for this wavefront's quantisation groups, as MFMA operands
@@ -431,6 +458,7 @@ __global__ void __launch_bounds__(512) int4_phase1_kernel(const Phase1Args p) {
     xsum[i] = s;
   }
 
+  FFS_TR(1);
   // cross-wave sum of `nt` tiles' partials, activation, store of h (bf16 pairs)
   auto finish = [&](int nt, int col0, int col_step) {
     __syncthreads();
@@ -438,14 +466,14 @@ __global__ void __launch_bounds__(512) int4_phase1_kernel(const Phase1Args p) {
     if (t < nt) {
       float u0 = 0.f, g0 = 0.f, u1 = 0.f, g1 = 0.f;
 #pragma unroll
-      for (int w = 0; w < 8; ++w) {
+      for (int w = 0; w < NWV; ++w) {
         u0 += red[t][w][0][2 * pair]; g0 += red[t][w][1][2 * pair];
         u1 += red[t][w][0][2 * pair + 1]; g1 += red[t][w][1][2 * pair + 1];
       }
       const int l = pair >> 1, r = (pair & 1) * 2;
       const int tok = l & 15, neuron = 4 * (l >> 4) + r;
-      const float h0 = p.n_up == 2 ? silu_f(g0) * u0 : gelu_f(u0);
-      const float h1 = p.n_up == 2 ? silu_f(g1) * u1 : gelu_f(u1);
+      const float h0 = NUP == 2 ? silu_f(g0) * u0 : gelu_f(u0);
+      const float h1 = NUP == 2 ? silu_f(g1) * u1 : gelu_f(u1);
       if (tok < p.T)
         *(uint32_t*)(p.h + (int64_t)tok * p.hl + col0 + t * col_step + neuron) = pack_bf16x2(h0, h1);
     }
@@ -454,77 +482,102 @@ __global__ void __launch_bounds__(512) int4_phase1_kernel(const Phase1Args p) {
   if (heavy) {
     f32x4_t au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int half = 0; half * HG < GPW; ++half) {
+    for (int i = 0; i < GPW; ++i) {
 #pragma unroll
-      for (int ii = 0; ii < HG; ++ii) {
-        const int i = half * HG + ii;
-        if (i >= GPW || wave * GPW + i >= p.G) continue;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          VFrag a, b;
-          a.u = R[(ii * 4 + st) * 2];
-          au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xr[i][st].v, au, 0, 0, 0);
-          if (p.n_up == 2) {
-            b.u = R[(ii * 4 + st) * 2 + 1];
-            ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.v, xr[i][st].v, ag, 0, 0, 0);
-          }
+      for (int st = 0; st < 4; ++st) {
+        VFrag a, c;
+        a.u = R[st * 2];
+        au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xr[i][st].v, au, 0, 0, 0);
+        if (NUP == 2) {
+          c.u = R[st * 2 + 1];
+          ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(c.v, xr[i][st].v, ag, 0, 0, 0);
         }
+        if (i + 1 < GPW) load_h(st, i + 1);
       }
-      if ((half + 1) * HG < GPW) load_h(half + 1);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       red[0][wave][0][lane * 4 + r] = au[r];
       red[0][wave][1][lane * 4 + r] = ag[r];
     }
+    FFS_TR(2);
     finish(1, wg * 16, 0);
+    FFS_TR(3);
     return;
   }
 
-  for (int qb = qt0; qb < qt_end; qb += P1_MAXT) {
-    const int nt = min(P1_MAXT, qt_end - qb);
+  // one tile: products group by group; with REFILL the group's registers are reloaded with the
+  // same group of tile qt + 1 as soon as its MFMAs are issued
+  auto tile = [&](int qt, auto refill) {
+    constexpr bool REFILL = decltype(refill)::value;
+    f32x4_t au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < P1_MAXT; ++t) {
-      f32x4_t au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
-      if (t < nt) {
+    for (int i = 0; i < GPW; ++i) {
+      const float corr = 136.f * xsum[i];
+      f32x4_t ru = {0.f, 0.f, 0.f, 0.f}, rg = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < GPW; ++i) {
-          if (wave * GPW + i >= p.G) continue;
-          const float corr = 136.f * xsum[i];
-          {
-            f32x4_t raw = {0.f, 0.f, 0.f, 0.f};
+      for (int st = 0; st < 4; ++st)
+        ru = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(R[i * 2][st]).v, xr[i][st].v, ru, 0, 0, 0);
+      if (NUP == 2) {
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
-              raw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(R[(t * GPW + i) * 2][st]).v, xr[i][st].v, raw, 0, 0, 0);
-            const uint32_t sb[4] = {su[t][i][0] & 0xffffu, su[t][i][0] >> 16, su[t][i][1] & 0xffffu, su[t][i][1] >> 16};
-#pragma unroll
-            for (int r = 0; r < 4; ++r) au[r] = fmaf(half_bits_to_f32((uint16_t)sb[r]), raw[r] - corr, au[r]);
-          }
-          if (p.n_up == 2) {
-            f32x4_t raw = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-              raw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(R[(t * GPW + i) * 2 + 1][st]).v, xr[i][st].v, raw, 0, 0, 0);
-            const uint32_t sb[4] = {sg[t][i][0] & 0xffffu, sg[t][i][0] >> 16, sg[t][i][1] & 0xffffu, sg[t][i][1] >> 16};
-#pragma unroll
-            for (int r = 0; r < 4; ++r) ag[r] = fmaf(half_bits_to_f32((uint16_t)sb[r]), raw[r] - corr, ag[r]);
-          }
-          __builtin_amdgcn_sched_barrier(0);   // one group at a time: keeps the dequantised operands few
-        }
+        for (int st = 0; st < 4; ++st)
+          rg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(R[i * 2 + 1][st]).v, xr[i][st].v, rg, 0, 0, 0);
       }
+      float fu[4], fg[4];
+      fu[0] = half_bits_to_f32((uint16_t)(su[i][0] & 0xffffu)); fu[1] = half_bits_to_f32((uint16_t)(su[i][0] >> 16));
+      fu[2] = half_bits_to_f32((uint16_t)(su[i][1] & 0xffffu)); fu[3] = half_bits_to_f32((uint16_t)(su[i][1] >> 16));
+      if (NUP == 2) {
+        fg[0] = half_bits_to_f32((uint16_t)(sg[i][0] & 0xffffu)); fg[1] = half_bits_to_f32((uint16_t)(sg[i][0] >> 16));
+        fg[2] = half_bits_to_f32((uint16_t)(sg[i][1] & 0xffffu)); fg[3] = half_bits_to_f32((uint16_t)(sg[i][1] >> 16));
+      }
+      if (REFILL) load_q(i, qt + 1);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        red[t][wave][0][lane * 4 + r] = au[r];
-        red[t][wave][1][lane * 4 + r] = ag[r];
+        au[r] = fmaf(fu[r], ru[r] - corr, au[r]);
+        if (NUP == 2) ag[r] = fmaf(fg[r], rg[r] - corr, ag[r]);
       }
+      __builtin_amdgcn_sched_barrier(0);   // one group at a time: keeps the dequantised operands few
     }
-    // the next batch's weights are requested before this batch is reduced
-    const int qn = qb + P1_MAXT;
 #pragma unroll
-    for (int t = 0; t < P1_MAXT; ++t)
-      if (qn + t < qt_end) load_q(t, qn + t);
-    finish(nt, p.h_off_q + qb * 16, 16);
-    if (qn < qt_end) __syncthreads();   // red is reused
+    for (int r = 0; r < 4; ++r) {
+      red[0][wave][0][lane * 4 + r] = au[r];
+      red[0][wave][1][lane * 4 + r] = ag[r];
+    }
+  };
+  int qt = qt0;
+  for (; qt + 1 < qt_end; ++qt) {
+    tile(qt, std::true_type{});
+    FFS_TR(2 + 2 * (qt - qt0));
+    finish(1, p.h_off_q + qt * 16, 16);
+    __syncthreads();   // red is reused
+    FFS_TR(3 + 2 * (qt - qt0));
+  }
+  if (qt < qt_end) {
+    tile(qt, std::false_type{});
+    FFS_TR(2 + 2 * (qt - qt0));
+    finish(1, p.h_off_q + qt * 16, 16);
+    FFS_TR(3 + 2 * (qt - qt0));
+  }
+}
+
+// 16-byte global load whose completion the kernel tracks itself: the compiler neither waits for
+// it nor moves it; every use is preceded by wait_loads<N>(reg), which waits until at most the N
+// most recently issued vector-memory operations are outstanding and ties the register to the wait.
+__device__ __forceinline__ u32x4_t load16_untracked(const void* ptr) {
+  u32x4_t v;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_loads(u32x4_t& r) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(N) : "memory");
+}
+
+template <int I, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < END) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, END>(f);
   }
 }
 
@@ -538,6 +591,9 @@ struct Phase2Args {
   int JBr, jp128;
   float* part;             // [G][S][2][16][128] fp32 (heavy, remainder)
   unsigned* counters;      // [G] arrivals, zero on entry
+#ifdef FFS_TRACE
+  unsigned long long* trace;
+#endif
   bf16_t* Y;
   bf16_t* Yh;
   bf16_t* Yr;
@@ -554,71 +610,101 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
   const int cg = blockIdx.x, sp = blockIdx.y;
+#ifdef FFS_TRACE
+#undef FFS_TR
+#define FFS_TR(k) do { if (tid == 0) p.trace[((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#endif
+  FFS_TR(0);
 
   const int NJ = p.JBr > sp ? (p.JBr - sp + p.S - 1) / p.S : 0;           // int4 blocks sp, sp+S, ...
   const int NHq = p.JBh * 4 > sp ? (p.JBh * 4 - sp + p.S - 1) / p.S : 0;  // heavy steps sp, sp+S, ...
+  // Loads are kept free of branches (indices past the end are clamped to the last valid block:
+  // a repeated address, served by the cache) so that the compiler's memory-counter waits stay
+  // exact and the small activation loads below need not wait for the weights behind them.
   u32x4_t w2[P2_MAXJ], wh[P2_MAXH];
+  // (a part with no block at all for this workgroup reads the start of the other part's
+  // blocks instead, which exist: d_ff > 0)
+  const u32x4_t* qsrc = NJ > 0 ? p.q_down : p.hv_down;
+  const u32x4_t* hsrc = NHq > 0 ? p.hv_down : p.q_down;
   auto load_down = [&](int pass) {
 #pragma unroll
     for (int i = 0; i < P2_MAXJ; ++i) {
-      const int ii = pass * P2_MAXJ + i;
-      if (ii < NJ) w2[i] = p.q_down[(((int64_t)cg * p.JBr + sp + ii * p.S) * 8 + wave) * 64 + lane];
+      const int ii = min(pass * P2_MAXJ + i, NJ - 1);
+      const int64_t at = NJ > 0 ? (((int64_t)cg * p.JBr + sp + ii * p.S) * 8 + wave) * 64 + lane : tid;
+      w2[i] = load16_untracked(qsrc + at);
     }
 #pragma unroll
     for (int i = 0; i < P2_MAXH; ++i) {
-      const int ii = pass * P2_MAXH + i;
-      if (ii < NHq) {
-        const int hq = sp + ii * p.S;
-        wh[i] = p.hv_down[((((int64_t)cg * p.JBh + (hq >> 2)) * 8 + wave) * 4 + (hq & 3)) * 64 + lane];
-      }
+      const int hq = sp + min(pass * P2_MAXH + i, NHq - 1) * p.S;
+      const int64_t at = NHq > 0 ? ((((int64_t)cg * p.JBh + (hq >> 2)) * 8 + wave) * 4 + (hq & 3)) * 64 + lane : tid;
+      wh[i] = load16_untracked(hsrc + at);
     }
   };
-  load_down(0);
 
   f32x4_t acc_r = {0.f, 0.f, 0.f, 0.f}, acc_h = {0.f, 0.f, 0.f, 0.f};
   float hsum = 0.f;
   const int n_pass_j = (NJ + P2_MAXJ - 1) / P2_MAXJ, n_pass_h = (NHq + P2_MAXH - 1) / P2_MAXH;
   const int n_pass = n_pass_j > n_pass_h ? n_pass_j : n_pass_h;
+  constexpr int HPW = (P2_STEPS + 7) / 8;   // operand steps prepared per wavefront and pass
   for (int pass = 0; pass < n_pass; ++pass) {
-    if (pass > 0) {
-      __syncthreads();   // hop is reused
-      load_down(pass);
-    }
+    if (pass > 0) __syncthreads();   // hop is reused
     const int nj = max(0, min(P2_MAXJ, NJ - pass * P2_MAXJ));
     const int nh = max(0, min(P2_MAXH, NHq - pass * P2_MAXH));
     const int n_steps = nj * 4 + nh;
-    // operands: step sigma < 4 nj is (int4 block sigma / 4, 32-neuron step sigma % 4), the rest heavy
-    for (int sgm = wave; sgm < n_steps; sgm += 8) {
-      int j0, hv;
-      if (sgm < nj * 4) {
-        const int jb = sp + (pass * P2_MAXJ + (sgm >> 2)) * p.S;
-        j0 = jb * 128 + 32 * (sgm & 3) + 8 * q;
-        hv = 0;
-      } else {
-        const int hq = sp + (pass * P2_MAXH + (sgm - nj * 4)) * p.S;
-        j0 = (hq >> 2) * 128 + 32 * (hq & 3) + 8 * q;
-        hv = 1;
-      }
+    // 1. the activations (and, for the int4 part, the neurons' scales for this column group) of
+    //    this wavefront's operand steps: step sigma < 4 nj is (int4 block sigma / 4, 32-neuron
+    //    step sigma % 4), the rest heavy.  Requested before the weights: they come from cache
+    //    and return first.
+    u32x4_t hreg[HPW], sreg[HPW];
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) {
+      const int sgm = min(wave + 8 * i, n_steps - 1);
+      const bool hv = sgm >= nj * 4;
+      const int jq = sp + (pass * P2_MAXJ + (sgm >> 2)) * p.S;
+      const int hq = sp + (pass * P2_MAXH + (sgm - nj * 4)) * p.S;
+      const int j0 = hv ? (hq >> 2) * 128 + 32 * (hq & 3) + 8 * q : jq * 128 + 32 * (sgm & 3) + 8 * q;
+      const int tok = n < p.T ? n : 0;
+      hreg[i] = load16_untracked(p.h + (int64_t)tok * p.hl + (hv ? 0 : p.h_off_q) + j0);
+      sreg[i] = load16_untracked(p.s_down + (int64_t)cg * p.jp128 + (hv ? 0 : j0));
+    }
+    // 2. the weights
+    load_down(pass);
+    if (pass == 0) FFS_TR(1);
+    // 3. operands into LDS (the P2_MAXJ + P2_MAXH weight loads may still be in flight)
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) {
+      wait_loads<P2_MAXJ + P2_MAXH>(hreg[i]);
+      wait_loads<P2_MAXJ + P2_MAXH>(sreg[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) {
+      const int sgm = wave + 8 * i;
+      const bool hv = sgm >= nj * 4;
       VFrag f;
-      f.u = u32x4_t{0, 0, 0, 0};
-      if (n < p.T) f.u = *(const u32x4_t*)(p.h + (int64_t)n * p.hl + (hv ? 0 : p.h_off_q) + j0);
-      if (!hv) {
+      f.u = hreg[i];
+      float part = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
         // the down row of a neuron is quantised in groups along the outputs: its scale for this
         // column group multiplies the neuron's activation
-        const u32x4_t sv = *(const u32x4_t*)(p.s_down + (int64_t)cg * p.jp128 + j0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float lo = __uint_as_float(f.w[e] << 16) * half_bits_to_f32((uint16_t)(sv[e] & 0xffffu));
-          const float hi = __uint_as_float(f.w[e] & 0xffff0000u) * half_bits_to_f32((uint16_t)(sv[e] >> 16));
-          f.w[e] = pack_bf16x2(lo, hi);
-          hsum += __uint_as_float(f.w[e] << 16) + __uint_as_float(f.w[e] & 0xffff0000u);
-        }
+        const float lo = __uint_as_float(f.w[e] << 16) * half_bits_to_f32((uint16_t)(sreg[i][e] & 0xffffu));
+        const float hi = __uint_as_float(f.w[e] & 0xffff0000u) * half_bits_to_f32((uint16_t)(sreg[i][e] >> 16));
+        const uint32_t sc = pack_bf16x2(lo, hi);
+        part += __uint_as_float(sc << 16) + __uint_as_float(sc & 0xffff0000u);
+        f.w[e] = hv ? f.w[e] : sc;
       }
-      hop[sgm][lane] = f.u;
+      if (n >= p.T) { f.u = u32x4_t{0, 0, 0, 0}; part = 0.f; }
+      if (sgm < n_steps) {
+        hop[sgm][lane] = f.u;
+        if (!hv) hsum += part;
+      }
     }
+    FFS_TR(2 + 3 * pass);
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < P2_MAXJ; ++i) {
+    FFS_TR(3 + 3 * pass);
+    static_for<0, P2_MAXJ>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      wait_loads<P2_MAXJ - 1 - i + P2_MAXH>(w2[i]);
       if (i < nj) {
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
@@ -627,16 +713,18 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
           acc_r = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8v(w2[i][st]).v, b.v, acc_r, 0, 0, 0);
         }
       }
-    }
-#pragma unroll
-    for (int i = 0; i < P2_MAXH; ++i) {
+    });
+    static_for<0, P2_MAXH>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      wait_loads<P2_MAXH - 1 - i>(wh[i]);
       if (i < nh) {
         VFrag a, b;
         a.u = wh[i];
         b.u = hop[nj * 4 + i][lane];
         acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc_h, 0, 0, 0);
       }
-    }
+    });
+    FFS_TR(4 + 3 * pass);
   }
   // the constant 136 of the offset-binary codes: subtract 136 * (sum of this workgroup's scaled activations)
   hsum += __shfl_xor(hsum, 16);
@@ -651,40 +739,50 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc_r[r] -= corr;
   }
-  // lane holds outputs c = 16 wave + 4 q + r of token n
-  float* pw = p.part + ((int64_t)(cg * p.S + sp) * 2) * 16 * 128;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    st_dev(&pw[n * 128 + wave * 16 + 4 * q + r], acc_h[r]);
-    st_dev(&pw[16 * 128 + n * 128 + wave * 16 + 4 * q + r], acc_r[r]);
+  // lane holds outputs c = 16 wave + 4 q + r of token n.  Unless the caller wants the heavy
+  // and the remainder parts separately, only their sum crosses workgroups.
+  const bool parts = p.Yh != nullptr || p.Yr != nullptr;
+  float* pw = p.part + ((int64_t)(cg * p.S + sp) * 2) * 16 * 128 + n * 128 + wave * 16 + 4 * q;
+  if (parts) {
+    st_dev2(pw, acc_h[0], acc_h[1]);
+    st_dev2(pw + 2, acc_h[2], acc_h[3]);
+    st_dev2(pw + 16 * 128, acc_r[0], acc_r[1]);
+    st_dev2(pw + 16 * 128 + 2, acc_r[2], acc_r[3]);
+  } else {
+    st_dev2(pw, acc_h[0] + acc_r[0], acc_h[1] + acc_r[1]);
+    st_dev2(pw + 2, acc_h[2] + acc_r[2], acc_h[3] + acc_r[3]);
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's device-scope stores are done
   __syncthreads();
+  FFS_TR(8);
   if (tid == 0) flag_s = atomicAdd(&p.counters[cg], 1u) == (unsigned)(p.S - 1);
   __syncthreads();
+  FFS_TR(9);
   if (!flag_s) return;
-  for (int o = tid; o < 16 * 128; o += 512) {
+  // last workgroup of the column group: fixed-order sum over the splits, two outputs per thread
+  for (int o = 2 * tid; o < 16 * 128; o += 1024) {
     const int tok = o >> 7, c = o & 127;
     if (tok >= p.T) continue;
-    // all loads first (independent), then the fixed-order sum
-    float va[16], vb[16];
+    // all loads first (independent), then the sums
+    float2 va[16], vb[16];
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
-      va[s] = 0.f; vb[s] = 0.f;
+      va[s] = make_float2(0.f, 0.f); vb[s] = make_float2(0.f, 0.f);
       if (s < p.S) {
         const float* ps = p.part + ((int64_t)(cg * p.S + s) * 2) * 16 * 128;
-        va[s] = ld_dev(ps + o);
-        vb[s] = ld_dev(ps + 16 * 128 + o);
+        va[s] = ld_dev2(ps + o);
+        if (parts) vb[s] = ld_dev2(ps + 16 * 128 + o);
       }
     }
-    float a = 0.f, b = 0.f;
+    float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
 #pragma unroll
-    for (int s = 0; s < 16; ++s) { a += va[s]; b += vb[s]; }
+    for (int s = 0; s < 16; ++s) { a0 += va[s].x; a1 += va[s].y; b0 += vb[s].x; b1 += vb[s].y; }
     const int64_t oi = (int64_t)tok * p.d + cg * 128 + c;
-    p.Y[oi] = f32_to_bf16(a + b);
-    if (p.Yh) p.Yh[oi] = f32_to_bf16(a);
-    if (p.Yr) p.Yr[oi] = f32_to_bf16(b);
+    *(uint32_t*)(p.Y + oi) = pack_bf16x2(a0 + b0, a1 + b1);
+    if (p.Yh) *(uint32_t*)(p.Yh + oi) = pack_bf16x2(a0, a1);
+    if (p.Yr) *(uint32_t*)(p.Yr + oi) = pack_bf16x2(b0, b1);
   }
+  FFS_TR(10);
 }
 
 static int phase2_splits(int G) {
@@ -705,6 +803,9 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     w.off_cnt = off; off = align256(off + (size_t)L.groups * 4);
     w.off_part = off; off = align256(off + (size_t)L.groups * S * 2 * 16 * 128 * 4);
     w.n_split = S;
+#ifdef FFS_TRACE
+    off = align256(off + (1u << 20));
+#endif
     w.total_bytes = off;
     return w;
   }
@@ -731,9 +832,10 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   return w;
 }
 
-template <int GPW>
+template <int GPW, int NWV>
 static int launch_phase1(const Phase1Args& a, int grid, hipStream_t st) {
-  hipLaunchKernelGGL(int4_phase1_kernel<GPW>, dim3(grid), dim3(512), 0, st, a);
+  if (a.n_up == 2) hipLaunchKernelGGL((int4_phase1_kernel<GPW, NWV, 2>), dim3(grid), dim3(NWV * 64), 0, st, a);
+  else hipLaunchKernelGGL((int4_phase1_kernel<GPW, NWV, 1>), dim3(grid), dim3(NWV * 64), 0, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -742,8 +844,9 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
   const int m = d.d_ff - d.k, dm = d.d_model, G = L.groups;
   const int hl = L.kp128 + L.jp128;
   const int S = w.n_split;
-  const int gpw = (G + 7) / 8;
-  if (gpw > 8) return -2;
+  const int nwv = 8;
+  const int gpw = (G + nwv - 1) / nwv;
+  if (gpw > 4) return -2;
   const int n_h = L.kp / 16, n_q = m > 0 ? L.jp16 / 16 : 0;
   // int4 tiles per workgroup: about one 8-wave workgroup per CU in total, so that the tokens'
   // activations are fetched once per CU rather than once per tile
@@ -753,9 +856,6 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
   const int grid1 = n_h + (n_q + tpw - 1) / tpw;
   for (int t0 = 0; t0 < M; t0 += 16) {
     const int T = M - t0 < 16 ? M - t0 : 16;
-    // h columns no neuron writes (padding up to whole 128-blocks) must read as zero and the
-    // arrival counters start at zero: they are adjacent, one fill covers both
-    if (launch_fill_zero(ws + w.off_h, w.off_part - w.off_h, st)) return -1;
     Phase1Args a = {};
     a.X = (const bf16_t*)X + (int64_t)t0 * dm;
     a.T = T; a.d = dm; a.G = G; a.n_up = L.n_up;
@@ -768,12 +868,20 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
     a.s_gate = (const uint16_t*)(split + L.off_s4[1]);
     a.n_qtiles = n_q; a.tpw = tpw;
     a.h = (bf16_t*)(ws + w.off_h); a.hl = hl; a.h_off_q = L.kp128;
+    a.counters = (unsigned*)(ws + w.off_cnt); a.n_counters = G;
+#ifdef FFS_TRACE
+    a.trace = (unsigned long long*)(ws + w.off_part);
+#endif
     if (grid1 > 0) {
       int rc;
-      if (gpw <= 1) rc = launch_phase1<1>(a, grid1, st);
-      else if (gpw <= 2) rc = launch_phase1<2>(a, grid1, st);
-      else if (gpw <= 4) rc = launch_phase1<4>(a, grid1, st);
-      else rc = launch_phase1<8>(a, grid1, st);
+      if (nwv == 16) {
+        if (gpw <= 2) rc = launch_phase1<2, 16>(a, grid1, st);
+        else rc = launch_phase1<4, 16>(a, grid1, st);
+      } else {
+        if (gpw <= 1) rc = launch_phase1<1, 8>(a, grid1, st);
+        else if (gpw <= 2) rc = launch_phase1<2, 8>(a, grid1, st);
+        else rc = launch_phase1<4, 8>(a, grid1, st);
+      }
       if (rc) return rc;
     }
     Phase2Args b = {};
@@ -789,6 +897,10 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
     b.Y = (bf16_t*)Y + (int64_t)t0 * dm;
     b.Yh = Y_heavy ? (bf16_t*)Y_heavy + (int64_t)t0 * dm : nullptr;
     b.Yr = Y_rem ? (bf16_t*)Y_rem + (int64_t)t0 * dm : nullptr;
+#ifdef FFS_TRACE
+    if (getenv("FFS_ONLY_P1")) continue;
+    b.trace = (unsigned long long*)(ws + w.total_bytes - (1u << 20));
+#endif
     hipLaunchKernelGGL(int4_phase2_kernel, dim3(G, S), dim3(512), 0, st, b);
     if (hipGetLastError() != hipSuccess) return -1;
   }
