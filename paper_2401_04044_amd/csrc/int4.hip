@@ -394,7 +394,25 @@ __global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args 
     }
   }
 
-  // ---- weights first.  One register buffer, refilled piecewise: as soon as the MFMAs of a
+  // ---- tokens' activations for this wavefront's quantisation groups, as MFMA operands.
+  // Requested before the weights (they come from cache and return first, so the per-group sums
+  // below are formed while the weights are in flight); addresses are clamped and the values
+  // masked so that the loads stay unconditional.
+  VFrag xr[GPW][4];
+  float xsum[GPW];
+#pragma unroll
+  for (int i = 0; i < GPW; ++i) {
+    const int g = wave * GPW + i;
+    const bool valid = g < p.G && n < p.T;
+    const int gc = min(g, p.G - 1), nc = min(n, p.T - 1);
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      const u32x4_t v = *(const u32x4_t*)(p.X + (int64_t)nc * p.d + gc * 128 + 32 * st + 8 * q);
+      xr[i][st].u = valid ? v : u32x4_t{0, 0, 0, 0};
+    }
+  }
+
+  // ---- then the weights.  One register buffer, refilled piecewise: as soon as the MFMAs of a
   // quantisation group (int4) or of a 32-element step (heavy) are issued, the same registers
   // are loaded with the corresponding piece of the next tile / group, so that about a tile's
   // worth of this wavefront's weights is in flight while it computes.
@@ -430,19 +448,6 @@ __global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args 
     for (int i = 0; i < GPW; ++i) load_q(i, qt0);
   }
 
-  // ---- tokens' activations for this wavefront's quantisation groups, as MFMA operands
-  VFrag xr[GPW][4];
-  float xsum[GPW];
-#pragma unroll
-  for (int i = 0; i < GPW; ++i) {
-    const int g = wave * GPW + i;
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      u32x4_t v = {0, 0, 0, 0};
-      if (g < p.G && n < p.T) v = *(const u32x4_t*)(p.X + (int64_t)n * p.d + g * 128 + 32 * st + 8 * q);
-      xr[i][st].u = v;
-    }
-  }
 #pragma unroll
   for (int i = 0; i < GPW; ++i) {
     float s = 0.f;
@@ -874,14 +879,9 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
 #endif
     if (grid1 > 0) {
       int rc;
-      if (nwv == 16) {
-        if (gpw <= 2) rc = launch_phase1<2, 16>(a, grid1, st);
-        else rc = launch_phase1<4, 16>(a, grid1, st);
-      } else {
-        if (gpw <= 1) rc = launch_phase1<1, 8>(a, grid1, st);
-        else if (gpw <= 2) rc = launch_phase1<2, 8>(a, grid1, st);
-        else rc = launch_phase1<4, 8>(a, grid1, st);
-      }
+      if (gpw <= 1) rc = launch_phase1<1, 8>(a, grid1, st);
+      else if (gpw <= 2) rc = launch_phase1<2, 8>(a, grid1, st);
+      else rc = launch_phase1<4, 8>(a, grid1, st);
       if (rc) return rc;
     }
     Phase2Args b = {};
