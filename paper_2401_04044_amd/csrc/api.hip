@@ -300,10 +300,13 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   // Column offset inside a K-contiguous buffer: elements (row-major) or whole 16-wide
   // k blocks of 1 KiB (tiled).
   auto koff_bytes = [&](int koff) -> size_t { return L.tiled ? (size_t)(koff / 16) * 1024 : (size_t)koff * esz; };
+  // batches of at most 32 rows are bound by streaming the weights: dedicated kernels
+  const bool small_m = bf16 && M <= 32;
   auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
     if (g.group_m <= 0) g.group_m = 8;
     g.m_pad = w.t_pad;
     if (!bf16) return launch_gemm_f32(g, a, false, st);
+    if (small_m && !g.partial && (g.N & 31) == 0) return launch_skinny_bf16(g, a, (float*)(ws + w.off_kpart), st);
     return launch_gemm_bf16(g, a, false, shape, n_split, st);
   };
   const int big_m = M > 1024;   // 256-row tiles only pay off with enough rows
@@ -338,7 +341,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     g.M = M; g.N = L.rp; g.K = L.mp;
     g.split_col = L.rp;
     g.group_m = 1;   // h2 is the large operand
-    if (bf16 && w.g3_split > 1) {
+    if (bf16 && w.g3_split > 1 && !small_m) {
       float* part = (float*)(ws + w.off_kpart);
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
       FFS_TRY(run(g, ACT_NONE, big_m ? 17 : 4, w.g3_split));

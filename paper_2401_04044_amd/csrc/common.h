@@ -92,5 +92,9 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
 int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
                          hipStream_t st);
 int bf16_score_tile_m();
+// small-batch path (M <= 32, N a multiple of 32): weight-streaming kernel + fixed-order reduce;
+// part: scratch of skinny_part_bytes(N) bytes
+size_t skinny_part_bytes(int n_max);
+int launch_skinny_bf16(const GemmArgs& a, int act, float* part, hipStream_t st);
 
 }  // namespace ffsplit
