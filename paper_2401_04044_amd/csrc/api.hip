@@ -130,7 +130,7 @@ int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, con
     g.group_m = 8;
     g.act_cols = w.n_gemm;
     g.part_s2 = p2; g.part_s1 = p1; g.n_out = w.n_out;
-    if (bf16) FFS_TRY(launch_gemm_bf16(g, act_of(d), true, 0, 1, st));
+    if (bf16) FFS_TRY(launch_gemm_bf16(g, act_of(d), true, GEMM_256x128, 1, st));
     else FFS_TRY(launch_gemm_f32(g, act_of(d), true, st));
     FFS_TRY(launch_reduce_partials(p2, p1, w.tiles_m, w.n_out, d->d_ff, acc, st));
     *T_total += T;
@@ -322,7 +322,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
     g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
     g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
-    FFS_TRY(run(g, act, big_m ? (L.n1 >= 4096 ? 10 : 13) : 4, 1));
+    FFS_TRY(run(g, act, big_m ? (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_DEEP) : GEMM_128x128, 1));
   }
   if (rem_lr) {
     // G2: t * Q1 -> activation -> h2
@@ -333,7 +333,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
     g.act_cols = g.N; g.split_col = L.mp;
     g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
-    FFS_TRY(run(g, act, big_m ? 10 : 4, 1));
+    FFS_TRY(run(g, act, big_m ? GEMM_256x128 : GEMM_128x128, 1));
     // G3: h2 * P2 -> t2 into cat[:, kp:]  (long reduction: split-K, fixed-order sum)
     g = {};
     g.A = h2; g.lda = L.mp; g.a_tiled = L.tiled;
@@ -344,11 +344,11 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     if (bf16 && w.g3_split > 1 && !small_m) {
       float* part = (float*)(ws + w.off_kpart);
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
-      FFS_TRY(run(g, ACT_NONE, big_m ? 17 : 4, w.g3_split));
+      FFS_TRY(run(g, ACT_NONE, big_m ? GEMM_128x128_KSPLIT : GEMM_128x128, w.g3_split));
       FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, 1, st));
     } else {
       g.C0 = cat + koff_bytes(L.kp); g.ldc0 = L.k4; g.c0_tiled = L.tiled;
-      FFS_TRY(run(g, ACT_NONE, big_m ? 10 : 4, 1));
+      FFS_TRY(run(g, ACT_NONE, big_m ? GEMM_256x128 : GEMM_128x128, 1));
     }
   }
   // G4: [h1 | t2] * [W2h ; Q2] -> Y   (one fp32 accumulation, one rounding: Eq. 2's sum)
@@ -358,7 +358,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     g.Bt = sp + L.off_b4 + koff_bytes(koff); g.ldb = L.k4;
     g.M = M; g.N = dm; g.K = klen;
     g.split_col = dm; g.C0 = out; g.ldc0 = dm; g.n_store = dm;
-    return run(g, ACT_NONE, big_m ? 12 : 4, 1);
+    return run(g, ACT_NONE, GEMM_128x128, 1);
   };
   if (L.k4 > 0) {
     FFS_TRY(down(Y, 0, L.k4));

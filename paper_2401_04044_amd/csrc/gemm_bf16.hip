@@ -13,12 +13,12 @@
 //     of bank conflicts by construction.
 //   "row-major": ordinary [rows, ld] (the caller's X and Y).
 //
-// Kernel: BM x BN workgroup tile, BK-deep slabs double-buffered in LDS, next
-// slab prefetched into registers during the MFMA phase; each wavefront owns a
-// (BM/WGM) x (BN/WGN) sub-tile of 32x32 MFMA tiles.  The MFMA is issued with the
-// weights as the first operand so that a lane ends up with 4 consecutive output
-// columns of one row; one v_permlane32_swap turns that into 8 consecutive
-// columns = one 16-byte chunk of the tiled (or row-major) output.
+// Kernel: BM x BN workgroup tile; BK-deep slabs go from global memory straight into a ring of
+// LDS stages (global_load_lds_dwordx4, one 1 KiB operand block per wavefront instruction);
+// each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 32x32 MFMA tiles.  The MFMA is issued
+// with the weights as the first operand so that a lane ends up with 4 consecutive output
+// columns of one row; one v_permlane32_swap turns that into 8 consecutive columns = one
+// 16-byte chunk of the tiled (or row-major) output.
 //
 // Epilogues: plain / GeLU / SwiGLU (on (gate, up) pairs of 32-column blocks)
 // with two output destinations, fp32 split-K partials, and the neuron-norm
@@ -195,172 +195,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
       }
     }
   }
-}
-
-template <int BM, int BN, int BK, int WGM, int WGN, int PF, int ACT, bool DUAL, bool SCORE, bool A_TILED>
-__global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) gemm_bf16_kernel(const GemmArgs p) {
-  constexpr int NT = WGM * WGN * 64;
-  constexpr int WM = BM / WGM, WN = BN / WGN;
-  constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int NA = DUAL ? 2 : 1;
-  constexpr int KB = BK / 16;                  // k blocks per slab
-  constexpr int A_CH = BM / 32 * KB * 64;      // 16-byte chunks of one A slab
-  constexpr int B_CH = BN / 32 * KB * 64;
-  constexpr int CA = A_CH / NT, CB = B_CH / NT;
-  constexpr int STAGE = NA * A_CH + B_CH;      // chunks per stage
-  constexpr bool SWAP = !SCORE;
-  static_assert(A_CH % NT == 0 && B_CH % NT == 0, "slab must divide over the threads");
-  static_assert(ACT != ACT_GLU || (TN % 2 == 0), "GLU needs paired column blocks per wave");
-
-  extern __shared__ u32x4_t smem[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int tiles_n = (p.N + BN - 1) / BN;
-  const int tiles_m = (p.M + BM - 1) / BM;
-  const int logical = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  // row tiles are walked in groups of p.group_m so that the tiles an XCD works on at
-  // one time form a compact 2-D block (operands shared through its L2)
-  const int gsz = p.group_m * tiles_n;
-  const int first_m = (logical / gsz) * p.group_m;
-  const int gm = min(tiles_m - first_m, p.group_m);
-  const int tm = first_m + (logical % gsz) % gm, tn = (logical % gsz) / gm;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  // K range of this split (multiples of BK)
-  const int kt_total = (p.K + BK - 1) / BK;
-  const int kt_per = (kt_total + (int)gridDim.y - 1) / (int)gridDim.y;
-  const int kt0 = blockIdx.y * kt_per;
-  const int kt1 = min(kt_total, kt0 + kt_per);
-
-  const char* Aptr[NA] = {(const char*)p.A};
-  if (DUAL) Aptr[NA - 1] = (const char*)p.A1;
-
-  // ---- per-thread source addresses and LDS slots
-  const char* a_src[NA][CA];
-  const char* b_src[CB];
-  int a_dst[CA];
-  int a_kc[CA];  // row-major: k offset (elements) of the chunk inside the slab
-  const int mrb_last = (p.M + 31) / 32 - 1;  // last valid row block of a tiled A
-#pragma unroll
-  for (int i = 0; i < CA; ++i) {
-    const int u = tid + i * NT;
-    if (A_TILED) {
-      // chunk u of the slab: row block u / (KB*64), then contiguous
-      const int rb = u / (KB * 64), rest = u % (KB * 64);
-      int grb = m0 / 32 + rb;
-      grb = grb <= mrb_last ? grb : mrb_last;
-#pragma unroll
-      for (int s = 0; s < NA; ++s)
-        a_src[s][i] = Aptr[s] + ((int64_t)grb * (p.lda / 16) * 64 + rest) * 16;
-      a_dst[i] = u;
-      a_kc[i] = 0;
-    } else {
-      // coalesced rows: 8 lanes x 8 rows per 16-byte column of chunks
-      constexpr int CPR = BK / 8;  // chunks per row
-      const int r8 = u & 7, ch = (u >> 3) % CPR, rg = u / (8 * CPR);
-      const int row = rg * 8 + r8;
-      int g = m0 + row;
-      g = g < p.M ? g : p.M - 1;
-#pragma unroll
-      for (int s = 0; s < NA; ++s) a_src[s][i] = Aptr[s] + ((int64_t)g * p.lda + ch * 8) * 2;
-      a_dst[i] = ((row >> 5) * KB + (ch >> 1)) * 64 + (ch & 1) * 32 + (row & 31);
-      a_kc[i] = ch * 8;
-    }
-  }
-  const int nrb_last = (p.N + 31) / 32 - 1;
-#pragma unroll
-  for (int i = 0; i < CB; ++i) {
-    const int u = tid + i * NT;
-    const int rb = u / (KB * 64), rest = u % (KB * 64);
-    int grb = n0 / 32 + rb;
-    grb = grb <= nrb_last ? grb : nrb_last;
-    b_src[i] = (const char*)p.Bt + ((int64_t)grb * (p.ldb / 16) * 64 + rest) * 16;
-  }
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  // PF register sets hold the slabs in flight from global memory (slab s lives in set
-  // (s - kt0) % PF); LDS is double-buffered.
-  u32x4_t ra[PF][NA][CA], rb_[PF][CB];
-
-  auto load_global = [&](int kt, int set) {
-    const int64_t a_off = A_TILED ? (int64_t)kt * KB * 1024 : (int64_t)kt * BK * 2;
-    const int64_t b_off = (int64_t)kt * KB * 1024;
-#pragma unroll
-    for (int s = 0; s < NA; ++s)
-#pragma unroll
-      for (int i = 0; i < CA; ++i) {
-        if (A_TILED) ra[set][s][i] = *(const u32x4_t*)(a_src[s][i] + a_off);
-        else ra[set][s][i] = (kt * BK + a_kc[i]) < p.K ? *(const u32x4_t*)(a_src[s][i] + a_off) : u32x4_t{0, 0, 0, 0};
-      }
-#pragma unroll
-    for (int i = 0; i < CB; ++i) rb_[set][i] = *(const u32x4_t*)(b_src[i] + b_off);
-  };
-  auto store_lds = [&](int buf, int set) {
-    u32x4_t* sA = smem + buf * STAGE;
-    u32x4_t* sB = sA + NA * A_CH;
-#pragma unroll
-    for (int s = 0; s < NA; ++s)
-#pragma unroll
-      for (int i = 0; i < CA; ++i) sA[s * A_CH + a_dst[i]] = ra[set][s][i];
-#pragma unroll
-    for (int i = 0; i < CB; ++i) sB[tid + i * NT] = rb_[set][i];
-  };
-
-#pragma unroll
-  for (int j = 0; j < PF; ++j)
-    if (kt0 + j < kt1) load_global(kt0 + j, j);
-  if (kt0 < kt1) {
-    store_lds(0, 0);
-    if (kt0 + PF < kt1) load_global(kt0 + PF, 0);
-  }
-  __syncthreads();
-
-  for (int ktb = kt0; ktb < kt1; ktb += PF) {
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-      const int kt = ktb + j;
-      if (kt >= kt1) break;
-      const int cur = (kt - kt0) & 1;
-      const u32x4_t* sA = smem + cur * STAGE;
-      const u32x4_t* sB = sA + NA * A_CH;
-#pragma unroll
-      for (int ks = 0; ks < KB; ++ks) {
-        Frag a[NA][TM], b[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int s = 0; s < NA; ++s) a[s][i].u = sA[s * A_CH + ((wm * TM + i) * KB + ks) * 64 + lane];
-#pragma unroll
-        for (int jj = 0; jj < TN; ++jj) b[jj].u = sB[((wn * TN + jj) * KB + ks) * 64 + lane];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int jj = 0; jj < TN; ++jj) {
-            const Frag& af = a[DUAL ? (jj & 1) : 0][i];
-            if (SWAP)
-              acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[jj].v, af.v, acc[i][jj], 0, 0, 0);
-            else
-              acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, b[jj].v, acc[i][jj], 0, 0, 0);
-          }
-      }
-      if (kt + 1 < kt1) {
-        const int set = (j + 1) % PF;
-        store_lds(cur ^ 1, set);
-        if (kt + 1 + PF < kt1) load_global(kt + 1 + PF, set);
-      }
-      __syncthreads();
-    }
-  }
-
-  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE>(p, acc, m0, n0, tm, wm, wn, lane, tid, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -744,76 +578,23 @@ static int launch_dl_shape(const GemmArgs& a, int act, int n_split, hipStream_t 
   return -1;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int PF, int ACT, bool DUAL, bool SCORE, bool A_TILED>
-static int launch_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
-  constexpr int NA = DUAL ? 2 : 1;
-  constexpr size_t lds = (size_t)2 * (NA * BM + BN) * BK * 2;
-  auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, PF, ACT, DUAL, SCORE, A_TILED>;
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return -1;
-    configured = true;
-  }
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * 64), lds, st, a);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
-}
+int bf16_score_tile_m() { return 256; }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int PF>
-static int launch_shape(const GemmArgs& a, int act, bool score, int n_split, hipStream_t st) {
-  const bool dual = a.A1 != nullptr;
-  const bool at = a.a_tiled != 0;
-  if (score) {
-    if constexpr (BM == 128 && BN == 128 && PF == 1 && BK == 64) {
-      if (at) return -1;
-      if (act == ACT_GELU) return launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GELU, false, true, false>(a, 1, st);
-      if (act == ACT_GLU) return launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, false, true, false>(a, 1, st);
-    }
-    return -1;
-  }
-  if (act == ACT_NONE)
-    return at ? launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_NONE, false, false, true>(a, n_split, st)
-              : launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_NONE, false, false, false>(a, n_split, st);
-  if (act == ACT_GELU)
-    return at ? launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GELU, false, false, true>(a, 1, st)
-              : launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GELU, false, false, false>(a, 1, st);
-  if (act == ACT_GLU && !dual)
-    return at ? launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, false, false, true>(a, 1, st)
-              : launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, false, false, false>(a, 1, st);
-  if (act == ACT_GLU && dual && at) return launch_cfg<BM, BN, BK, WGM, WGN, PF, ACT_GLU, true, false, true>(a, 1, st);
-  return -1;
-}
-
-int bf16_score_tile_m() { return 128; }
-
-// shape: 0 = 128x128 tile (small / skinny problems), 1 = 256x128 tile
 int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_split, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return 0;
-  if (score) return launch_shape<128, 128, 64, 2, 2, 1>(a, act, score, n_split, st);
+  if (score) {
+    // calibration: row-major tokens, column sums of the activations in the epilogue
+    if (a.a_tiled) return -1;
+    if (act == ACT_GELU) return launch_dl_cfg<256, 128, 32, 2, 2, 1, 3, ACT_GELU, false, true, false>(a, 1, st);
+    if (act == ACT_GLU) return launch_dl_cfg<256, 128, 32, 2, 2, 1, 3, ACT_GLU, false, true, false>(a, 1, st);
+    return -1;
+  }
   switch (shape) {
-    case 0: return launch_shape<128, 128, 64, 2, 2, 1>(a, act, score, n_split, st);
-    case 1: return launch_shape<256, 128, 32, 2, 2, 1>(a, act, score, n_split, st);
-    case 2: return launch_shape<256, 256, 64, 2, 4, 1>(a, act, score, n_split, st);
-    case 3: return launch_shape<256, 256, 32, 2, 4, 1>(a, act, score, n_split, st);
-    case 4: return launch_shape<128, 128, 64, 2, 2, 2>(a, act, score, n_split, st);
-    case 5: return launch_shape<256, 128, 32, 2, 2, 2>(a, act, score, n_split, st);
-    case 6: return launch_shape<256, 128, 32, 2, 2, 3>(a, act, score, n_split, st);
-    case 7: return launch_shape<256, 256, 32, 2, 4, 2>(a, act, score, n_split, st);
-    case 8: return launch_shape<256, 256, 32, 2, 4, 3>(a, act, score, n_split, st);
-    case 9: return launch_shape<128, 128, 32, 2, 2, 3>(a, act, score, n_split, st);
-    case 10: return launch_dl_shape<256, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
-    case 11: return launch_dl_shape<256, 256, 32, 2, 4, 1, 4>(a, act, n_split, st);
-    case 12: return launch_dl_shape<128, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
-    case 13: return launch_dl_shape<128, 128, 32, 2, 2, 1, 4>(a, act, n_split, st);
-    case 14: return launch_dl_shape<256, 256, 32, 2, 4, 1, 3>(a, act, n_split, st);
-    case 15: return launch_dl_shape<256, 128, 32, 2, 2, 2, 5>(a, act, n_split, st);
-    case 16: return launch_dl_shape<128, 128, 32, 2, 2, 2, 8>(a, act, n_split, st);
-    case 17: return launch_dl_shape<128, 128, 64, 2, 2, 2, 4>(a, act, n_split, st);
-    case 18: return launch_dl_shape<256, 128, 64, 2, 2, 2, 3>(a, act, n_split, st);
-    case 19: return launch_dl_shape<128, 128, 32, 2, 2, 1, 8>(a, act, n_split, st);
-    case 20: return launch_dl_shape<256, 128, 32, 2, 2, 1, 6>(a, act, n_split, st);
-    case 21: return launch_dl_shape<128, 128, 32, 2, 2, 1, 6>(a, act, n_split, st);
+    case GEMM_256x128: return launch_dl_shape<256, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
+    case GEMM_128x128: return launch_dl_shape<128, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
+    case GEMM_128x128_DEEP: return launch_dl_shape<128, 128, 32, 2, 2, 1, 4>(a, act, n_split, st);
+    case GEMM_128x128_KSPLIT: return launch_dl_shape<128, 128, 64, 2, 2, 2, 4>(a, act, n_split, st);
+    case GEMM_256x256: return launch_dl_shape<256, 256, 32, 2, 4, 1, 3>(a, act, n_split, st);
   }
   return -1;
 }

@@ -90,7 +90,7 @@ inline ScoreWs make_score_ws(const ffsplit_desc_t& d, int64_t T) {
   ScoreWs w = {};
   const int n_up = d.act == FFSPLIT_ACT_SWIGLU ? 2 : 1;
   const int esz = d.dtype == FFSPLIT_BF16 ? 2 : 4;
-  const int tile_m = d.dtype == FFSPLIT_BF16 ? 128 : 64;
+  const int tile_m = d.dtype == FFSPLIT_BF16 ? 256 : 64;
   w.n_out = round_up(d.d_ff, 64);
   w.n_gemm = n_up * w.n_out;
   w.tiles_m = (int)((T + tile_m - 1) / tile_m);

@@ -142,9 +142,15 @@ __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceAr
   auto sum_block = [&](int b) {
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     const float4* src = (const float4*)p.part + ((int64_t)b * 4 + g) * 64 + lane;
-    for (int sp = 0; sp < p.n_split; ++sp) {
-      const float4 v = src[(int64_t)sp * p.n_rb * 256];
-      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    // eight independent loads at a time, added in range order
+    const int64_t step = (int64_t)p.n_rb * 256;
+    for (int sp = 0; sp < p.n_split; sp += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(sp + u, p.n_split - 1) * step];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (sp + u < p.n_split) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
     }
     return s;
   };
