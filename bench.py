@@ -8,9 +8,11 @@ comes from the library's own score -> select -> build calls (timed once, reporte
 under "pipeline").  Inputs, weights and the packed split are resident in HBM
 before the timed region.  Prints ONE JSON line.
 
-Also measured, as extra keys: the int4 decode of the Llama-2-7B-shaped layer at
-batch 1/4/16 against the HBM roofline (rotating over enough split copies that
-every weight byte comes from HBM, not from the 256 MB last-level cache).
+Also measured, as extra keys, against the HBM roofline (rotating over enough
+split copies that every weight byte comes from HBM, not from the 256 MB
+last-level cache): the int4 decode of the Llama-2-7B-shaped layer at batch
+1/4/16, and the bf16 low-rank decode of the Llama-2-7B-shaped layer (batch
+1/8/32) and of one OPT-13B-shaped layer (batch 16).
 """
 import argparse
 import json
@@ -24,6 +26,9 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK = 2.5e15   # FLOP/s, dense bf16, MI355X datasheet
 HBM_PEAK = 8.0e12         # B/s
+# HBM bytes of one C2 forward (read + written), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/gemm_bf16_chain_C2_prefill.md (scaled by the reference copy there)
+TRAFFIC_C2_PREFILL = 377.1e6   # 267.5 MB read + 109.6 MB written
 
 
 def parse():
@@ -31,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-decode", action="store_true", help="skip the int4 decode section")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--copies", type=int, default=4, help="split copies rotated through in the prefill loop")
     ap.add_argument("--calib-copy", action="store_true",
@@ -50,7 +55,8 @@ def main():
     import torch
     import paper_2401_04044_amd as ff
     import workloads as wl
-    from workloads.configs import C2, C4
+    import dataclasses
+    from workloads.configs import C2, C3, C4, C5
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
@@ -154,9 +160,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": "C2 OPT-1.3B-shaped split FFN prefill: d_model=2048 d_ff=8192 GeLU k=246 rank=512 "
                                "T=8x512=4096, one layer", "split_copies": len(splits)},
-        "roofline": {"bound": "mfma", "kernel": "ffsplit_forward: 4 chained gemm_bf16_kernel launches",
+        "roofline": {"bound": "mfma",
+                     "kernel": "ffsplit_forward = 4 chained gemm_bf16_dl_kernel launches (+ split-K sum); "
+                               "per-launch figures in profiles/",
                      "achieved": flops / t_ev / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
-                     "frac": flops / t_ev / MFMA_BF16_PEAK, "traffic": None,
+                     "frac": flops / t_ev / MFMA_BF16_PEAK, "traffic": TRAFFIC_C2_PREFILL,
                      "flops_per_launch": flops, "us_per_launch_hip_events": t_ev * 1e6},
         "parity": {"rel_frobenius_vs_oracle_32_rows": rel_err, "heavy_set_equals_planted": heavy_ok},
         "pipeline": {"score_us_T4096": t_score * 1e6,
@@ -210,6 +218,41 @@ def main():
                             "frac_hbm": c4.weight_bytes() / t4 / HBM_PEAK}
         out["decode_int4"] = {"workload": "C4 Llama-2-7B-shaped SwiGLU, k=550 bf16 heavy + int4-g128 remainder",
                               "bytes_per_step": c4.weight_bytes(), "split_copies": n_copies, **dec}
+
+
+        # ------------------------------------------------------------ extra: bf16 low-rank decode (HBM-bound)
+        del s4s, s4, ws4
+        torch.cuda.empty_cache()
+        dl = {}
+        for cfg_d, n_cp in ((C3, 10), (C5, 8)):
+            Ld = wl.make_layer(cfg_d)
+            facs = wl.make_factors(dataclasses.replace(cfg_d, exact_svd=False), Ld, Ld["planted"])
+            dd = ff.make_desc(cfg_d.d_model, cfg_d.d_ff, cfg_d.act, cfg_d.dtype, cfg_d.k, "lowrank", cfg_d.rank)
+            spd = ff.build_split(dd, dev(Ld["W1"]), dev(Ld["Wg"]), dev(Ld["W2"]),
+                                 torch.from_numpy(Ld["planted"]).cuda(), {k: dev(v) for k, v in facs.items()})
+            torch.cuda.synchronize()
+            spds = [spd] + [spd.clone() for _ in range(n_cp - 1)]
+            note(f"{cfg_d.name}: split built, {n_cp} copies of {cfg_d.weight_bytes()/1e6:.0f} MB")
+            for B in cfg_d.decode_B:
+                wsd = torch.empty(ff.workspace_bytes(dd, ff.WS_FORWARD, B), dtype=torch.uint8, device="cuda")
+                xb = dev(wl.make_tokens(cfg_d, B))
+                yb = torch.empty((B, cfg_d.d_model), dtype=bf, device="cuda")
+                st = {"i": 0}
+
+                def lstep():
+                    ff.forward(dd, spds[st["i"] % n_cp], xb, yb, False, wsd)
+                    st["i"] += 1
+
+                td, _ = timed(lstep, 100, 20)
+                note(f"{cfg_d.name} low-rank decode B={B}: {td*1e6:.1f} us")
+                dl[f"{cfg_d.name.split('-')[0]}_B{B}"] = {
+                    "us": td * 1e6, "tokens_per_s": B / td, "bytes_per_step": cfg_d.weight_bytes(),
+                    "GBps": cfg_d.weight_bytes() / td / 1e9, "frac_hbm": cfg_d.weight_bytes() / td / HBM_PEAK}
+            del spds, spd
+            torch.cuda.empty_cache()
+        out["decode_lowrank_bf16"] = {"workload": "C3 Llama-2-7B-shaped (k=550, rank 1024) and one C5 OPT-13B-shaped "
+                                                  "layer (k=819, rank 1280): heavy bf16 + low-rank factors, seeded "
+                                                  "Gaussian factors", **dl}
 
     print(json.dumps(out))
 
