@@ -344,7 +344,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     if (bf16 && w.g3_split > 1 && !small_m) {
       float* part = (float*)(ws + w.off_kpart);
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
-      FFS_TRY(run(g, ACT_NONE, big_m ? GEMM_128x128_KSPLIT : GEMM_128x128, w.g3_split));
+      FFS_TRY(run(g, ACT_NONE, big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128, w.g3_split));
       FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, 1, st));
     } else {
       g.C0 = cat + koff_bytes(L.kp); g.ldc0 = L.k4; g.c0_tiled = L.tiled;

@@ -570,9 +570,14 @@ static int launch_dl_shape(const GemmArgs& a, int act, int n_split, hipStream_t 
     if (act == ACT_GLU && !dual)
       return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, false, false, true>(a, 1, st)
                 : launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, false, false, false>(a, 1, st);
-    if constexpr ((size_t)STAGES * (2 * BM + BN) * BK * 2 <= 160 * 1024 && (2 * (BM / 32) * (BK / 16)) % (WGM * WGN * KG) == 0) {
-      if (act == ACT_GLU && dual && at)
-        return launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, true, false, true>(a, 1, st);
+    if constexpr ((2 * (BM / 32) * (BK / 16)) % (WGM * WGN * KG) == 0) {
+      // two left operands double the A part of a stage: fewer stages where that keeps two
+      // workgroups per CU (80 KiB each)
+      constexpr int DST = ((size_t)STAGES * (2 * BM + BN) * BK * 2 > 80 * 1024 && STAGES > 2) ? 2 : STAGES;
+      if constexpr ((size_t)DST * (2 * BM + BN) * BK * 2 <= 160 * 1024) {
+        if (act == ACT_GLU && dual && at)
+          return launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, DST, ACT_GLU, true, false, true>(a, 1, st);
+      }
     }
   }
   return -1;

@@ -822,11 +822,27 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   w.g3_split = 1;
   w.off_kpart = off;
   if (L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
-    // split the long reduction of h2 * P2 (128x128 tiles) until about one workgroup per CU exists
-    // (more splits cost more partial-sum traffic than they gain: measured)
-    const int tiles = (int)((T + 127) / 128) * ((L.rp + 127) / 128);
-    int sp = 256 / (tiles > 0 ? tiles : 1);
+    // Split the long reduction of h2 * P2 across workgroups (more splits cost more partial-sum
+    // traffic than they gain: measured).  Narrow products (rank <= 512 at 4096 rows) use 128x128
+    // tiles with the in-workgroup K split, one workgroup per CU; wider ones use 256x128 tiles,
+    // two workgroups per CU, with the number of splits that fills the 512 slots best.
+    const int tiles128 = (int)((T + 127) / 128) * ((L.rp + 127) / 128);
     const int max_sp = L.mp / 512 > 0 ? L.mp / 512 : 1;   // keep >= 8 slabs of 64 per split
+    int sp;
+    if (tiles128 <= 128 || T <= 1024) {
+      w.g3_wide = 0;
+      sp = 256 / (tiles128 > 0 ? tiles128 : 1);
+    } else {
+      w.g3_wide = 1;
+      const int tiles256 = (int)((T + 255) / 256) * ((L.rp + 127) / 128);
+      sp = 1;
+      double best = 0.0;
+      for (int c = 1; c <= 8; ++c) {
+        const int wgs = tiles256 * c;
+        const double fill = (double)wgs / (512.0 * ((wgs + 511) / 512));
+        if (fill > best + 0.03) { best = fill; sp = c; }
+      }
+    }
     if (sp > max_sp) sp = max_sp;
     if (sp > 16) sp = 16;
     if (sp < 1) sp = 1;

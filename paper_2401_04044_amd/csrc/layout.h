@@ -108,6 +108,7 @@ struct FwdWs {
   size_t off_cat, off_t, off_h2, off_kpart;
   int t_pad;       // rows of the intermediates (T, padded to 32 when tiled)
   int g3_split;    // split-K factor of the h2 * P2 product
+  int g3_wide;     // that product has enough tiles for 256x128 tiles (else: in-workgroup K split)
   // INT4 decode scratch
   size_t off_h, off_part, off_cnt;
   int n_split;
