@@ -124,6 +124,13 @@ FWD_CASES = [
     ("c3_reduced_swiglu_f32", f32_variant(reduced(C3, 64, 200, rank=16)), 70),
     ("c5_reduced", reduced(C5, 128, 520, rank=40), 65),
     ("single_token", reduced(C3, 128, 300, rank=32), 1),
+    # at most 32 rows: the weight-streaming small-batch kernels (and the first size past them)
+    ("small_batch_gelu_5", reduced(C2, 320, 1111, rank=72), 5),
+    ("small_batch_gelu_32", reduced(C5, 256, 1000, rank=64), 32),
+    ("small_batch_gelu_33", reduced(C5, 256, 1000, rank=64), 33),
+    ("small_batch_swiglu_8", reduced(C3, 192, 700, rank=64), 8),
+    ("small_batch_swiglu_31", reduced(C3, 328, 1500, rank=40), 31),
+    ("small_batch_long_k", reduced(C5, 128, 9000, rank=48), 3),
     # more than 1024 rows: 256-row tiles, split-K of the long reduction, dual-operand SwiGLU
     ("c2_reduced_tall", reduced(C2, 256, 2100, rank=128), 1300),
     ("c3_reduced_tall", reduced(C3, 192, 1500, rank=64), 1059),
@@ -251,3 +258,33 @@ def test_int4_edge_sets(ff):
         torch.cuda.synchronize()
         want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=128)
         assert relf(host(Y), want[0]) < TOL["bf16"]
+
+
+# ---------------------------------------------------------------- deleting neurons (Sec. 4.1)
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_deleting_neurons_leaves_the_scored_residual(ff, act):
+    """Forward with a set S of neurons dropped (heavy = all the others, remainder NONE): the
+    squared residual against the full layer is the score of Eq. 3 for a single neuron, and for
+    a larger set it is the norm of the set's own output (cross terms included), which the
+    oracle gives by evaluating only S."""
+    base = reduced(C3 if act == "swiglu" else C2, 96, 160, rank=16)
+    cfg = f32_variant(base)
+    L = wl.make_layer(cfg)
+    T = 40
+    X = wl.make_tokens(cfg, T)
+    Ld = layer_to_dev(L, cfg.dtype)
+    scores, _, _ = gpu_scores(ff, desc_for(ff, cfg, "none"), Ld, [dev(X, cfg.dtype)], 0)
+    scores = scores.cpu().numpy().astype(np.float64)
+    everything = np.arange(cfg.d_ff, dtype=np.int32)
+    full, _ = run_forward(ff, cfg, L, everything, T, "none", X=X)
+    planted = int(L["planted"][0])
+    for S in ([planted], [3], [3, planted, 77], list(range(10, 50))):
+        keep = np.setdiff1d(everything, np.asarray(S, np.int32)).astype(np.int32)
+        less, want_less = run_forward(ff, cfg, L, keep, T, "none", X=X)
+        assert relf(less[0], want_less[0]) < TOL["f32"]
+        res = float(np.sum((full[0] - less[0]) ** 2))
+        only_s = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], np.asarray(S, np.int32), cfg.act, "none", None)[0]
+        assert res == pytest.approx(float(np.sum(only_s ** 2)), rel=2e-3)
+        if len(S) == 1:
+            assert res == pytest.approx(scores[S[0]], rel=2e-3)
