@@ -42,6 +42,101 @@ inline int act_of(const ffsplit_desc_t* d) { return d->act == FFSPLIT_ACT_SWIGLU
 
 }  // namespace
 
+// The chained products of one forward call for the NONE / DENSE / LOWRANK layouts (sp: packed
+// split, ws: scratch laid out by w).  Also the large-batch path of the int4 remainder, which
+// first expands its weights to a DENSE image.
+static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& w, const char* sp, const void* X, int M,
+                         void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st) {
+  const int bf16 = d->dtype == FFSPLIT_BF16;
+  const int esz = bf16 ? 2 : 4;
+  const int act = act_of(d);
+  const bool glu = act == ACT_GLU;
+  const int dm = d->d_model, k = d->k, m = d->d_ff - d->k;
+  char* cat = ws + w.off_cat;    // [T, k4]  = [h1 | t2] (or [h1 | h_rest] for DENSE)
+  char* tbuf = ws + w.off_t;     // [T, n_up*rp]
+  char* h2 = ws + w.off_h2;      // [T, mp]
+  const bool rem_lr = d->rem_kind == FFSPLIT_REM_LOWRANK && m > 0;
+  const bool rem_dense = d->rem_kind == FFSPLIT_REM_DENSE && m > 0;
+  // Column offset inside a K-contiguous buffer: elements (row-major) or whole 16-wide
+  // k blocks of 1 KiB (tiled).
+  auto koff_bytes = [&](int koff) -> size_t { return L.tiled ? (size_t)(koff / 16) * 1024 : (size_t)koff * esz; };
+  // batches of at most 32 rows are bound by streaming the weights: dedicated kernels
+  const bool small_m = bf16 && M <= 32;
+  auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
+    if (g.group_m <= 0) g.group_m = 8;
+    g.m_pad = w.t_pad;
+    if (!bf16) return launch_gemm_f32(g, a, false, st);
+    if (small_m && !g.partial && (g.N & 31) == 0) return launch_skinny_bf16(g, a, (float*)(ws + w.off_kpart), st);
+    return launch_gemm_bf16(g, a, false, shape, n_split, st);
+  };
+  const int big_m = M > 1024;   // 256-row tiles only pay off with enough rows
+
+  // G1: X * [W1h | P1] (SwiGLU: [gate/up heavy pairs | Pg | P1]) -> h1 (activated) and t
+  if (L.n1 > 0) {
+    GemmArgs g = {};
+    g.A = X; g.lda = dm; g.Bt = sp + L.off_b1; g.ldb = L.dk;
+    g.M = M; g.N = L.n1; g.K = dm;
+    const int acted = rem_dense ? (L.kp + L.mp) : L.kp;   // neurons activated in this product
+    g.act_cols = L.n_up * acted;
+    g.split_col = acted;
+    g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
+    g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
+    g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
+    FFS_TRY(run(g, act, big_m ? (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_DEEP) : GEMM_128x128, 1));
+  }
+  if (rem_lr) {
+    // G2: t * Q1 -> activation -> h2
+    GemmArgs g = {};
+    g.A = tbuf; g.lda = (int64_t)L.n_up * L.rp; g.a_tiled = L.tiled;
+    if (glu) g.A1 = tbuf + koff_bytes(L.rp);
+    g.Bt = sp + L.off_q1; g.ldb = L.rp;
+    g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
+    g.act_cols = g.N; g.split_col = L.mp;
+    g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
+    FFS_TRY(run(g, act, big_m ? GEMM_256x128 : GEMM_128x128, 1));
+    // G3: h2 * P2 -> t2 into cat[:, kp:]  (long reduction: split-K, fixed-order sum)
+    g = {};
+    g.A = h2; g.lda = L.mp; g.a_tiled = L.tiled;
+    g.Bt = sp + L.off_p2; g.ldb = L.mp;
+    g.M = M; g.N = L.rp; g.K = L.mp;
+    g.split_col = L.rp;
+    g.group_m = 1;   // h2 is the large operand
+    if (bf16 && w.g3_split > 1 && !small_m) {
+      float* part = (float*)(ws + w.off_kpart);
+      g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
+      FFS_TRY(run(g, ACT_NONE, big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128, w.g3_split));
+      FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, 1, st));
+    } else {
+      g.C0 = cat + koff_bytes(L.kp); g.ldc0 = L.k4; g.c0_tiled = L.tiled;
+      FFS_TRY(run(g, ACT_NONE, big_m ? GEMM_256x128 : GEMM_128x128, 1));
+    }
+  }
+  // G4: [h1 | t2] * [W2h ; Q2] -> Y   (one fp32 accumulation, one rounding: Eq. 2's sum)
+  auto down = [&](void* out, int koff, int klen) -> int {
+    GemmArgs g = {};
+    g.A = cat + koff_bytes(koff); g.lda = L.k4; g.a_tiled = L.tiled;
+    g.Bt = sp + L.off_b4 + koff_bytes(koff); g.ldb = L.k4;
+    g.M = M; g.N = dm; g.K = klen;
+    g.split_col = dm; g.C0 = out; g.ldc0 = dm; g.n_store = dm;
+    return run(g, ACT_NONE, GEMM_128x128, 1);
+  };
+  if (L.k4 > 0) {
+    FFS_TRY(down(Y, 0, L.k4));
+  } else {
+    FFS_TRY(launch_fill_zero(Y, (size_t)M * dm * esz, st));
+  }
+  if (Y_heavy) {
+    if (L.kp > 0) FFS_TRY(down(Y_heavy, 0, L.kp));
+    else FFS_TRY(launch_fill_zero(Y_heavy, (size_t)M * dm * esz, st));
+  }
+  if (Y_rem) {
+    if (L.k4 > L.kp) FFS_TRY(down(Y_rem, L.kp, L.k4 - L.kp));
+    else FFS_TRY(launch_fill_zero(Y_rem, (size_t)M * dm * esz, st));
+  }
+  (void)k;
+  return FFSPLIT_OK;
+}
+
 extern "C" {
 
 const char* ffsplit_status_string(int s) {
@@ -279,102 +374,23 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   if (!workspace || workspace_bytes < w.total_bytes) return FFSPLIT_E_WORKSPACE;
   if ((uintptr_t)workspace & 255u) return FFSPLIT_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
-  const int bf16 = d->dtype == FFSPLIT_BF16;
-  const int esz = bf16 ? 2 : 4;
-  const int act = act_of(d);
-  const bool glu = act == ACT_GLU;
-  const int dm = d->d_model, k = d->k, m = d->d_ff - d->k;
   const char* sp = (const char*)split;
   char* ws = (char*)workspace;
-  char* cat = ws + w.off_cat;    // [T, k4]  = [h1 | t2] (or [h1 | h_rest] for DENSE)
-  char* tbuf = ws + w.off_t;     // [T, n_up*rp]
-  char* h2 = ws + w.off_h2;      // [T, mp]
   const int M = (int)T;
-  const bool rem_lr = d->rem_kind == FFSPLIT_REM_LOWRANK && m > 0;
-  const bool rem_dense = d->rem_kind == FFSPLIT_REM_DENSE && m > 0;
   if (d->rem_kind == FFSPLIT_REM_INT4) {
+    if (w.i4_prefill) {
+      // many tokens: expand the int4 remainder to bf16 once, then the dense chain on MFMA tiles
+      ffsplit_desc_t dd = *d;
+      dd.rem_kind = FFSPLIT_REM_DENSE;
+      const Layout LD = make_layout(dd);
+      const FwdWs wd = make_fwd_ws(dd, LD, T);
+      FFS_TRY(launch_int4_expand(*d, L, LD, sp, ws + w.off_img, st));
+      return forward_chain(&dd, LD, wd, ws + w.off_img, X, M, Y, Y_heavy, Y_rem, ws + w.off_dense, st);
+    }
     const int r4 = int4_forward(*d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st);
     return r4 == 0 ? FFSPLIT_OK : (r4 == -2 ? FFSPLIT_E_UNSUPPORTED : FFSPLIT_E_HIP);
   }
-
-  // Column offset inside a K-contiguous buffer: elements (row-major) or whole 16-wide
-  // k blocks of 1 KiB (tiled).
-  auto koff_bytes = [&](int koff) -> size_t { return L.tiled ? (size_t)(koff / 16) * 1024 : (size_t)koff * esz; };
-  // batches of at most 32 rows are bound by streaming the weights: dedicated kernels
-  const bool small_m = bf16 && M <= 32;
-  auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
-    if (g.group_m <= 0) g.group_m = 8;
-    g.m_pad = w.t_pad;
-    if (!bf16) return launch_gemm_f32(g, a, false, st);
-    if (small_m && !g.partial && (g.N & 31) == 0) return launch_skinny_bf16(g, a, (float*)(ws + w.off_kpart), st);
-    return launch_gemm_bf16(g, a, false, shape, n_split, st);
-  };
-  const int big_m = M > 1024;   // 256-row tiles only pay off with enough rows
-
-  // G1: X * [W1h | P1] (SwiGLU: [gate/up heavy pairs | Pg | P1]) -> h1 (activated) and t
-  if (L.n1 > 0) {
-    GemmArgs g = {};
-    g.A = X; g.lda = dm; g.Bt = sp + L.off_b1; g.ldb = L.dk;
-    g.M = M; g.N = L.n1; g.K = dm;
-    const int acted = rem_dense ? (L.kp + L.mp) : L.kp;   // neurons activated in this product
-    g.act_cols = L.n_up * acted;
-    g.split_col = acted;
-    g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
-    g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
-    g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
-    FFS_TRY(run(g, act, big_m ? (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_DEEP) : GEMM_128x128, 1));
-  }
-  if (rem_lr) {
-    // G2: t * Q1 -> activation -> h2
-    GemmArgs g = {};
-    g.A = tbuf; g.lda = (int64_t)L.n_up * L.rp; g.a_tiled = L.tiled;
-    if (glu) g.A1 = tbuf + koff_bytes(L.rp);
-    g.Bt = sp + L.off_q1; g.ldb = L.rp;
-    g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
-    g.act_cols = g.N; g.split_col = L.mp;
-    g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
-    FFS_TRY(run(g, act, big_m ? GEMM_256x128 : GEMM_128x128, 1));
-    // G3: h2 * P2 -> t2 into cat[:, kp:]  (long reduction: split-K, fixed-order sum)
-    g = {};
-    g.A = h2; g.lda = L.mp; g.a_tiled = L.tiled;
-    g.Bt = sp + L.off_p2; g.ldb = L.mp;
-    g.M = M; g.N = L.rp; g.K = L.mp;
-    g.split_col = L.rp;
-    g.group_m = 1;   // h2 is the large operand
-    if (bf16 && w.g3_split > 1 && !small_m) {
-      float* part = (float*)(ws + w.off_kpart);
-      g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
-      FFS_TRY(run(g, ACT_NONE, big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128, w.g3_split));
-      FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, 1, st));
-    } else {
-      g.C0 = cat + koff_bytes(L.kp); g.ldc0 = L.k4; g.c0_tiled = L.tiled;
-      FFS_TRY(run(g, ACT_NONE, big_m ? GEMM_256x128 : GEMM_128x128, 1));
-    }
-  }
-  // G4: [h1 | t2] * [W2h ; Q2] -> Y   (one fp32 accumulation, one rounding: Eq. 2's sum)
-  auto down = [&](void* out, int koff, int klen) -> int {
-    GemmArgs g = {};
-    g.A = cat + koff_bytes(koff); g.lda = L.k4; g.a_tiled = L.tiled;
-    g.Bt = sp + L.off_b4 + koff_bytes(koff); g.ldb = L.k4;
-    g.M = M; g.N = dm; g.K = klen;
-    g.split_col = dm; g.C0 = out; g.ldc0 = dm; g.n_store = dm;
-    return run(g, ACT_NONE, GEMM_128x128, 1);
-  };
-  if (L.k4 > 0) {
-    FFS_TRY(down(Y, 0, L.k4));
-  } else {
-    FFS_TRY(launch_fill_zero(Y, (size_t)M * dm * esz, st));
-  }
-  if (Y_heavy) {
-    if (L.kp > 0) FFS_TRY(down(Y_heavy, 0, L.kp));
-    else FFS_TRY(launch_fill_zero(Y_heavy, (size_t)M * dm * esz, st));
-  }
-  if (Y_rem) {
-    if (L.k4 > L.kp) FFS_TRY(down(Y_rem, L.kp, L.k4 - L.kp));
-    else FFS_TRY(launch_fill_zero(Y_rem, (size_t)M * dm * esz, st));
-  }
-  (void)k;
-  return FFSPLIT_OK;
+  return forward_chain(d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st);
 }
 
 int ffsplit_split_export(const ffsplit_desc_t* d, const void* split, int32_t what, int8_t* q_out, uint16_t* s_out,

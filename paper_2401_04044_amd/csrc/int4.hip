@@ -790,6 +790,126 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
   FFS_TR(10);
 }
 
+// ---------------------------------------------------------------- expansion for large batches
+
+struct ExpandArgs {
+  const u32x4_t* hv[3];      // heavy bf16 blocks: up, gate, down
+  const uint32_t* nib[3];    // int4 codes
+  const uint16_t* sc[3];     // fp16 group scales
+  int n_up, G, d;
+  int kp16, kp128, jp16, jp128;   // padded counts of the int4 layout
+  int kpD, mpD, k4D;              // padded counts of the DENSE layout
+  int64_t n_chunks;
+  u32x4_t* out;
+};
+
+// eight codes of one dword (element e = 2 i in nibble i, e = 2 i + 1 in nibble 4 + i) times
+// their scales -> eight bf16
+__device__ __forceinline__ u32x4_t expand8(uint32_t dw, const float* s) {
+  u32x4_t o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = (float)((int)((dw >> (4 * i)) & 15u) - 8) * s[2 * i];
+    const float hi = (float)((int)((dw >> (4 * (4 + i))) & 15u) - 8) * s[2 * i + 1];
+    o[i] = pack_bf16x2(lo, hi);
+  }
+  return o;
+}
+
+// B1t image [n_up (kpD + mpD), d], tiled: one thread per 16-byte chunk (row, 8 inputs)
+__global__ void __launch_bounds__(256) expand_up_kernel(const ExpandArgs a) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= a.n_chunks) return;
+  const int lane = (int)(id & 63);
+  const int64_t blk = id >> 6;
+  const int kbs = a.d / 16;
+  const int rb = (int)(blk / kbs), kb = (int)(blk % kbs);
+  const int row = rb * 32 + (lane & 31), k0 = kb * 16 + 8 * (lane >> 5);
+  const int heavy_rows = a.n_up * a.kpD;
+  const bool heavy = row < heavy_rows;
+  const int rr = heavy ? row : row - heavy_rows;
+  // SwiGLU: 32-row blocks alternate gate / up
+  const int which = a.n_up == 2 ? (((rr >> 5) & 1) ? 0 : 1) : 0;   // index into hv / nib / sc: 0 up, 1 gate
+  const int n = a.n_up == 2 ? ((rr >> 6) * 32 + (rr & 31)) : rr;
+  const int g = k0 >> 7, s = (k0 & 127) >> 5, q = (k0 & 31) >> 3, r16 = n & 15, t16 = n >> 4;
+  u32x4_t o = {0, 0, 0, 0};
+  if (heavy) {
+    if (n < a.kp16) o = a.hv[which][(((int64_t)t16 * a.G + g) * 4 + s) * 64 + q * 16 + r16];
+  } else if (n < a.jp16) {
+    const uint32_t dw = a.nib[which][(((int64_t)t16 * a.G + g) * 64 + q * 16 + r16) * 4 + s];
+    const float sc = half_bits_to_f32(a.sc[which][((int64_t)t16 * a.G + g) * 16 + r16]);
+    const float ss[8] = {sc, sc, sc, sc, sc, sc, sc, sc};
+    o = expand8(dw, ss);
+  }
+  a.out[id] = o;
+}
+
+// B4t image [d, kpD + mpD], tiled: one thread per 16-byte chunk (output c, 8 neurons)
+__global__ void __launch_bounds__(256) expand_down_kernel(const ExpandArgs a) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= a.n_chunks) return;
+  const int lane = (int)(id & 63);
+  const int64_t blk = id >> 6;
+  const int kbs = a.k4D / 16;
+  const int rb = (int)(blk / kbs), kb = (int)(blk % kbs);
+  const int c = rb * 32 + (lane & 31), col0 = kb * 16 + 8 * (lane >> 5);
+  const int cg = c >> 7, ct = (c & 127) >> 4, r16 = c & 15;
+  u32x4_t o = {0, 0, 0, 0};
+  if (c < a.d) {
+    if (col0 < a.kpD) {
+      const int j0 = col0;
+      if (j0 < a.kp128) {
+        const int jb = j0 >> 7, s = (j0 & 127) >> 5, q = (j0 & 31) >> 3;
+        o = a.hv[2][(((((int64_t)cg * (a.kp128 / 128) + jb) * 8 + ct) * 4 + s) * 64) + q * 16 + r16];
+      }
+    } else {
+      const int j0 = col0 - a.kpD;
+      if (j0 < a.jp128) {
+        const int jb = j0 >> 7, s = (j0 & 127) >> 5, q = (j0 & 31) >> 3;
+        const uint32_t dw = a.nib[2][((((int64_t)cg * (a.jp128 / 128) + jb) * 8 + ct) * 64 + q * 16 + r16) * 4 + s];
+        const uint4 sb = *(const uint4*)(a.sc[2] + (int64_t)cg * a.jp128 + j0);
+        const uint32_t sw[4] = {sb.x, sb.y, sb.z, sb.w};
+        float ss[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          ss[2 * i] = half_bits_to_f32((uint16_t)(sw[i] & 0xffffu));
+          ss[2 * i + 1] = half_bits_to_f32((uint16_t)(sw[i] >> 16));
+        }
+        o = expand8(dw, ss);
+      }
+    }
+  }
+  a.out[id] = o;
+}
+
+int launch_int4_expand(const ffsplit_desc_t& d, const Layout& L, const Layout& LD, const char* split, char* image,
+                       hipStream_t st) {
+  if (!LD.tiled || LD.dk != d.d_model || LD.dn != d.d_model) return -1;   // d_model is a multiple of 128 here
+  ExpandArgs a = {};
+  for (int w = 0; w < 3; ++w) {
+    a.hv[w] = (const u32x4_t*)(split + L.off_hv[w]);
+    a.nib[w] = (const uint32_t*)(split + L.off_i4[w]);
+    a.sc[w] = (const uint16_t*)(split + L.off_s4[w]);
+  }
+  a.n_up = L.n_up; a.G = L.groups; a.d = d.d_model;
+  a.kp16 = d.k > 0 ? L.kp : 0; a.kp128 = d.k > 0 ? L.kp128 : 0;
+  a.jp16 = d.d_ff > d.k ? L.jp16 : 0; a.jp128 = d.d_ff > d.k ? L.jp128 : 0;
+  a.kpD = LD.kp; a.mpD = LD.mp; a.k4D = LD.k4;
+  if (LD.n1 > 0) {
+    a.n_chunks = (int64_t)LD.n1 * d.d_model / 8;
+    a.out = (u32x4_t*)(image + LD.off_b1);
+    hipLaunchKernelGGL(expand_up_kernel, dim3((unsigned)((a.n_chunks + 255) / 256)), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return -1;
+  }
+  if (LD.k4 > 0) {
+    a.n_chunks = (int64_t)LD.dn * LD.k4 / 8;
+    a.out = (u32x4_t*)(image + LD.off_b4);
+    hipLaunchKernelGGL(expand_down_kernel, dim3((unsigned)((a.n_chunks + 255) / 256)), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return -1;
+  }
+  return 0;
+}
+
 static int phase2_splits(int G) {
   int S = 256 / (G > 0 ? G : 1);   // about one 8-wave workgroup per CU
   if (S > 16) S = 16;
@@ -799,6 +919,16 @@ static int phase2_splits(int G) {
 
 FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   FwdWs w = {};
+  if (d.rem_kind == FFSPLIT_REM_INT4 && T > INT4_DECODE_MAX_T) {
+    ffsplit_desc_t dd = d;
+    dd.rem_kind = FFSPLIT_REM_DENSE;
+    const Layout LD = make_layout(dd);
+    w.i4_prefill = 1;
+    w.off_img = 0;
+    w.off_dense = align256(LD.total_bytes);
+    w.total_bytes = w.off_dense + make_fwd_ws(dd, LD, T).total_bytes;
+    return w;
+  }
   if (d.rem_kind == FFSPLIT_REM_INT4) {
     const int hl = L.kp128 + L.jp128;
     const int S = phase2_splits(L.groups);

@@ -112,8 +112,16 @@ struct FwdWs {
   // INT4 decode scratch
   size_t off_h, off_part, off_cnt;
   int n_split;
+  // INT4 with many tokens: bf16 image of the split in the DENSE layout, then that chain's scratch
+  int i4_prefill;
+  size_t off_img, off_dense;
   size_t total_bytes;
 };
+
+// INT4 remainder: up to this many tokens take the weight-streaming decode kernels, 16 tokens
+// per pass; beyond it the weights are expanded to bf16 once and the dense chain runs
+// (expanding plus the chain at that size costs about as much as 12 passes).
+constexpr int INT4_DECODE_MAX_T = 192;
 
 inline size_t build_ws_bytes(const ffsplit_desc_t& d) { return align256((size_t)8 * d.d_ff) + 256; }
 

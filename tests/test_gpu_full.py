@@ -144,6 +144,29 @@ def test_c4_llama7b_shape_int4_decode(ff):
             assert e < TOL["bf16"], (B, nm, e)
 
 
+def test_c4_llama7b_shape_int4_many_tokens(ff):
+    """4096 tokens through the int4 split (weights expanded to bf16, dense chain), sampled rows."""
+    cfg = C4
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    idx_h = L["planted"]
+    desc = desc_for(ff, cfg)
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx_h).cuda())
+    del Ld
+    T = 4096
+    X = wl.make_tokens(cfg, T)
+    Y, Yh, Yr = ff.forward(desc, split, dev(X, "bf16"), want_parts=True)
+    torch.cuda.synchronize()
+    rows = sampled_rows(T, 24)
+    sw = orc.split_weights(L["W1"], L["W2"], L["Wg"], idx_h)
+    qw = orc.quantize_remainder(sw, cfg.group)
+    Y1 = orc.forward_heavy(X[rows], sw, "swiglu")
+    Y2 = orc.forward_remainder_int4(X[rows], qw, cfg.group, "swiglu")
+    for g, w, nm in zip((Y, Yh, Yr), (Y1 + Y2, Y1, Y2), ("Y", "Y_heavy", "Y_rem")):
+        e = relf(host(g[torch.from_numpy(rows).cuda()]), w)
+        assert e < TOL["bf16"], (nm, e)
+
+
 def test_c5_opt13b_shape_layers_teacher_forced(ff):
     """Two layers of the 40-layer stack at full width, each fed the oracle's own
     layer input (rounded to bf16): x <- x + FFN_split(n(x)), n = per-token RMS

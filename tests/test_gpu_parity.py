@@ -207,6 +207,9 @@ def test_forward_is_deterministic_and_T0_is_noop(ff):
     a, _ = run_forward(ff, cfg, L, L["planted"], 200, "lowrank", fac)
     b, _ = run_forward(ff, cfg, L, L["planted"], 200, "lowrank", fac)
     assert np.array_equal(a[0], b[0])
+    # small batch: the sum over the ranges of a reduction does not depend on arrival order
+    small = [run_forward(ff, cfg, L, L["planted"], 7, "lowrank", fac)[0][0] for _ in range(4)]
+    assert all(np.array_equal(small[0], s) for s in small[1:])
     desc = desc_for(ff, cfg, "lowrank")
     assert ff.lib.ffsplit_forward(__import__("ctypes").byref(desc), None, None, 0, None, None, None, None, 0, None) == 0
 
@@ -218,6 +221,9 @@ I4_CASES = [
     ("c4_reduced_ragged", reduced(C4, 384, 1000), (3, 16, 21)),
     ("c4_gelu", reduced(C2, 256, 500).__class__(**{**reduced(C2, 256, 500).__dict__, "rem_kind": "int4", "group": 128}), (2,)),
     ("c4_width1024", reduced(C4, 1024, 600), (5,)),
+    # more than 192 tokens: the int4 weights are expanded to bf16 and the dense chain runs
+    ("c4_reduced_many_tokens", reduced(C4, 256, 700), (192, 193, 300)),
+    ("c4_gelu_many_tokens", reduced(C2, 384, 1000).__class__(**{**reduced(C2, 384, 1000).__dict__, "rem_kind": "int4", "group": 128}), (1100,)),
 ]
 
 
@@ -250,14 +256,15 @@ def test_int4_edge_sets(ff):
     cfg = reduced(C4, 256, 300)
     L = wl.make_layer(cfg)
     Ld = layer_to_dev(L, cfg.dtype)
-    X = wl.make_tokens(cfg, 4)
     for idx in (np.zeros(0, np.int32), np.arange(300, dtype=np.int32)):
         desc = desc_for(ff, cfg, "int4", k=len(idx))
         split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
-        Y = ff.forward(desc, split, dev(X, cfg.dtype))
-        torch.cuda.synchronize()
-        want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=128)
-        assert relf(host(Y), want[0]) < TOL["bf16"]
+        for T in (4, 250):                      # decode kernels / expanded weights
+            X = wl.make_tokens(cfg, T)
+            Y = ff.forward(desc, split, dev(X, cfg.dtype))
+            torch.cuda.synchronize()
+            want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=128)
+            assert relf(host(Y), want[0]) < TOL["bf16"], T
 
 
 # ---------------------------------------------------------------- deleting neurons (Sec. 4.1)
