@@ -218,12 +218,23 @@ def main():
                             "frac_hbm": c4.weight_bytes() / t4 / HBM_PEAK}
         out["decode_int4"] = {"workload": "C4 Llama-2-7B-shaped SwiGLU, k=550 bf16 heavy + int4-g128 remainder",
                               "bytes_per_step": c4.weight_bytes(), "split_copies": n_copies, **dec}
+        # the same split with many tokens: weights expanded to bf16 once per call, then dense MFMA products
+        Tp = 4096
+        wsp = torch.empty(ff.workspace_bytes(d4, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
+        xp = dev(wl.make_tokens(c4, Tp))
+        yp = torch.empty((Tp, c4.d_model), dtype=bf, device="cuda")
+        tp4, _ = timed(lambda: ff.forward(d4, s4, xp, yp, False, wsp), 10, 3)
+        fl4 = 6.0 * Tp * c4.d_model * c4.d_ff          # the layer's dense products: the int4 split skips none
+        note(f"int4 prefill T={Tp}: {tp4*1e6:.1f} us")
+        out["prefill_int4"] = {"workload": f"C4 layer, T={Tp}", "us": tp4 * 1e6, "tokens_per_s": Tp / tp4,
+                               "flops": fl4, "TFLOPs": fl4 / tp4 / 1e12, "frac_mfma": fl4 / tp4 / MFMA_BF16_PEAK}
+        del wsp, xp, yp
 
 
         # ------------------------------------------------------------ extra: bf16 low-rank decode (HBM-bound)
         del s4s, s4, ws4
         torch.cuda.empty_cache()
-        dl = {}
+        dl, pl = {}, {}
         for cfg_d, n_cp in ((C3, 10), (C5, 8)):
             Ld = wl.make_layer(cfg_d)
             facs = wl.make_factors(dataclasses.replace(cfg_d, exact_svd=False), Ld, Ld["planted"])
@@ -248,8 +259,25 @@ def main():
                 dl[f"{cfg_d.name.split('-')[0]}_B{B}"] = {
                     "us": td * 1e6, "tokens_per_s": B / td, "bytes_per_step": cfg_d.weight_bytes(),
                     "GBps": cfg_d.weight_bytes() / td / 1e9, "frac_hbm": cfg_d.weight_bytes() / td / HBM_PEAK}
-            del spds, spd
+            # prefill of the same layer (MFMA-bound)
+            Tp = cfg_d.prefill_T
+            wsd = torch.empty(ff.workspace_bytes(dd, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
+            xp = dev(wl.make_tokens(cfg_d, Tp))
+            yp = torch.empty((Tp, cfg_d.d_model), dtype=bf, device="cuda")
+            st = {"i": 0}
+
+            def pstep():
+                ff.forward(dd, spds[st["i"] % n_cp], xp, yp, False, wsd)
+                st["i"] += 1
+
+            tpf, _ = timed(pstep, 20, 5)
+            flp = cfg_d.flops_per_token() * Tp
+            note(f"{cfg_d.name} prefill T={Tp}: {tpf*1e6:.1f} us")
+            pl[cfg_d.name.split('-')[0]] = {"T": Tp, "us": tpf * 1e6, "tokens_per_s": Tp / tpf, "flops": flp,
+                                            "TFLOPs": flp / tpf / 1e12, "frac_mfma": flp / tpf / MFMA_BF16_PEAK}
+            del spds, spd, wsd, xp, yp
             torch.cuda.empty_cache()
+        out["prefill_lowrank_bf16"] = {"workload": "the same C3 and C5 layers, 4096 tokens", **pl}
         out["decode_lowrank_bf16"] = {"workload": "C3 Llama-2-7B-shaped (k=550, rank 1024) and one C5 OPT-13B-shaped "
                                                   "layer (k=819, rank 1280): heavy bf16 + low-rank factors, seeded "
                                                   "Gaussian factors", **dl}

@@ -148,6 +148,11 @@ int ffsplit_build_split(const ffsplit_desc_t* desc, const void* W1, const void* 
  * buffers that receive FFN_1(X) and FFN_2~(X) separately (diagnostic; costs
  * extra launches).  Accumulation is fp32; intermediates between the chained
  * products are stored in desc->dtype.
+ * INT4: up to 192 tokens run in passes of 16 through weight-streaming kernels
+ * that apply the group scales in fp32; above that the dequantised weights
+ * float(s) * q are first written once, rounded to bf16, into the workspace
+ * (which is why ffsplit_workspace_bytes grows with a dense copy of the layer
+ * there) and the products run on them.
  */
 int ffsplit_forward(const ffsplit_desc_t* desc, const void* split, const void* X, int64_t T,
                     void* Y, void* Y_heavy, void* Y_rem,
