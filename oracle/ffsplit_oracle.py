@@ -5,13 +5,14 @@ equations; it shares no code with the HIP library and never imports it.  Only
 the tests, the smoke check and the benchmark's cpu_baseline leg may call it.
 
 Every function names the passage it follows.  All floating-point work is fp64
-with no intermediate rounding, except the int4 quantiser, whose decisions
+with no intermediate rounding, except the group-wise quantiser, whose decisions
 (scale, integer code) are taken in fp32/fp16 exactly as specified there so that
 a GPU implementation can agree bit for bit.
 
 Pins (tests/test_oracle_pins.py): dense special cases (heavy = all neurons,
 full-rank factors), Y = Y1 + Y2, the neuron-removal identity of Sec. 4.1 by
-brute force, exhaustive ranking for top-k, enumeration of the 16 int4 levels,
+brute force, exhaustive ranking for top-k, enumeration of the levels of the 3-,
+4- and 8-bit quantiser,
 closed-form identities of GeLU/SiLU, the parameter-count figure of Sec. 5.1.1.
 Forward outputs at the full workload shapes have no pin beyond those identities
 holding at full shape: parity unpinned there (the oracle is the definition).
@@ -252,11 +253,42 @@ def forward_remainder_int4(X, qw, group, act):
     return _act_pair(Z, G, act) @ dequantize(*qw["W2r"], group)
 
 
-def forward_split(X, W1, W2, Wg, idx, act, rem_kind, factors=None, group=128, bits=4):
+def quantize_heavy(sw, group, bits=8):
+    """Sec. 5.2, the LLM setting: the heavy neurons are quantised too, at a
+    higher bit width (8 bits, group 128), each neuron's up column, gate column
+    and down row in groups along d_model like the remainder's.
+    Returns {name: (q [k, d], s [k, d/group])}."""
+    out = {"W1h": quantize_rtn(sw["W1h"].T, group, bits),
+           "W2h": quantize_rtn(sw["W2h"], group, bits)}
+    if sw["Wgh"] is not None:
+        out["Wgh"] = quantize_rtn(sw["Wgh"].T, group, bits)
+    return out
+
+
+def forward_heavy_quant(X, qh, group, act):
+    """FFN_1 with the heavy neurons' weights replaced by their dequantised values."""
+    X = np.asarray(X, F64)
+    Z = X @ dequantize(*qh["W1h"], group).T
+    G = None
+    if act == "swiglu":
+        G = X @ dequantize(*qh["Wgh"], group).T
+    return _act_pair(Z, G, act) @ dequantize(*qh["W2h"], group)
+
+
+def forward_split(X, W1, W2, Wg, idx, act, rem_kind, factors=None, group=128, bits=4, heavy_bits=8):
     """Eq. 2: Y = FFN_1(X) + FFN_2~(X).  rem_kind: "none" (FFN_2 dropped),
     "dense", "lowrank" (factors refer to the remainder in ascending index
-    order), "int4".  Returns (Y, Y1, Y2)."""
+    order), "int4" (remainder at `bits`, heavy untouched), "w3h8" (Sec. 5.2's
+    pairing for the LLMs: heavy at heavy_bits = 8, remainder at 3 bits, both
+    round-to-nearest with the same group length).  Returns (Y, Y1, Y2)."""
     sw = split_weights(W1, W2, Wg, idx)
+    if rem_kind == "w3h8":
+        k, m = sw["W1h"].shape[1], sw["W1r"].shape[1]
+        X64 = np.asarray(X, F64)
+        zero = np.zeros((X64.shape[0], np.asarray(W2).shape[1]), F64)
+        Y1 = forward_heavy_quant(X, quantize_heavy(sw, group, heavy_bits), group, act) if k else zero
+        Y2 = forward_remainder_int4(X, quantize_remainder(sw, group, 3), group, act) if m else zero
+        return Y1 + Y2, Y1, Y2
     Y1 = forward_heavy(X, sw, act)
     if rem_kind == "none" or sw["W1r"].shape[1] == 0:
         Y2 = np.zeros_like(Y1)

@@ -318,6 +318,73 @@ def test_int4_forward_uses_dequantised_weights():
     assert np.array_equal(Y, Y1 + Y2)
 
 
+# ----------------------------------------------------------------- 3-bit / 8-bit pairing (Sec. 5.2, LLM setting)
+
+@pytest.mark.parametrize("bits", [3, 8])
+def test_quantiser_levels_and_invariants_at_other_widths(bits):
+    qmax = (1 << (bits - 1)) - 1
+    # one group holding every level -qmax..qmax times 0.25 (and one repeat): exact codes, exact scale
+    lv = np.arange(-qmax, qmax + 1)
+    w = (np.concatenate([lv, [qmax]]) * 0.25).astype(np.float32)[None, :]
+    q, s = orc.quantize_rtn(w, w.shape[1], bits)
+    assert float(s[0, 0]) == 0.25
+    assert q[0].tolist() == lv.tolist() + [qmax]
+    assert np.array_equal(orc.dequantize(q, s, w.shape[1]), w.astype(np.float64))
+    # ties to even, scale 1: halves go to the even neighbour
+    w = np.array([[float(qmax), 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 0.0]], np.float32)
+    q, s = orc.quantize_rtn(w, 8, bits)
+    assert float(s[0, 0]) == 1.0
+    assert q.tolist() == [[qmax, 0, 2, 2, 0, -2, -2, 0]]
+    # a value that would round past the top level is clamped (scale rounded down by fp16)
+    rng = np.random.default_rng(11)
+    W = wl.bf16_round(rng.standard_normal((20, 384)).astype(np.float32) * 0.02)
+    q, s = orc.quantize_rtn(W, 128, bits)
+    assert q.min() >= -qmax - 1 and q.max() <= qmax
+    assert np.all(np.abs(q.reshape(20, 3, 128)).max(axis=2) == qmax)       # group maximum -> +-qmax
+    deq = orc.dequantize(q, s, 128)
+    sfull = np.repeat(s.astype(np.float64), 128, axis=1)
+    assert np.all(np.abs(W - deq) <= 0.5 * sfull * (1 + 1e-6) + qmax * sfull * 2.0 ** -11)
+    a = np.abs(W.reshape(20, 3, 128)).max(axis=2)
+    assert np.array_equal(s, (a / np.float32(qmax)).astype(np.float16))
+    # finer grids nest: the 8-bit error is far below the 3-bit error on the same data
+    if bits == 8:
+        q3, s3 = orc.quantize_rtn(W, 128, 3)
+        assert np.linalg.norm(W - deq) < 0.05 * np.linalg.norm(W - orc.dequantize(q3, s3, 128))
+
+
+def test_w3h8_forward_uses_dequantised_heavy_and_remainder():
+    X, W1, W2, Wg = tiny("swiglu", T=4, d=8, f=12, seed=23)
+    idx = np.array([7, 2, 10], np.int32)
+    Y, Y1, Y2 = orc.forward_split(X, W1, W2, Wg, idx, "swiglu", "w3h8", group=4)
+    rest = wl.remainder_order(idx, 12)
+
+    def deq_cols(W, bits):      # W [8, n]: quantise each column (a neuron) along d in groups of 4
+        qmax = (1 << (bits - 1)) - 1
+        out = np.zeros_like(W)
+        for j in range(W.shape[1]):
+            for g in range(2):
+                w = W[4 * g:4 * g + 4, j].astype(np.float32)
+                s = np.float16(np.max(np.abs(w)) / np.float32(qmax))
+                qq = np.clip(np.rint(w / np.float32(s)), -qmax - 1, qmax) if s > 0 else np.zeros(4)
+                out[4 * g:4 * g + 4, j] = qq.astype(np.float64) * float(s)
+        return out
+    ref1 = np.array(py_dense_ffn(X.tolist(), deq_cols(W1[:, idx], 8).tolist(), deq_cols(W2[idx, :].T, 8).T.tolist(),
+                                 deq_cols(Wg[:, idx], 8).tolist(), "swiglu"))
+    ref2 = np.array(py_dense_ffn(X.tolist(), deq_cols(W1[:, rest], 3).tolist(), deq_cols(W2[rest, :].T, 3).T.tolist(),
+                                 deq_cols(Wg[:, rest], 3).tolist(), "swiglu"))
+    assert np.allclose(Y1, ref1, rtol=1e-12, atol=1e-13)
+    assert np.allclose(Y2, ref2, rtol=1e-12, atol=1e-13)
+    assert np.array_equal(Y, Y1 + Y2)
+    # 8 bits on the heavy part is close to leaving it alone; 3 bits on the remainder is not exact either
+    _, Y1_exact, _ = orc.forward_split(X, W1, W2, Wg, idx, "swiglu", "none")
+    assert orc.rel_frobenius(Y1, Y1_exact) < 0.05
+    # edge sets
+    for ids in (np.zeros(0, np.int32), np.arange(12, dtype=np.int32)):
+        Ya, Y1a, Y2a = orc.forward_split(X, W1, W2, Wg, ids, "swiglu", "w3h8", group=4)
+        assert np.array_equal(Ya, Y1a + Y2a)
+        assert (not Y1a.any()) if len(ids) == 0 else (not Y2a.any())
+
+
 # ----------------------------------------------------------------- stack reading
 
 def test_token_rms_normalise():
