@@ -45,7 +45,8 @@ enum { FFSPLIT_F32 = 0, FFSPLIT_BF16 = 1 };
 enum { FFSPLIT_REM_NONE = 0,      /* FFN_2 dropped                                        */
        FFSPLIT_REM_DENSE = 1,     /* FFN_2 kept uncompressed                              */
        FFSPLIT_REM_LOWRANK = 2,   /* each remainder matrix given as two rank-r factors    */
-       FFSPLIT_REM_INT4 = 3 };    /* remainder weights as group-wise symmetric int4       */
+       FFSPLIT_REM_INT4 = 3,      /* remainder weights as group-wise symmetric int4       */
+       FFSPLIT_REM_W3H8 = 4 };    /* heavy weights int8, remainder int3, both group-wise  */
 enum { FFSPLIT_SCORE_SUMSQ = 0,   /* Eq. 3: ||sigma(X U[:,j])||_F^2 * ||V[j,:]||_F^2      */
        FFSPLIT_SCORE_MEAN_L2 = 1, /* mean_t ||sigma(x_t U[:,j]) V[j,:]||_2                */
        FFSPLIT_SCORE_ACT_ONLY = 2 /* ||sigma(X U[:,j])||_F^2 (Sec. 2's heavy-hitter norm) */ };
@@ -71,7 +72,7 @@ typedef struct {
   int32_t k;         /* |h2|, 0..d_ff                                                     */
   int32_t rem_kind;  /* FFSPLIT_REM_*                                                     */
   int32_t rank;      /* LOWRANK: r, the same for every factored matrix                    */
-  int32_t group;     /* INT4: group length along d_model (must divide it; multiple of 32) */
+  int32_t group;     /* INT4, W3H8: group length along d_model (must divide it; multiple of 32) */
 } ffsplit_desc_t;
 
 /* Static description of a status code. */
@@ -135,6 +136,10 @@ int ffsplit_select_heavy(const float* scores, int32_t d_ff, int32_t k,
  *            desc->group (Sec. 5.2), in fp32:  a = max|w|, s = fp16(a / 7),
  *            q = s == 0 ? 0 : clamp(rint(w / float(s)), -8, 7) (ties to even),
  *            dequantised value float(s) * q.  Requires dtype BF16.
+ *   W3H8     Sec. 5.2's setting for the LLMs: the same quantiser at 3 bits
+ *            (a / 3, codes -4..3) on the remainder and at 8 bits (a / 127,
+ *            codes -128..127) on the heavy neurons' columns and rows, which
+ *            are therefore not kept in bf16.  Requires dtype BF16.
  */
 int ffsplit_build_split(const ffsplit_desc_t* desc, const void* W1, const void* Wg,
                         const void* W2, const int32_t* idx, const void* const* factors,
@@ -153,16 +158,19 @@ int ffsplit_build_split(const ffsplit_desc_t* desc, const void* W1, const void* 
  * float(s) * q are first written once, rounded to bf16, into the workspace
  * (which is why ffsplit_workspace_bytes grows with a dense copy of the layer
  * there) and the products run on them.
+ * W3H8: weights enter every product as bf16(float(s) * q); up to 32 tokens
+ * stream the codes once, larger batches expand them to bf16 first as above.
  */
 int ffsplit_forward(const ffsplit_desc_t* desc, const void* split, const void* X, int64_t T,
                     void* Y, void* Y_heavy, void* Y_rem,
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Test hook: unpack the INT4 remainder of a built split into logical order.
- * what = 0 (W1 columns), 1 (Wg columns), 2 (W2 rows).  q_out: [m, d_model] int8
- * codes; s_out: [m, d_model/group] fp16 scale bits (uint16); neuron order =
- * remainder ascending.
+ * Test hook: unpack the quantised weights of a built split (INT4, W3H8) into
+ * logical order.  what = 0 (W1 columns), 1 (Wg columns), 2 (W2 rows) of the
+ * remainder: q_out [m, d_model] int8 codes, s_out [m, d_model/group] fp16 scale
+ * bits (uint16), neuron order = remainder ascending.  W3H8 only: what = 3, 4, 5
+ * likewise for the heavy neurons ([k, ...], in the order of idx).
  */
 int ffsplit_split_export(const ffsplit_desc_t* desc, const void* split, int32_t what,
                          int8_t* q_out, uint16_t* s_out, void* stream);

@@ -6,7 +6,7 @@ import torch
 
 ACT_GELU, ACT_SWIGLU = 0, 1
 F32, BF16 = 0, 1
-REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4 = 0, 1, 2, 3
+REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4, REM_W3H8 = 0, 1, 2, 3, 4
 SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY = 0, 1, 2
 WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD = 0, 1, 2, 3
 E_NONFINITE = -7
@@ -66,7 +66,7 @@ def status_string(code: int) -> str:
 def make_desc(d_model, d_ff, act="gelu", dtype="bf16", k=0, rem_kind="none", rank=0, group=0) -> Desc:
     acts = {"gelu": ACT_GELU, "swiglu": ACT_SWIGLU}
     dts = {"f32": F32, "bf16": BF16}
-    rems = {"none": REM_NONE, "dense": REM_DENSE, "lowrank": REM_LOWRANK, "int4": REM_INT4}
+    rems = {"none": REM_NONE, "dense": REM_DENSE, "lowrank": REM_LOWRANK, "int4": REM_INT4, "w3h8": REM_W3H8}
     return Desc(d_model, d_ff, acts.get(act, act), dts.get(dtype, dtype), k, rems.get(rem_kind, rem_kind),
                 rank, group)
 
@@ -161,10 +161,11 @@ def forward(desc, split, X, Y=None, want_parts=False, workspace=None):
 
 
 def split_export(desc, split, what):
-    """INT4 test hook: (q int8 [m, d_model], scale bits uint16 as int16 tensor [m, d_model/group])."""
-    m = desc.d_ff - desc.k
-    q = torch.empty((m, desc.d_model), dtype=torch.int8, device=split.device)
-    s = torch.empty((m, desc.d_model // desc.group), dtype=torch.int16, device=split.device)
+    """Test hook of the quantised kinds: (q int8 [n, d_model], scale bits uint16 as int16 tensor
+    [n, d_model/group]); what 0..2 = remainder W1 / Wg / W2 (n = m), 3..5 = heavy (W3H8 only, n = k)."""
+    n = desc.k if what >= 3 else desc.d_ff - desc.k
+    q = torch.empty((n, desc.d_model), dtype=torch.int8, device=split.device)
+    s = torch.empty((n, desc.d_model // desc.group), dtype=torch.int16, device=split.device)
     rc = lib.ffsplit_split_export(ctypes.byref(desc), _ptr(split), what, _ptr(q), _ptr(s), _stream())
     _check(rc, "ffsplit_split_export")
     return q, s

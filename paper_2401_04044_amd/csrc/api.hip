@@ -4,6 +4,7 @@
 #include "layout.h"
 #include "prep.h"
 #include "int4.h"
+#include "quant.h"
 
 using namespace ffsplit;
 
@@ -18,14 +19,14 @@ int check_desc(const ffsplit_desc_t* d, bool need_split_fields) {
   if (d->dtype != FFSPLIT_F32 && d->dtype != FFSPLIT_BF16) return FFSPLIT_E_BADDESC;
   if (d->d_model % 8 != 0) return FFSPLIT_E_BADSHAPE;
   if (!need_split_fields) return FFSPLIT_OK;
-  if (d->rem_kind < FFSPLIT_REM_NONE || d->rem_kind > FFSPLIT_REM_INT4) return FFSPLIT_E_BADDESC;
+  if (d->rem_kind < FFSPLIT_REM_NONE || d->rem_kind > FFSPLIT_REM_W3H8) return FFSPLIT_E_BADDESC;
   if (d->k < 0 || d->k > d->d_ff) return FFSPLIT_E_BADSHAPE;
   const int m = d->d_ff - d->k;
   if (d->rem_kind == FFSPLIT_REM_LOWRANK && m > 0) {
     if (d->rank <= 0) return FFSPLIT_E_BADSHAPE;
     if (d->rank > (d->d_model < m ? d->d_model : m)) return FFSPLIT_E_BADSHAPE;
   }
-  if (d->rem_kind == FFSPLIT_REM_INT4) {
+  if (d->rem_kind == FFSPLIT_REM_INT4 || d->rem_kind == FFSPLIT_REM_W3H8) {
     if (d->group <= 0 || d->group % 32 != 0 || d->d_model % d->group != 0) return FFSPLIT_E_BADSHAPE;
     if (d->dtype != FFSPLIT_BF16) return FFSPLIT_E_UNSUPPORTED;
     if (d->group != 128 || d->d_model % 128 != 0) return FFSPLIT_E_UNSUPPORTED;
@@ -264,7 +265,8 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
     }
   }
   if (misaligned(W1) || misaligned(Wg) || misaligned(W2) || ((uintptr_t)split & 255u)) return FFSPLIT_E_ALIGN;
-  const bool need_rest = (d->rem_kind == FFSPLIT_REM_DENSE || d->rem_kind == FFSPLIT_REM_INT4) && m > 0;
+  const bool need_rest = (d->rem_kind == FFSPLIT_REM_DENSE || d->rem_kind == FFSPLIT_REM_INT4 ||
+                          d->rem_kind == FFSPLIT_REM_W3H8) && m > 0;
   const size_t ws_need = need_rest ? build_ws_bytes(*d) : 0;
   if (need_rest && (!workspace || workspace_bytes < ws_need)) return FFSPLIT_E_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -282,6 +284,10 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
 
   if (d->rem_kind == FFSPLIT_REM_INT4) {
     FFS_TRY(launch_int4_pack(*d, L, W1, Wg, W2, rest, idx, sp, st));
+    return FFSPLIT_OK;
+  }
+  if (d->rem_kind == FFSPLIT_REM_W3H8) {
+    FFS_TRY(launch_w3h8_pack(*d, L, W1, Wg, W2, rest, idx, sp, st));
     return FFSPLIT_OK;
   }
 
@@ -377,6 +383,14 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   const char* sp = (const char*)split;
   char* ws = (char*)workspace;
   const int M = (int)T;
+  if (d->rem_kind == FFSPLIT_REM_W3H8) {
+    ffsplit_desc_t dd = *d;
+    dd.rem_kind = FFSPLIT_REM_DENSE;
+    const Layout LD = make_layout(dd);
+    const FwdWs wd = make_fwd_ws(dd, LD, T);
+    FFS_TRY(launch_w3h8_expand(*d, L, LD, sp, ws + w.off_img, st));
+    return forward_chain(&dd, LD, wd, ws + w.off_img, X, M, Y, Y_heavy, Y_rem, ws + w.off_dense, st);
+  }
   if (d->rem_kind == FFSPLIT_REM_INT4) {
     if (w.i4_prefill) {
       // many tokens: expand the int4 remainder to bf16 once, then the dense chain on MFMA tiles
@@ -397,10 +411,15 @@ int ffsplit_split_export(const ffsplit_desc_t* d, const void* split, int32_t wha
                          void* stream) {
   int rc = check_desc(d, true);
   if (rc) return rc;
-  if (d->rem_kind != FFSPLIT_REM_INT4) return FFSPLIT_E_UNSUPPORTED;
+  if (d->rem_kind != FFSPLIT_REM_INT4 && d->rem_kind != FFSPLIT_REM_W3H8) return FFSPLIT_E_UNSUPPORTED;
   if (!split || !q_out || !s_out) return FFSPLIT_E_NULLPTR;
-  if (what < 0 || what > 2 || (what == 1 && d->act != FFSPLIT_ACT_SWIGLU)) return FFSPLIT_E_BADDESC;
+  const int what_max = d->rem_kind == FFSPLIT_REM_W3H8 ? 5 : 2;
+  if (what < 0 || what > what_max || (what % 3 == 1 && d->act != FFSPLIT_ACT_SWIGLU)) return FFSPLIT_E_BADDESC;
   const Layout L = make_layout(*d);
+  if (d->rem_kind == FFSPLIT_REM_W3H8) {
+    FFS_TRY(launch_w3h8_export(*d, L, (const char*)split, what, q_out, s_out, (hipStream_t)stream));
+    return FFSPLIT_OK;
+  }
   FFS_TRY(launch_int4_export(*d, L, (const char*)split, what, q_out, s_out, (hipStream_t)stream));
   return FFSPLIT_OK;
 }

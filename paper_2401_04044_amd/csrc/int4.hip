@@ -919,7 +919,7 @@ static int phase2_splits(int G) {
 
 FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   FwdWs w = {};
-  if (d.rem_kind == FFSPLIT_REM_INT4 && T > INT4_DECODE_MAX_T) {
+  if ((d.rem_kind == FFSPLIT_REM_INT4 && T > INT4_DECODE_MAX_T) || d.rem_kind == FFSPLIT_REM_W3H8) {
     ffsplit_desc_t dd = d;
     dd.rem_kind = FFSPLIT_REM_DENSE;
     const Layout LD = make_layout(dd);

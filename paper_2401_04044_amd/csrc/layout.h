@@ -35,8 +35,14 @@ struct Layout {
   int jp16, jp128, kp128, groups;
   size_t off_i4[3], off_s4[3];       // nibbles / scales of gate(W1), Wg, W2
   size_t off_hv[3];                  // heavy bf16 blocks in decode order
+  // W3H8 (quant.hip): four quantised matrices, 0 heavy up/gate rows (int8), 1 remainder up/gate
+  // rows (int3), 2 heavy down columns (int8), 3 remainder down columns (int3)
+  size_t off_qc[4], off_qs[4];       // codes / fp16 scales
   size_t total_bytes;
 };
+
+// quantised tiled blocks: 32 rows x 64 reduction elements
+inline size_t qblock_bytes(int bits) { return bits == 8 ? 2048 : 768; }
 
 inline Layout make_layout(const ffsplit_desc_t& d) {
   Layout L = {};
@@ -47,15 +53,28 @@ inline Layout make_layout(const ffsplit_desc_t& d) {
   const bool lr = d.rem_kind == FFSPLIT_REM_LOWRANK && m > 0;
   const bool dn = d.rem_kind == FFSPLIT_REM_DENSE && m > 0;
   const bool i4 = d.rem_kind == FFSPLIT_REM_INT4;
+  const bool q38 = d.rem_kind == FFSPLIT_REM_W3H8;
   L.rp = lr ? round_up(d.rank, 64) : 0;
-  L.mp = (lr || dn) ? round_up(m, 64) : 0;
-  L.k4 = L.kp + (lr ? L.rp : 0) + (dn ? L.mp : 0);
+  L.mp = (lr || dn || q38) ? round_up(m, 64) : 0;
+  L.k4 = L.kp + (lr ? L.rp : 0) + ((dn || q38) ? L.mp : 0);
   L.n1 = L.n_up * L.k4;
   size_t off = 0;
   L.tiled = d.dtype == FFSPLIT_BF16;
   L.dk = L.tiled ? round_up(d.d_model, 64) : d.d_model;
   L.dn = L.tiled ? round_up(d.d_model, 32) : d.d_model;
-  if (!i4) {
+  if (q38) {
+    // same padded counts and row order as the DENSE layout, so that expanding gives its image
+    L.groups = d.d_model / 128;
+    const int rows[4] = {L.n_up * L.kp, L.n_up * L.mp, L.dn, L.dn};
+    const int ks[4] = {L.dk, L.dk, L.kp, L.mp};
+    for (int i = 0; i < 4; ++i) {
+      const int bits = (i & 1) ? 3 : 8;
+      L.off_qc[i] = off; off = align256(off + (size_t)(rows[i] / 32) * (ks[i] / 64) * qblock_bytes(bits));
+      // up / gate: one scale per (row, group of 128 inputs); down: per (group of 128 outputs, neuron)
+      L.off_qs[i] = off;
+      off = align256(off + (i < 2 ? (size_t)rows[i] * L.groups * 2 : (size_t)(L.dn / 128) * ks[i] * 2));
+    }
+  } else if (!i4) {
     L.off_b1 = off; off = align256(off + (size_t)L.n1 * L.dk * L.esz);
     L.off_q1 = off; if (lr) off = align256(off + (size_t)L.n_up * L.mp * L.rp * L.esz);
     L.off_p2 = off; if (lr) off = align256(off + (size_t)L.rp * L.mp * L.esz);

@@ -1,0 +1,94 @@
+// Internal: the quantised tiled weight format of the 8-bit heavy / 3-bit remainder split
+// (Sec. 5.2, the setting for the LLMs) and its device-side pack / unpack helpers.
+//
+// A matrix [rows, K] (K-contiguous, like every packed weight here) is cut into blocks of
+// 32 rows x 64 reduction elements = four 32 x 16 operand blocks of v_mfma_f32_32x32x16_bf16.
+// Lane l = 32 c + r of a wavefront owns row r and, for each of the four operand blocks j,
+// the eight elements 16 j + 8 c + e (e = 0..7): 32 codes, numbered t = 8 j + e.  Codes are
+// stored offset-binary, u = q + 2^(bits-1).
+//   8 bits  2 KiB per block: two 1 KiB halves; half h holds, at byte 16 l + 8 (j & 1) + e,
+//           the code of operand block j = 2 h + (j & 1).
+//   3 bits  768 bytes per block: three dwords per lane at 12 l; dword 0 has the low two bits
+//           of codes 0..15 (code t at bits 2 t), dword 1 those of codes 16..31, dword 2 the
+//           third bit of all 32 codes (code t at bit t).
+// Blocks are ordered [row block][k block].
+#pragma once
+#include "common.h"
+
+namespace ffsplit {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t q_u32x4;
+
+// round-to-nearest symmetric code of w for scale s (fp32 decisions), offset-binary
+__device__ __forceinline__ uint32_t q_code(float w, float s, int bits) {
+  const float qmax = (float)((1 << (bits - 1)) - 1);
+  int q = 0;
+  if (s > 0.f) {
+    float t = rintf(w / s);
+    t = fminf(fmaxf(t, -qmax - 1.f), qmax);
+    q = (int)t;
+  }
+  return (uint32_t)(q + (1 << (bits - 1)));
+}
+
+__device__ __forceinline__ float q_scale(float amax, int bits, uint16_t* bits_out) {
+  const _Float16 h = (_Float16)(amax / (float)((1 << (bits - 1)) - 1));
+  __builtin_memcpy(bits_out, &h, 2);
+  return (float)h;
+}
+
+__device__ __forceinline__ float q_half(uint16_t h) {
+  _Float16 x;
+  __builtin_memcpy(&x, &h, 2);
+  return (float)x;
+}
+
+// the lane's 32 codes of one block, still packed
+template <int BITS>
+struct QPacked;
+template <>
+struct QPacked<8> {
+  q_u32x4 h[2];
+};
+template <>
+struct QPacked<3> {
+  uint32_t lo[2], hi;
+};
+
+__device__ __forceinline__ QPacked<8> q_load8(const char* block, int lane) {
+  QPacked<8> p;
+  p.h[0] = *(const q_u32x4*)(block + lane * 16);
+  p.h[1] = *(const q_u32x4*)(block + 1024 + lane * 16);
+  return p;
+}
+__device__ __forceinline__ QPacked<3> q_load3(const char* block, int lane) {
+  QPacked<3> p;
+  const uint32_t* w = (const uint32_t*)(block + lane * 12);
+  p.lo[0] = w[0]; p.lo[1] = w[1]; p.hi = w[2];
+  return p;
+}
+
+// code t (0..31) of the lane as a signed integer
+__device__ __forceinline__ int q_get(const QPacked<8>& p, int t) {
+  const int j = t >> 3, e = t & 7;
+  const uint32_t w = p.h[j >> 1][2 * (j & 1) + (e >> 2)];
+  return (int)((w >> (8 * (e & 3))) & 255u) - 128;
+}
+__device__ __forceinline__ int q_get(const QPacked<3>& p, int t) {
+  const uint32_t lo = (p.lo[t >> 4] >> (2 * (t & 15))) & 3u;
+  const uint32_t hi = (p.hi >> t) & 1u;
+  return (int)(lo | (hi << 2)) - 4;
+}
+
+// eight dequantised weights of operand block j (static) as one MFMA operand register set:
+// bf16(s[e] * q), s per element
+template <int BITS>
+__device__ __forceinline__ q_u32x4 q_operand(const QPacked<BITS>& p, int j, const float s[8]) {
+  q_u32x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    o[i] = pack_bf16x2((float)q_get(p, 8 * j + 2 * i) * s[2 * i], (float)q_get(p, 8 * j + 2 * i + 1) * s[2 * i + 1]);
+  return o;
+}
+
+}  // namespace ffsplit

@@ -28,7 +28,7 @@ def desc_for(ff, cfg, rem_kind=None, k=None, rank=None):
     rk = cfg.rem_kind if rem_kind is None else rem_kind
     return ff.make_desc(cfg.d_model, cfg.d_ff, cfg.act, cfg.dtype, cfg.k if k is None else k, rk,
                         (cfg.rank if rank is None else rank) if rk == "lowrank" else 0,
-                        cfg.group if rk == "int4" else 0)
+                        (cfg.group or 128) if rk in ("int4", "w3h8") else 0)
 
 
 def layer_to_dev(L, dtype):

@@ -295,3 +295,55 @@ def test_deleting_neurons_leaves_the_scored_residual(ff, act):
         assert res == pytest.approx(float(np.sum(only_s ** 2)), rel=2e-3)
         if len(S) == 1:
             assert res == pytest.approx(scores[S[0]], rel=2e-3)
+
+
+# ---------------------------------------------------------------- 8-bit heavy / 3-bit remainder (Sec. 5.2, LLM setting)
+
+W3H8_CASES = [
+    ("llama_reduced", reduced(C4, 256, 700), (1, 7, 32, 33, 300)),
+    ("llama_reduced_ragged", reduced(C4, 384, 1000), (16, 200)),
+    ("gelu_reduced", reduced(C2, 256, 500), (3, 1100)),
+]
+
+
+@pytest.mark.parametrize("name,cfg,Ts", W3H8_CASES, ids=[c[0] for c in W3H8_CASES])
+def test_w3h8_codes_scales_and_forward(ff, name, cfg, Ts):
+    L = wl.make_layer(cfg)
+    idx = L["planted"][::-1].copy()
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc = desc_for(ff, cfg, "w3h8")
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
+    sw = orc.split_weights(L["W1"], L["W2"], L["Wg"], idx)
+    qr = orc.quantize_remainder(sw, 128, 3)
+    qh = orc.quantize_heavy(sw, 128, 8)
+    for what, src, nm in ((0, qr, "W1r"), (1, qr, "Wgr"), (2, qr, "W2r"), (3, qh, "W1h"), (4, qh, "Wgh"), (5, qh, "W2h")):
+        if nm not in src:
+            continue
+        q, s = ff.split_export(desc, split, what)
+        torch.cuda.synchronize()
+        assert np.array_equal(q.cpu().numpy(), src[nm][0]), nm                 # integer codes, bit for bit
+        assert np.array_equal(s.cpu().numpy().view(np.uint16), src[nm][1].view(np.uint16)), nm
+    for T in Ts:
+        X = wl.make_tokens(cfg, T)
+        Y, Yh, Yr = ff.forward(desc, split, dev(X, cfg.dtype), want_parts=True)
+        Y_only = ff.forward(desc, split, dev(X, cfg.dtype))
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y_only)
+        want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "w3h8", group=128)
+        for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
+            assert relf(host(g), w) < TOL["bf16"], (T, nm, relf(host(g), w))
+
+
+def test_w3h8_edge_sets(ff):
+    cfg = reduced(C4, 256, 300)
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    for idx in (np.zeros(0, np.int32), np.arange(300, dtype=np.int32)):
+        desc = desc_for(ff, cfg, "w3h8", k=len(idx))
+        split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
+        for T in (4, 250):
+            X = wl.make_tokens(cfg, T)
+            Y = ff.forward(desc, split, dev(X, cfg.dtype))
+            torch.cuda.synchronize()
+            want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "w3h8", group=128)
+            assert relf(host(Y), want[0]) < TOL["bf16"], T
