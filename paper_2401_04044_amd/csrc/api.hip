@@ -384,6 +384,10 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   char* ws = (char*)workspace;
   const int M = (int)T;
   if (d->rem_kind == FFSPLIT_REM_W3H8) {
+    if (M <= W3H8_DECODE_MAX_T) {
+      FFS_TRY(w3h8_forward_small(*d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st));
+      return FFSPLIT_OK;
+    }
     ffsplit_desc_t dd = *d;
     dd.rem_kind = FFSPLIT_REM_DENSE;
     const Layout LD = make_layout(dd);

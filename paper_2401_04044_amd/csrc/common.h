@@ -104,5 +104,22 @@ int bf16_score_tile_m();
 // part: scratch of skinny_part_bytes(N) bytes
 size_t skinny_part_bytes(int n_max);
 int launch_skinny_bf16(const GemmArgs& a, int act, float* part, hipStream_t st);
+// the reduce half alone: sum of n_split ranges of partial tiles, activation, stores
+// (f16_out: the destinations hold fp16, saturating, instead of bf16)
+int launch_skinny_reduce(const GemmArgs& a, int act, const float* part, int n_split, int f16_out, hipStream_t st);
+// weights of one product in the quantised tiled format (qformat.h)
+struct SkinnyQ {
+  const void* codes;
+  const void* scales;
+  int bits;   // 8 or 3
+  int down;   // 0: one scale per (row, 128 reduction elements), [row block][G][32];
+              // 1: one per (128 rows, reduction element), [rows / 128][Kp]
+  int G, Kp;
+};
+// stream half alone (a.K a multiple of 64; up: a.A row-major bf16, K a multiple of 128; down:
+// a.A tiled fp16 with one row block): writes the
+// partial tiles of ranges [slot0, slot0 + *n_split) of part (skinny_q_part_bytes(N) bytes)
+size_t skinny_q_part_bytes(int n_max);
+int launch_skinny_q_stream(const GemmArgs& a, const SkinnyQ& q, float* part, int slot0, int* n_split, hipStream_t st);
 
 }  // namespace ffsplit

@@ -919,6 +919,16 @@ static int phase2_splits(int G) {
 
 FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   FwdWs w = {};
+  if (d.rem_kind == FFSPLIT_REM_W3H8 && T <= W3H8_DECODE_MAX_T) {
+    size_t off = 0;
+    w.t_pad = 32;
+    w.off_cat = off; off = align256(off + (size_t)32 * (L.k4 > 0 ? L.k4 : 16) * 2);
+    int n_max = L.n_up * (L.kp > L.mp ? L.kp : L.mp);
+    if (L.dn > n_max) n_max = L.dn;
+    w.off_kpart = off; off = align256(off + skinny_q_part_bytes(n_max));
+    w.total_bytes = off;
+    return w;
+  }
   if ((d.rem_kind == FFSPLIT_REM_INT4 && T > INT4_DECODE_MAX_T) || d.rem_kind == FFSPLIT_REM_W3H8) {
     ffsplit_desc_t dd = d;
     dd.rem_kind = FFSPLIT_REM_DENSE;

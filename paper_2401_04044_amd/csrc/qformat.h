@@ -8,9 +8,13 @@
 // stored offset-binary, u = q + 2^(bits-1).
 //   8 bits  2 KiB per block: two 1 KiB halves; half h holds, at byte 16 l + 8 (j & 1) + e,
 //           the code of operand block j = 2 h + (j & 1).
-//   3 bits  768 bytes per block: three dwords per lane at 12 l; dword 0 has the low two bits
-//           of codes 0..15 (code t at bits 2 t), dword 1 those of codes 16..31, dword 2 the
-//           third bit of all 32 codes (code t at bit t).
+//   3 bits  768 bytes per block: three dwords per lane at 12 l.  The code of operand block j,
+//           element e belongs to pair p = 4 j + (e >> 1) (one MFMA operand register holds a
+//           pair, element 2 i in its low half) and half h = e & 1.  Dword j >> 1 has its low
+//           two bits at bit 2 (p & 7) + 16 h; dword 2 has its third bit at bit
+//           (p + 2 + 16 h) mod 32.  So  (lo >> 2 (p & 7)) & 0x00030003  and
+//           rotr(hi, p) & 0x00040004  are both halves of the pair's register at once, and
+//           or-ing 0x43004300 (0x64006400) makes it the bf16 (fp16) pair 128 + u (1024 + u).
 // Blocks are ordered [row block][k block].
 #pragma once
 #include "common.h"
@@ -74,10 +78,24 @@ __device__ __forceinline__ int q_get(const QPacked<8>& p, int t) {
   const uint32_t w = p.h[j >> 1][2 * (j & 1) + (e >> 2)];
   return (int)((w >> (8 * (e & 3))) & 255u) - 128;
 }
+__device__ __forceinline__ int q_pos_lo(int t) { return 2 * ((4 * (t >> 3) + ((t & 7) >> 1)) & 7) + 16 * (t & 1); }
+__device__ __forceinline__ int q_pos_hi(int t) { return (4 * (t >> 3) + ((t & 7) >> 1) + 2 + 16 * (t & 1)) & 31; }
 __device__ __forceinline__ int q_get(const QPacked<3>& p, int t) {
-  const uint32_t lo = (p.lo[t >> 4] >> (2 * (t & 15))) & 3u;
-  const uint32_t hi = (p.hi >> t) & 1u;
+  const uint32_t lo = (p.lo[t >> 4] >> q_pos_lo(t)) & 3u;
+  const uint32_t hi = (p.hi >> q_pos_hi(t)) & 1u;
   return (int)(lo | (hi << 2)) - 4;
+}
+
+// register i (elements 2 i, 2 i + 1) of operand block j as the pair (magic + u) in both halves
+__device__ __forceinline__ uint32_t q_pair(const QPacked<3>& p, int j, int i, uint32_t magic) {
+  const int pr = 4 * j + i;
+  const uint32_t r = ((p.lo[j >> 1] >> (2 * (pr & 7))) & 0x00030003u) | magic;
+  return (__builtin_amdgcn_alignbit(p.hi, p.hi, pr) & 0x00040004u) | r;
+}
+// 8 bits: bytes (2 i, 2 i + 1) of operand block j under the high byte of magic
+__device__ __forceinline__ uint32_t q_pair(const QPacked<8>& p, int j, int i, uint32_t magic_bytes) {
+  const uint32_t w = p.h[j >> 1][2 * (j & 1) + (i >> 1)];
+  return __builtin_amdgcn_perm(magic_bytes, w, (i & 1) ? 0x04030402u : 0x04010400u);
 }
 
 // eight dequantised weights of operand block j (static) as one MFMA operand register set:

@@ -7,6 +7,7 @@
 // per 128 outputs, so in the down matrices (rows = outputs, reduction over neurons) the scale
 // changes with every reduction element and is constant over 128 consecutive rows.
 #include "quant.h"
+#include "prep.h"
 #include "qformat.h"
 
 namespace ffsplit {
@@ -33,8 +34,8 @@ __device__ __forceinline__ void store_codes(char* block, int lane, const uint32_
     uint32_t lo[2] = {0, 0}, hi = 0;
 #pragma unroll
     for (int t = 0; t < 32; ++t) {
-      lo[t >> 4] |= (u[t] & 3u) << (2 * (t & 15));
-      hi |= ((u[t] >> 2) & 1u) << t;
+      lo[t >> 4] |= (u[t] & 3u) << q_pos_lo(t);
+      hi |= ((u[t] >> 2) & 1u) << q_pos_hi(t);
     }
     uint32_t* w = (uint32_t*)(block + lane * 12);
     w[0] = lo[0]; w[1] = lo[1]; w[2] = hi;
@@ -306,6 +307,53 @@ int launch_w3h8_expand(const ffsplit_desc_t& d, const Layout& L, const Layout& L
     hipLaunchKernelGGL(expand_down_q_kernel, dim3((unsigned)((a.n_chunks + 255) / 256)), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return -1;
   }
+  return 0;
+}
+
+int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X,
+                       int M, void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st) {
+  const int dm = d.d_model;
+  const int act = d.act == FFSPLIT_ACT_SWIGLU ? ACT_GLU : ACT_GELU;
+  char* cat = ws + w.off_cat;                  // [32, k4] tiled fp16: activated heavy | remainder neurons
+  float* part = (float*)(ws + w.off_kpart);
+  const size_t esz = 2;
+  auto koff = [&](int col) { return (size_t)(col / 16) * 1024; };
+  // up / gate products, heavy (8 bits) then remainder (3 bits): act(X W) into their columns of cat
+  for (int i = 0; i < 2; ++i) {
+    const int Kp = i ? L.mp : L.kp;
+    if (Kp == 0) continue;
+    GemmArgs g = {};
+    g.A = X; g.lda = dm; g.M = M; g.N = L.n_up * Kp; g.K = dm;
+    g.act_cols = g.N; g.split_col = Kp;
+    g.C0 = cat + koff(i ? L.kp : 0); g.ldc0 = L.k4; g.c0_tiled = 1;
+    SkinnyQ q = {split + L.off_qc[i], split + L.off_qs[i], i ? 3 : 8, 0, L.groups, 0};
+    int S = 0;
+    if (launch_skinny_q_stream(g, q, part, 0, &S, st)) return -1;
+    if (launch_skinny_reduce(g, act, part, S, 1, st)) return -1;
+  }
+  // down product: both segments of the reduction stream into partial tiles, one sum (Eq. 2's
+  // addition happens in fp32, one rounding)
+  GemmArgs g = {};
+  g.M = M; g.N = dm; g.lda = L.k4; g.a_tiled = 1;
+  g.split_col = dm; g.ldc0 = dm; g.n_store = dm;
+  int S[2] = {0, 0};
+  for (int i = 0; i < 2; ++i) {
+    const int Kp = i ? L.mp : L.kp;
+    if (Kp == 0) continue;
+    g.A = cat + koff(i ? L.kp : 0); g.K = Kp;
+    SkinnyQ q = {split + L.off_qc[2 + i], split + L.off_qs[2 + i], i ? 3 : 8, 1, L.groups, Kp};
+    if (launch_skinny_q_stream(g, q, part, S[0], &S[i], st)) return -1;
+  }
+  const size_t seg = (size_t)S[0] * (dm / 32) * 1024;   // floats of the heavy segment's tiles
+  auto emit = [&](void* out, const float* p0, int n) -> int {
+    if (!out) return 0;
+    if (n == 0) return launch_fill_zero(out, (size_t)M * dm * esz, st);
+    g.C0 = out;
+    return launch_skinny_reduce(g, ACT_NONE, p0, n, 0, st);
+  };
+  if (emit(Y, part, S[0] + S[1])) return -1;
+  if (emit(Y_heavy, part, S[0])) return -1;
+  if (emit(Y_rem, part + seg, S[1])) return -1;
   return 0;
 }
 

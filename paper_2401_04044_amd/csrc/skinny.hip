@@ -13,6 +13,8 @@
 // them in a fixed order, applies the activation and writes bf16 (tiled or row-major, one or
 // two destinations) with the same column rules as the large-batch kernels' epilogue.
 #include "common.h"
+#include "layout.h"
+#include "qformat.h"
 
 namespace ffsplit {
 
@@ -107,6 +109,230 @@ __global__ void __launch_bounds__(256) skinny_stream_kernel(const SkinnyArgs p) 
   for (int g = 0; g < 4; ++g) dst[g * 64] = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
 }
 
+// The same product with the weights in the quantised tiled format (32 x 64 blocks of 8- or
+// 3-bit codes plus fp16 group scales; qformat.h).  The packed blocks are the only traffic that
+// comes from HBM; they are unpacked in the integer domain: a shift, a rotate and two and-or
+// per operand register give the pair (magic + u) directly.
+//   UP    (one scale per row and 128 reduction elements; activations = the caller's bf16 X):
+//         the unscaled codes go through the MFMA, one group of 128 at a time, and the group's
+//         fp32 result is scaled per row afterwards.  3 bits: operands are the bf16 values
+//         128 + u, and a second MFMA with an all-ones operand gives the group's sum of
+//         activations, so that 132 times it removes the offset.  8 bits: the codes do not fit
+//         a bf16 mantissa; X is converted to fp16 (exact) and the operands are the fp16 values
+//         q = (1024 + u) - 1152.
+//   DOWN  (one scale per reduction element and 128 rows; activations fp16, written by the UP
+//         products' reduce step): operands are the fp16 values s * q, from one packed add and
+//         one packed multiply with the scale pair as loaded.
+// Work split: a workgroup of four wavefronts owns RB adjacent row blocks (they share the
+// activation blocks, and for DOWN the scales) over one range of the reduction; the wavefronts
+// take a quarter of the range each and add their accumulators through LDS in a fixed order.
+// Each wavefront keeps two units in registers: everything the next unit needs (weights,
+// scales, activations) is requested in one batch before the current one is computed, so no
+// younger load ever has to be waited for behind an older one.
+struct SkinnyQArgs {
+  const void* A;
+  int64_t lda;
+  int M, n_rb, n_split, nu_total, nu_per, slot0;   // units: UP groups of two blocks, DOWN blocks
+  const char* codes;
+  const uint16_t* scales;
+  int G, Kp;
+  float* part;
+};
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+union QFrag {
+  u32x4_t u;
+  bf16x8_t b;
+  f16x8_t h;
+};
+union H2 {
+  uint32_t u;
+  f16x2_t h;
+};
+
+template <int BITS, bool DOWN>
+struct QShape {
+  static constexpr int RB = BITS == 3 ? (DOWN ? 4 : 2) : (DOWN ? 2 : 1);   // row blocks per workgroup
+  static constexpr int UB = DOWN ? 1 : 2;                                  // blocks per unit
+};
+
+template <int BITS, bool DOWN>
+struct QUnit {
+  QPacked<BITS> w[QShape<BITS, DOWN>::RB][QShape<BITS, DOWN>::UB];
+  u32x4_t a[QShape<BITS, DOWN>::UB * 4];
+  u32x4_t sd[DOWN ? 4 : 1];                                  // DOWN: scale pairs of the block's 64 elements
+  u32x2_t su[DOWN ? 1 : QShape<BITS, DOWN>::RB][4];          // UP: the lane's 16 row scales per row block
+};
+
+template <int BITS, bool DOWN>
+__global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs p) {
+  constexpr int RB = QShape<BITS, DOWN>::RB, UB = QShape<BITS, DOWN>::UB;
+  constexpr int BB = BITS == 8 ? 2048 : 768;
+  constexpr bool F16 = DOWN || BITS == 8;                    // fp16 MFMA
+  __shared__ float red[4][RB][16][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n_rbg = p.n_rb / RB;
+  const int rb = ((int)blockIdx.x % n_rbg) * RB, sp = (int)blockIdx.x / n_rbg;
+  const int U0 = sp * p.nu_per;
+  const int U1 = min(p.nu_total, U0 + p.nu_per);             // U0 < U1 by construction of the grid
+  const int per = (U1 - U0 + 3) / 4;
+  const int u0 = U0 + wave * per;
+  const int u1 = min(U1, u0 + per);                          // may be empty: the wavefront then adds zeros
+  const int r = lane & 31, c2 = lane >> 5;
+
+  const char* wbase = p.codes + (int64_t)rb * p.nu_total * UB * BB;
+  const int64_t wrow = (int64_t)p.nu_total * UB * BB;        // bytes from one row block to the next
+  const char* abase = (const char*)p.A;
+  if (DOWN) abase += (int64_t)lane * 16;                                // tiled, one row block
+  else abase += ((int64_t)min(r, p.M - 1) * p.lda + c2 * 8) * 2;        // row-major
+
+  auto load = [&](QUnit<BITS, DOWN>& q, int u) {
+    const int uc = max(U0, min(u, U1 - 1));                  // past the range: any valid unit, masked later
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int x = 0; x < UB; ++x) {
+        const char* blk = wbase + i * wrow + (int64_t)(uc * UB + x) * BB;
+        if constexpr (BITS == 8) q.w[i][x] = q_load8(blk, lane);
+        else q.w[i][x] = q_load3(blk, lane);
+      }
+#pragma unroll
+    for (int kb = 0; kb < UB * 4; ++kb)
+      q.a[kb] = DOWN ? *(const u32x4_t*)(abase + (int64_t)(uc * 4 + kb) * 1024)
+                     : *(const u32x4_t*)(abase + (int64_t)(uc * 8 + kb) * 32);
+    if constexpr (DOWN) {
+      const uint16_t* sb = p.scales + (int64_t)(rb >> 2) * p.Kp + uc * 64 + 8 * c2;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) q.sd[j] = *(const u32x4_t*)(sb + 16 * j);
+    } else {
+      // rows 8 g + 4 c2 + i of a row block live in accumulator registers 4 g + i
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        const uint16_t* sb = p.scales + ((int64_t)(rb + i) * p.G + uc) * 32 + 4 * c2;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) q.su[i][g] = *(const u32x2_t*)(sb + 8 * g);
+      }
+    }
+  };
+
+  const f32x16_t zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  f32x16_t tot[RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i) tot[i] = zero;
+
+  auto compute = [&](const QUnit<BITS, DOWN>& q, bool live) {
+    QFrag a[UB * 4];
+#pragma unroll
+    for (int kb = 0; kb < UB * 4; ++kb) {
+      a[kb].u = live ? q.a[kb] : u32x4_t{0, 0, 0, 0};
+      if constexpr (!DOWN && BITS == 8) {
+        // bf16 -> fp16: eight significant bits, exact (round toward zero never rounds)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(a[kb].u[i] << 16),
+                                                    __uint_as_float(a[kb].u[i] & 0xffff0000u));
+          uint32_t hb;
+          __builtin_memcpy(&hb, &h, 4);
+          a[kb].u[i] = hb;
+        }
+      }
+    }
+    if constexpr (DOWN) {
+      const _Float16 off = BITS == 8 ? (_Float16)-1152.0f : (_Float16)-1028.0f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int rbi = 0; rbi < RB; ++rbi) {
+          QFrag wf;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            H2 v, s2;
+            v.u = q_pair(q.w[rbi][0], j, i, BITS == 8 ? 0x64646464u : 0x64006400u);
+            s2.u = q.sd[j][i];
+            v.h = (v.h + f16x2_t{off, off}) * s2.h;
+            wf.u[i] = v.u;
+          }
+          tot[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf.h, a[j].h, tot[rbi], 0, 0, 0);
+        }
+    } else {
+      f32x16_t ag[RB], ao = zero;
+#pragma unroll
+      for (int i = 0; i < RB; ++i) ag[i] = zero;
+      QFrag ones;
+      ones.u = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+#pragma unroll
+      for (int kb = 0; kb < 8; ++kb) {
+        if constexpr (!F16) ao = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.b, a[kb].b, ao, 0, 0, 0);
+#pragma unroll
+        for (int rbi = 0; rbi < RB; ++rbi) {
+          QFrag wf;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if constexpr (BITS == 8) {
+              H2 v;
+              v.u = q_pair(q.w[rbi][kb >> 2], kb & 3, i, 0x64646464u);
+              v.h = v.h + f16x2_t{(_Float16)-1152.0f, (_Float16)-1152.0f};
+              wf.u[i] = v.u;
+            } else {
+              wf.u[i] = q_pair(q.w[rbi][kb >> 2], kb & 3, i, 0x43004300u);
+            }
+          }
+          if constexpr (F16) ag[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf.h, a[kb].h, ag[rbi], 0, 0, 0);
+          else ag[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.b, a[kb].b, ag[rbi], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int rbi = 0; rbi < RB; ++rbi)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const u32x2_t sc = q.su[rbi][g];
+          const float s4[4] = {q_half((uint16_t)(sc[0] & 0xffffu)), q_half((uint16_t)(sc[0] >> 16)),
+                               q_half((uint16_t)(sc[1] & 0xffffu)), q_half((uint16_t)(sc[1] >> 16))};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float raw = F16 ? ag[rbi][4 * g + i] : fmaf(-132.0f, ao[4 * g + i], ag[rbi][4 * g + i]);
+            tot[rbi][4 * g + i] = fmaf(s4[i], raw, tot[rbi][4 * g + i]);
+          }
+        }
+    }
+  };
+
+  QUnit<BITS, DOWN> qa, qb;
+  load(qa, u0);
+  for (int u = u0; u < u1; u += 2) {
+    // (the scheduling barriers keep each batch of loads ahead of the arithmetic of the unit before)
+    load(qb, u + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(qa, u < u1);
+    __builtin_amdgcn_sched_barrier(0);
+    load(qa, u + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(qb, u + 1 < u1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // fixed-order sum over the four wavefronts; wavefront w finishes accumulator registers 4 w ..
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][i][v][lane] = tot[i][v];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      o[e] = red[0][i][4 * wave + e][lane];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) o[e] += red[w][i][4 * wave + e][lane];
+    }
+    float4* dst = (float4*)p.part + ((int64_t)((p.slot0 + sp) * p.n_rb + rb + i) * 4 + wave) * 64 + lane;
+    *dst = make_float4(o[0], o[1], o[2], o[3]);
+  }
+}
+
 __device__ __forceinline__ float sk_silu(float z) { return z / (1.0f + __expf(-z)); }
 
 // Sum over the ranges (fixed order), activation, bf16 stores.  One thread per (block, lane,
@@ -119,7 +345,14 @@ struct SkinnyReduceArgs {
   void* C1;
   int64_t ldc0, ldc1;
   int c0_tiled, c1_tiled, n_store;
+  int f16_out;   // destinations hold fp16 (saturating) instead of bf16
 };
+
+__device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi) {
+  H2 v;
+  v.h = f16x2_t{(_Float16)fminf(fmaxf(lo, -65504.f), 65504.f), (_Float16)fminf(fmaxf(hi, -65504.f), 65504.f)};
+  return v.u;
+}
 
 __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceArgs p) {
   const int id = blockIdx.x * 256 + threadIdx.x;
@@ -174,7 +407,8 @@ __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceAr
   int col, tiled;
   if (col0 < p.split_col) { base = (char*)p.C0; ld = p.ldc0; col = col0; tiled = p.c0_tiled; }
   else { base = (char*)p.C1; ld = p.ldc1; col = col0 - p.split_col; tiled = p.c1_tiled; }
-  const uint2 val = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+  const uint2 val = p.f16_out ? make_uint2(pack_f16x2_sat(v[0], v[1]), pack_f16x2_sat(v[2], v[3]))
+                              : make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
   if (tiled) {
     // (the destination has one 32-row block; rows past M hold repeats of row M - 1, finite)
     const int64_t chunk = ((int64_t)(col / 16) * 64) + ((col >> 3) & 1) * 32 + row;
@@ -213,13 +447,64 @@ int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) 
   if (g.a_tiled) hipLaunchKernelGGL(skinny_stream_kernel<true>, dim3((tasks + 3) / 4), dim3(256), 0, st, a);
   else hipLaunchKernelGGL(skinny_stream_kernel<false>, dim3((tasks + 3) / 4), dim3(256), 0, st, a);
   if (hipGetLastError() != hipSuccess) return -1;
+  return launch_skinny_reduce(g, act, part, a.n_split, 0, st);
+}
+
+int launch_skinny_reduce(const GemmArgs& g, int act, const float* part, int n_split, int f16_out, hipStream_t st) {
   SkinnyReduceArgs r = {};
-  r.part = part; r.n_rb = a.n_rb; r.n_split = a.n_split; r.M = g.M; r.N = g.N;
+  r.f16_out = f16_out;
+  r.part = part; r.n_rb = g.N / 32; r.n_split = n_split; r.M = g.M; r.N = g.N;
   r.act = act; r.act_cols = g.act_cols; r.split_col = g.split_col;
   r.C0 = g.C0; r.C1 = g.C1; r.ldc0 = g.ldc0; r.ldc1 = g.ldc1;
   r.c0_tiled = g.c0_tiled; r.c1_tiled = g.c1_tiled; r.n_store = g.n_store;
-  hipLaunchKernelGGL(skinny_reduce_kernel, dim3(a.n_rb), dim3(256), 0, st, r);
+  hipLaunchKernelGGL(skinny_reduce_kernel, dim3(r.n_rb), dim3(256), 0, st, r);
   return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+constexpr int SKQ_MAX_SPLIT = 32;
+size_t skinny_q_part_bytes(int n_max) {
+  // two streamed segments per product, each at most SKQ_MAX_SPLIT ranges of one 4 KiB tile per row block
+  return (size_t)2 * SKQ_MAX_SPLIT * ((n_max + 31) / 32) * 4096;
+}
+
+int launch_skinny_q_stream(const GemmArgs& g, const SkinnyQ& q, float* part, int slot0, int* n_split, hipStream_t st) {
+  *n_split = 0;
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return 0;
+  if (g.M > 32 || (g.K & 63) || (q.bits != 3 && q.bits != 8)) return -1;
+  if ((q.down != 0) != (g.a_tiled != 0) || (!q.down && (g.K & 127))) return -1;
+  const int rbs = q.bits == 3 ? (q.down ? 4 : 2) : (q.down ? 2 : 1);   // QShape::RB
+  if (g.N % (32 * rbs)) return -1;
+  SkinnyQArgs a = {};
+  a.A = g.A; a.lda = g.lda; a.M = g.M;
+  a.n_rb = g.N / 32;
+  const int n_rbg = a.n_rb / rbs;
+  const int ub = q.down ? 1 : 2;
+  a.nu_total = g.K / (64 * ub);
+  // ranges: about 512 workgroups, at least two units per wavefront, and partial tiles (4 KiB
+  // per row block and range) of at most a third of the packed weights' bytes
+  const size_t wbytes = (size_t)a.n_rb * (g.K / 64) * qblock_bytes(q.bits);
+  int S = (512 + n_rbg - 1) / n_rbg;
+  if (S > a.nu_total / 8) S = a.nu_total / 8;
+  const int cap = (int)(wbytes / ((size_t)12288 * a.n_rb));
+  if (S > cap) S = cap;
+  if (S > SKQ_MAX_SPLIT) S = SKQ_MAX_SPLIT;
+  if (S < 1) S = 1;
+  a.nu_per = (a.nu_total + S - 1) / S;
+  a.n_split = (a.nu_total + a.nu_per - 1) / a.nu_per;
+  a.slot0 = slot0;
+  a.codes = (const char*)q.codes; a.scales = (const uint16_t*)q.scales; a.G = q.G; a.Kp = q.Kp;
+  a.part = part;
+  const dim3 grid(n_rbg * a.n_split), blk(256);
+  if (q.bits == 8) {
+    if (q.down) hipLaunchKernelGGL((skinny_stream_q_kernel<8, true>), grid, blk, 0, st, a);
+    else hipLaunchKernelGGL((skinny_stream_q_kernel<8, false>), grid, blk, 0, st, a);
+  } else {
+    if (q.down) hipLaunchKernelGGL((skinny_stream_q_kernel<3, true>), grid, blk, 0, st, a);
+    else hipLaunchKernelGGL((skinny_stream_q_kernel<3, false>), grid, blk, 0, st, a);
+  }
+  if (hipGetLastError() != hipSuccess) return -1;
+  *n_split = a.n_split;
+  return 0;
 }
 
 }  // namespace ffsplit
