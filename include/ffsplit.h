@@ -158,8 +158,10 @@ int ffsplit_build_split(const ffsplit_desc_t* desc, const void* W1, const void* 
  * float(s) * q are first written once, rounded to bf16, into the workspace
  * (which is why ffsplit_workspace_bytes grows with a dense copy of the layer
  * there) and the products run on them.
- * W3H8: weights enter every product as bf16(float(s) * q); up to 32 tokens
- * stream the codes once, larger batches expand them to bf16 first as above.
+ * W3H8: up to 128 tokens run in passes of 32 that stream the packed codes
+ * (scales applied in fp32 or fp16, the activations between the two products
+ * kept in fp16, saturating); larger batches expand the weights to
+ * bf16(float(s) * q) first as above.
  */
 int ffsplit_forward(const ffsplit_desc_t* desc, const void* split, const void* X, int64_t T,
                     void* Y, void* Y_heavy, void* Y_rem,

@@ -385,7 +385,12 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   const int M = (int)T;
   if (d->rem_kind == FFSPLIT_REM_W3H8) {
     if (M <= W3H8_DECODE_MAX_T) {
-      FFS_TRY(w3h8_forward_small(*d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st));
+      // passes of at most 32 tokens, each streaming the packed codes once
+      for (int t0 = 0; t0 < M; t0 += 32) {
+        const size_t o = (size_t)t0 * d->d_model * 2;
+        FFS_TRY(w3h8_forward_small(*d, L, w, sp, (const char*)X + o, M - t0 < 32 ? M - t0 : 32, (char*)Y + o,
+                                   Y_heavy ? (char*)Y_heavy + o : nullptr, Y_rem ? (char*)Y_rem + o : nullptr, ws, st));
+      }
       return FFSPLIT_OK;
     }
     ffsplit_desc_t dd = *d;

@@ -116,8 +116,10 @@ struct SkinnyQ {
               // 1: one per (128 rows, reduction element), [rows / 128][Kp]
   int G, Kp;
 };
-// stream half alone (a.K a multiple of 64; up: a.A row-major bf16, K a multiple of 128; down:
-// a.A tiled fp16 with one row block): writes the
+// X [M <= 32, d] bf16 row-major -> one tiled row block (64 d bytes)
+int launch_skinny_tile_rows(const void* X, int M, int d, void* out, hipStream_t st);
+// stream half alone (a.K a multiple of 64; a.A tiled with one row block: bf16 for up, where K is a
+// multiple of 128, fp16 for down): writes the
 // partial tiles of ranges [slot0, slot0 + *n_split) of part (skinny_q_part_bytes(N) bytes)
 size_t skinny_q_part_bytes(int n_max);
 int launch_skinny_q_stream(const GemmArgs& a, const SkinnyQ& q, float* part, int slot0, int* n_split, hipStream_t st);

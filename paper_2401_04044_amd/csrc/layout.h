@@ -141,8 +141,9 @@ struct FwdWs {
 // per pass; beyond it the weights are expanded to bf16 once and the dense chain runs
 // (expanding plus the chain at that size costs about as much as 12 passes).
 constexpr int INT4_DECODE_MAX_T = 192;
-// W3H8: up to this many tokens stream the packed codes (one pass); beyond it they are expanded
-constexpr int W3H8_DECODE_MAX_T = 32;
+// W3H8: up to this many tokens stream the packed codes, 32 tokens per pass; beyond it they are
+// expanded (four passes cost less than expanding plus the chain at that size)
+constexpr int W3H8_DECODE_MAX_T = 128;
 
 inline size_t build_ws_bytes(const ffsplit_desc_t& d) { return align256((size_t)8 * d.d_ff) + 256; }
 

@@ -15,7 +15,7 @@ int launch_w3h8_export(const ffsplit_desc_t& d, const Layout& L, const char* spl
 int launch_w3h8_expand(const ffsplit_desc_t& d, const Layout& L, const Layout& LD, const char* split, char* image,
                        hipStream_t st);
 
-// forward for at most W3H8_DECODE_MAX_T tokens: the packed codes are streamed once per product
+// forward for at most 32 tokens (one pass): the packed codes are streamed once per product
 // (weight-streaming kernels of skinny.hip), scratch laid out by make_fwd_ws
 int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X,
                        int M, void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st);

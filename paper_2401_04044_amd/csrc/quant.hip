@@ -318,12 +318,14 @@ int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w,
   float* part = (float*)(ws + w.off_kpart);
   const size_t esz = 2;
   auto koff = [&](int col) { return (size_t)(col / 16) * 1024; };
+  char* xt = ws + w.off_t;                     // X as one tiled row block
+  if (launch_skinny_tile_rows(X, M, dm, xt, st)) return -1;
   // up / gate products, heavy (8 bits) then remainder (3 bits): act(X W) into their columns of cat
   for (int i = 0; i < 2; ++i) {
     const int Kp = i ? L.mp : L.kp;
     if (Kp == 0) continue;
     GemmArgs g = {};
-    g.A = X; g.lda = dm; g.M = M; g.N = L.n_up * Kp; g.K = dm;
+    g.A = xt; g.lda = dm; g.a_tiled = 1; g.M = M; g.N = L.n_up * Kp; g.K = dm;
     g.act_cols = g.N; g.split_col = Kp;
     g.C0 = cat + koff(i ? L.kp : 0); g.ldc0 = L.k4; g.c0_tiled = 1;
     SkinnyQ q = {split + L.off_qc[i], split + L.off_qs[i], i ? 3 : 8, 0, L.groups, 0};

@@ -113,7 +113,8 @@ __global__ void __launch_bounds__(256) skinny_stream_kernel(const SkinnyArgs p) 
 // 3-bit codes plus fp16 group scales; qformat.h).  The packed blocks are the only traffic that
 // comes from HBM; they are unpacked in the integer domain: a shift, a rotate and two and-or
 // per operand register give the pair (magic + u) directly.
-//   UP    (one scale per row and 128 reduction elements; activations = the caller's bf16 X):
+//   UP    (one scale per row and 128 reduction elements; activations = the caller's bf16 X,
+//         re-tiled once per call by tile_rows_kernel so that its loads are contiguous):
 //         the unscaled codes go through the MFMA, one group of 128 at a time, and the group's
 //         fp32 result is scaled per row afterwards.  3 bits: operands are the bf16 values
 //         128 + u, and a second MFMA with an all-ones operand gives the group's sum of
@@ -181,13 +182,12 @@ __global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs 
   const int per = (U1 - U0 + 3) / 4;
   const int u0 = U0 + wave * per;
   const int u1 = min(U1, u0 + per);                          // may be empty: the wavefront then adds zeros
-  const int r = lane & 31, c2 = lane >> 5;
+  const int c2 = lane >> 5;
 
   const char* wbase = p.codes + (int64_t)rb * p.nu_total * UB * BB;
   const int64_t wrow = (int64_t)p.nu_total * UB * BB;        // bytes from one row block to the next
   const char* abase = (const char*)p.A;
-  if (DOWN) abase += (int64_t)lane * 16;                                // tiled, one row block
-  else abase += ((int64_t)min(r, p.M - 1) * p.lda + c2 * 8) * 2;        // row-major
+  abase += (int64_t)lane * 16;                               // tiled, one row block
 
   auto load = [&](QUnit<BITS, DOWN>& q, int u) {
     const int uc = max(U0, min(u, U1 - 1));                  // past the range: any valid unit, masked later
@@ -201,8 +201,7 @@ __global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs 
       }
 #pragma unroll
     for (int kb = 0; kb < UB * 4; ++kb)
-      q.a[kb] = DOWN ? *(const u32x4_t*)(abase + (int64_t)(uc * 4 + kb) * 1024)
-                     : *(const u32x4_t*)(abase + (int64_t)(uc * 8 + kb) * 32);
+      q.a[kb] = *(const u32x4_t*)(abase + (int64_t)(uc * UB * 4 + kb) * 1024);
     if constexpr (DOWN) {
       const uint16_t* sb = p.scales + (int64_t)(rb >> 2) * p.Kp + uc * 64 + 8 * c2;
 #pragma unroll
@@ -331,6 +330,16 @@ __global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs 
     float4* dst = (float4*)p.part + ((int64_t)((p.slot0 + sp) * p.n_rb + rb + i) * 4 + wave) * 64 + lane;
     *dst = make_float4(o[0], o[1], o[2], o[3]);
   }
+}
+
+// X [M <= 32, d] row-major -> one tiled row block (1 KiB per 16 columns; rows past M repeat
+// row M - 1, which the later steps never store)
+__global__ void tile_rows_kernel(const uint16_t* X, int M, int d, u32x4_t* out) {
+  const int id = blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= (d / 16) * 64) return;
+  const int kb = id >> 6, lane = id & 63;
+  const int row = min(lane & 31, M - 1);
+  out[id] = *(const u32x4_t*)(X + (int64_t)row * d + kb * 16 + 8 * (lane >> 5));
 }
 
 __device__ __forceinline__ float sk_silu(float z) { return z / (1.0f + __expf(-z)); }
@@ -462,6 +471,13 @@ int launch_skinny_reduce(const GemmArgs& g, int act, const float* part, int n_sp
 }
 
 constexpr int SKQ_MAX_SPLIT = 32;
+int launch_skinny_tile_rows(const void* X, int M, int d, void* out, hipStream_t st) {
+  if (M <= 0 || M > 32 || (d & 15)) return -1;
+  const int n = (d / 16) * 64;
+  hipLaunchKernelGGL(tile_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (const uint16_t*)X, M, d, (u32x4_t*)out);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 size_t skinny_q_part_bytes(int n_max) {
   // two streamed segments per product, each at most SKQ_MAX_SPLIT ranges of one 4 KiB tile per row block
   return (size_t)2 * SKQ_MAX_SPLIT * ((n_max + 31) / 32) * 4096;
@@ -471,7 +487,7 @@ int launch_skinny_q_stream(const GemmArgs& g, const SkinnyQ& q, float* part, int
   *n_split = 0;
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return 0;
   if (g.M > 32 || (g.K & 63) || (q.bits != 3 && q.bits != 8)) return -1;
-  if ((q.down != 0) != (g.a_tiled != 0) || (!q.down && (g.K & 127))) return -1;
+  if (!g.a_tiled || (!q.down && (g.K & 127))) return -1;
   const int rbs = q.bits == 3 ? (q.down ? 4 : 2) : (q.down ? 2 : 1);   // QShape::RB
   if (g.N % (32 * rbs)) return -1;
   SkinnyQArgs a = {};
@@ -481,11 +497,11 @@ int launch_skinny_q_stream(const GemmArgs& g, const SkinnyQ& q, float* part, int
   const int ub = q.down ? 1 : 2;
   a.nu_total = g.K / (64 * ub);
   // ranges: about 512 workgroups, at least two units per wavefront, and partial tiles (4 KiB
-  // per row block and range) of at most a third of the packed weights' bytes
+  // per row block and range) of at most half of the packed weights' bytes
   const size_t wbytes = (size_t)a.n_rb * (g.K / 64) * qblock_bytes(q.bits);
   int S = (512 + n_rbg - 1) / n_rbg;
   if (S > a.nu_total / 8) S = a.nu_total / 8;
-  const int cap = (int)(wbytes / ((size_t)12288 * a.n_rb));
+  const int cap = (int)(wbytes / ((size_t)8192 * a.n_rb));
   if (S > cap) S = cap;
   if (S > SKQ_MAX_SPLIT) S = SKQ_MAX_SPLIT;
   if (S < 1) S = 1;

@@ -300,8 +300,8 @@ def test_deleting_neurons_leaves_the_scored_residual(ff, act):
 # ---------------------------------------------------------------- 8-bit heavy / 3-bit remainder (Sec. 5.2, LLM setting)
 
 W3H8_CASES = [
-    ("llama_reduced", reduced(C4, 256, 700), (1, 7, 32, 33, 300)),
-    ("llama_reduced_ragged", reduced(C4, 384, 1000), (16, 200)),
+    ("llama_reduced", reduced(C4, 256, 700), (1, 7, 32, 33, 128, 129, 300)),
+    ("llama_reduced_ragged", reduced(C4, 384, 1000), (16, 77, 200)),
     ("gelu_reduced", reduced(C2, 256, 500), (3, 1100)),
 ]
 
