@@ -228,11 +228,45 @@ def main():
         note(f"int4 prefill T={Tp}: {tp4*1e6:.1f} us")
         out["prefill_int4"] = {"workload": f"C4 layer, T={Tp}", "us": tp4 * 1e6, "tokens_per_s": Tp / tp4,
                                "flops": fl4, "TFLOPs": fl4 / tp4 / 1e12, "frac_mfma": fl4 / tp4 / MFMA_BF16_PEAK}
-        del wsp, xp, yp
+        del wsp, xp, yp, s4s, s4, ws4
+        torch.cuda.empty_cache()
+
+        # ------------------------------------------------------------ extra: 8-bit heavy / 3-bit remainder
+        d38 = ff.make_desc(c4.d_model, c4.d_ff, c4.act, c4.dtype, c4.k, "w3h8", 0, 128)
+        s38 = ff.build_split(d38, dev(L4["W1"]), dev(L4["Wg"]), dev(L4["W2"]), torch.from_numpy(L4["planted"]).cuda())
+        torch.cuda.synchronize()
+        m4 = c4.d_ff - c4.k
+        bytes38 = 3.0 * c4.k * c4.d_model + 3.0 * m4 * c4.d_model * 3 / 8 + 3.0 * c4.d_ff * (c4.d_model // 128) * 2
+        n38 = 20                                        # 20 x 57.6 MB = 1.15 GB >> last-level cache
+        s38s = [s38] + [s38.clone() for _ in range(n38 - 1)]
+        ws38 = torch.empty(ff.workspace_bytes(d38, ff.WS_FORWARD, 32), dtype=torch.uint8, device="cuda")
+        q38 = {}
+        for B in c4.decode_B:
+            xb = dev(wl.make_tokens(c4, B))
+            yb = torch.empty((B, c4.d_model), dtype=bf, device="cuda")
+            st = {"i": 0}
+
+            def qstep():
+                ff.forward(d38, s38s[st["i"] % n38], xb, yb, False, ws38)
+                st["i"] += 1
+
+            t38, _ = timed(qstep, 100, 20)
+            note(f"w3h8 decode B={B}: {t38*1e6:.1f} us")
+            q38[f"B{B}"] = {"us": t38 * 1e6, "tokens_per_s": B / t38, "GBps": bytes38 / t38 / 1e9,
+                            "frac_hbm": bytes38 / t38 / HBM_PEAK}
+        wsp = torch.empty(ff.workspace_bytes(d38, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
+        xp = dev(wl.make_tokens(c4, Tp))
+        yp = torch.empty((Tp, c4.d_model), dtype=bf, device="cuda")
+        tp38, _ = timed(lambda: ff.forward(d38, s38, xp, yp, False, wsp), 10, 3)
+        note(f"w3h8 prefill T={Tp}: {tp38*1e6:.1f} us")
+        out["w3h8"] = {"workload": "C4 layer with Sec. 5.2's pairing: heavy int8-g128, remainder int3-g128",
+                       "bytes_per_step": bytes38, "split_copies": n38, **q38,
+                       "prefill_T4096": {"us": tp38 * 1e6, "tokens_per_s": Tp / tp38, "TFLOPs": fl4 / tp38 / 1e12,
+                                         "frac_mfma": fl4 / tp38 / MFMA_BF16_PEAK}}
+        del wsp, xp, yp, s38s, s38, ws38
 
 
         # ------------------------------------------------------------ extra: bf16 low-rank decode (HBM-bound)
-        del s4s, s4, ws4
         torch.cuda.empty_cache()
         dl, pl = {}, {}
         for cfg_d, n_cp in ((C3, 10), (C5, 8)):
