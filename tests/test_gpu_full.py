@@ -167,6 +167,44 @@ def test_c4_llama7b_shape_int4_many_tokens(ff):
         assert e < TOL["bf16"], (nm, e)
 
 
+def test_c4_llama7b_shape_w3h8(ff):
+    """Sec. 5.2's pairing (heavy int8, remainder int3) at the Llama-2-7B shape: every code and
+    scale, decode batches on the packed codes, and 4096 tokens on the expanded weights."""
+    cfg = C4
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    idx_h = L["planted"]
+    desc = desc_for(ff, cfg, "w3h8")
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx_h).cuda())
+    del Ld
+    sw = orc.split_weights(L["W1"], L["W2"], L["Wg"], idx_h)
+    qr = orc.quantize_remainder(sw, 128, 3)
+    qh = orc.quantize_heavy(sw, 128, 8)
+    for what, src, nm in ((0, qr, "W1r"), (1, qr, "Wgr"), (2, qr, "W2r"), (3, qh, "W1h"), (4, qh, "Wgh"), (5, qh, "W2h")):
+        q, s = ff.split_export(desc, split, what)
+        torch.cuda.synchronize()
+        assert np.array_equal(q.cpu().numpy(), src[nm][0]), nm
+        assert np.array_equal(s.cpu().numpy().view(np.uint16), src[nm][1].view(np.uint16)), nm
+
+    def want(X):
+        Y1 = orc.forward_heavy_quant(X, qh, 128, "swiglu")
+        Y2 = orc.forward_remainder_int4(X, qr, 128, "swiglu")
+        return Y1 + Y2, Y1, Y2
+
+    for B in (1, 16, 32):
+        Xb = wl.make_tokens(cfg, B, wl.gen.S_EVAL, layer=B)
+        got = ff.forward(desc, split, dev(Xb, "bf16"), want_parts=True)
+        torch.cuda.synchronize()
+        for g, w, nm in zip(got, want(Xb), ("Y", "Y_heavy", "Y_rem")):
+            assert relf(host(g), w) < TOL["bf16"], (B, nm, relf(host(g), w))
+    T = 4096
+    X = wl.make_tokens(cfg, T)
+    Y = ff.forward(desc, split, dev(X, "bf16"))
+    torch.cuda.synchronize()
+    rows = sampled_rows(T, 24)
+    assert relf(host(Y[torch.from_numpy(rows).cuda()]), want(X[rows])[0]) < TOL["bf16"]
+
+
 def test_c5_opt13b_shape_layers_teacher_forced(ff):
     """Two layers of the 40-layer stack at full width, each fed the oracle's own
     layer input (rounded to bf16): x <- x + FFN_split(n(x)), n = per-token RMS
