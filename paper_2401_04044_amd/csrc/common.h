@@ -116,12 +116,21 @@ struct SkinnyQ {
               // 1: one per (128 rows, reduction element), [rows / 128][Kp]
   int G, Kp;
 };
-// X [M <= 32, d] bf16 row-major -> one tiled row block (64 d bytes)
-int launch_skinny_tile_rows(const void* X, int M, int d, void* out, hipStream_t st);
-// stream half alone (a.K a multiple of 64; a.A tiled with one row block: bf16 for up, where K is a
-// multiple of 128, fp16 for down): writes the
-// partial tiles of ranges [slot0, slot0 + *n_split) of part (skinny_q_part_bytes(N) bytes)
+// One product whose weights are part 8-bit (g8, q8), part 3-bit (g3, q3), in one launch; a part
+// with N = 0 or K = 0 is absent.  M <= 32, K a multiple of 64.
+//   up   (q.down = 0): A = the caller's row-major bf16 X, K a multiple of 128; the two parts
+//        are two row ranges of one output (8-bit rows first): partial tiles
+//        [range][g8.N / 32 + g3.N / 32 row blocks], n_split[0] ranges for the first rows,
+//        n_split[1] for the others (launch_skinny_reduce2).
+//   down (q.down = 1): A tiled fp16 with one row block; the two parts are two segments of the
+//        reduction over the same N rows: partial tiles of ranges [0, n_split[0]) and
+//        [n_split[0], n_split[0] + n_split[1]).
+// part: skinny_q_part_bytes(N) bytes.
 size_t skinny_q_part_bytes(int n_max);
-int launch_skinny_q_stream(const GemmArgs& a, const SkinnyQ& q, float* part, int slot0, int* n_split, hipStream_t st);
+int launch_skinny_q_pair(const GemmArgs& g8, const SkinnyQ& q8, const GemmArgs& g3, const SkinnyQ& q3, float* part,
+                         int n_split[2], hipStream_t st);
+// reduce with n_split ranges for row blocks below rb_split and n_split_b from there on
+int launch_skinny_reduce2(const GemmArgs& a, int act, const float* part, int n_split, int rb_split, int n_split_b,
+                          int f16_out, hipStream_t st);
 
 }  // namespace ffsplit

@@ -923,8 +923,7 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     size_t off = 0;
     w.t_pad = 32;
     w.off_cat = off; off = align256(off + (size_t)32 * (L.k4 > 0 ? L.k4 : 16) * 2);
-    w.off_t = off; off = align256(off + (size_t)32 * d.d_model * 2);
-    int n_max = L.n_up * (L.kp > L.mp ? L.kp : L.mp);
+    int n_max = L.n_up * L.k4;
     if (L.dn > n_max) n_max = L.dn;
     w.off_kpart = off; off = align256(off + skinny_q_part_bytes(n_max));
     w.total_bytes = off;

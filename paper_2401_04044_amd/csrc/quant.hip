@@ -318,20 +318,19 @@ int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w,
   float* part = (float*)(ws + w.off_kpart);
   const size_t esz = 2;
   auto koff = [&](int col) { return (size_t)(col / 16) * 1024; };
-  char* xt = ws + w.off_t;                     // X as one tiled row block
-  if (launch_skinny_tile_rows(X, M, dm, xt, st)) return -1;
-  // up / gate products, heavy (8 bits) then remainder (3 bits): act(X W) into their columns of cat
-  for (int i = 0; i < 2; ++i) {
-    const int Kp = i ? L.mp : L.kp;
-    if (Kp == 0) continue;
-    GemmArgs g = {};
-    g.A = xt; g.lda = dm; g.a_tiled = 1; g.M = M; g.N = L.n_up * Kp; g.K = dm;
-    g.act_cols = g.N; g.split_col = Kp;
-    g.C0 = cat + koff(i ? L.kp : 0); g.ldc0 = L.k4; g.c0_tiled = 1;
-    SkinnyQ q = {split + L.off_qc[i], split + L.off_qs[i], i ? 3 : 8, 0, L.groups, 0};
-    int S = 0;
-    if (launch_skinny_q_stream(g, q, part, 0, &S, st)) return -1;
-    if (launch_skinny_reduce(g, act, part, S, 1, st)) return -1;
+  // up / gate product, heavy rows (8 bits) then remainder rows (3 bits): act(X W) into cat
+  {
+    GemmArgs g8 = {}, g3 = {};
+    g8.A = X; g8.lda = dm; g8.M = M; g8.N = L.n_up * L.kp; g8.K = dm;
+    g3 = g8; g3.N = L.n_up * L.mp;
+    SkinnyQ q8 = {split + L.off_qc[0], split + L.off_qs[0], 8, 0, L.groups, 0};
+    SkinnyQ q3 = {split + L.off_qc[1], split + L.off_qs[1], 3, 0, L.groups, 0};
+    int S[2];
+    if (launch_skinny_q_pair(g8, q8, g3, q3, part, S, st)) return -1;
+    GemmArgs g = g8;
+    g.N = L.n_up * L.k4; g.act_cols = g.N; g.split_col = L.k4;
+    g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = 1;
+    if (g.N > 0 && launch_skinny_reduce2(g, act, part, S[0], L.n_up * L.kp / 32, S[1], 1, st)) return -1;
   }
   // down product: both segments of the reduction stream into partial tiles, one sum (Eq. 2's
   // addition happens in fp32, one rounding)
@@ -339,12 +338,13 @@ int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w,
   g.M = M; g.N = dm; g.lda = L.k4; g.a_tiled = 1;
   g.split_col = dm; g.ldc0 = dm; g.n_store = dm;
   int S[2] = {0, 0};
-  for (int i = 0; i < 2; ++i) {
-    const int Kp = i ? L.mp : L.kp;
-    if (Kp == 0) continue;
-    g.A = cat + koff(i ? L.kp : 0); g.K = Kp;
-    SkinnyQ q = {split + L.off_qc[2 + i], split + L.off_qs[2 + i], i ? 3 : 8, 1, L.groups, Kp};
-    if (launch_skinny_q_stream(g, q, part, S[0], &S[i], st)) return -1;
+  {
+    GemmArgs g8 = g, g3 = g;
+    g8.A = cat; g8.K = L.kp;
+    g3.A = cat + koff(L.kp); g3.K = L.mp;
+    SkinnyQ q8 = {split + L.off_qc[2], split + L.off_qs[2], 8, 1, L.groups, L.kp};
+    SkinnyQ q3 = {split + L.off_qc[3], split + L.off_qs[3], 3, 1, L.groups, L.mp};
+    if (launch_skinny_q_pair(g8, q8, g3, q3, part, S, st)) return -1;
   }
   const size_t seg = (size_t)S[0] * (dm / 32) * 1024;   // floats of the heavy segment's tiles
   auto emit = [&](void* out, const float* p0, int n) -> int {

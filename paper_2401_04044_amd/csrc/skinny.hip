@@ -113,8 +113,7 @@ __global__ void __launch_bounds__(256) skinny_stream_kernel(const SkinnyArgs p) 
 // 3-bit codes plus fp16 group scales; qformat.h).  The packed blocks are the only traffic that
 // comes from HBM; they are unpacked in the integer domain: a shift, a rotate and two and-or
 // per operand register give the pair (magic + u) directly.
-//   UP    (one scale per row and 128 reduction elements; activations = the caller's bf16 X,
-//         re-tiled once per call by tile_rows_kernel so that its loads are contiguous):
+//   UP    (one scale per row and 128 reduction elements; activations = the caller's bf16 X):
 //         the unscaled codes go through the MFMA, one group of 128 at a time, and the group's
 //         fp32 result is scaled per row afterwards.  3 bits: operands are the bf16 values
 //         128 + u, and a second MFMA with an all-ones operand gives the group's sum of
@@ -134,6 +133,7 @@ struct SkinnyQArgs {
   const void* A;
   int64_t lda;
   int M, n_rb, n_split, nu_total, nu_per, slot0;   // units: UP groups of two blocks, DOWN blocks
+  int rb_out0, n_rb_part;                          // partial tiles: first row block, row blocks per range
   const char* codes;
   const uint16_t* scales;
   int G, Kp;
@@ -168,26 +168,27 @@ struct QUnit {
 };
 
 template <int BITS, bool DOWN>
-__global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs p) {
+__device__ __forceinline__ void skinny_q_body(const SkinnyQArgs& p, int wg, float* red_mem) {
   constexpr int RB = QShape<BITS, DOWN>::RB, UB = QShape<BITS, DOWN>::UB;
   constexpr int BB = BITS == 8 ? 2048 : 768;
   constexpr bool F16 = DOWN || BITS == 8;                    // fp16 MFMA
-  __shared__ float red[4][RB][16][64];
+  float (*red)[RB][16][64] = (float (*)[RB][16][64])red_mem;   // [4][RB][16][64]
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_rbg = p.n_rb / RB;
-  const int rb = ((int)blockIdx.x % n_rbg) * RB, sp = (int)blockIdx.x / n_rbg;
+  const int rb = (wg % n_rbg) * RB, sp = wg / n_rbg;
   const int U0 = sp * p.nu_per;
   const int U1 = min(p.nu_total, U0 + p.nu_per);             // U0 < U1 by construction of the grid
   const int per = (U1 - U0 + 3) / 4;
   const int u0 = U0 + wave * per;
   const int u1 = min(U1, u0 + per);                          // may be empty: the wavefront then adds zeros
-  const int c2 = lane >> 5;
+  const int r = lane & 31, c2 = lane >> 5;
 
   const char* wbase = p.codes + (int64_t)rb * p.nu_total * UB * BB;
   const int64_t wrow = (int64_t)p.nu_total * UB * BB;        // bytes from one row block to the next
   const char* abase = (const char*)p.A;
-  abase += (int64_t)lane * 16;                               // tiled, one row block
+  if (DOWN) abase += (int64_t)lane * 16;                              // tiled, one row block
+  else abase += ((int64_t)min(r, p.M - 1) * p.lda + c2 * 8) * 2;      // the caller's row-major X
 
   auto load = [&](QUnit<BITS, DOWN>& q, int u) {
     const int uc = max(U0, min(u, U1 - 1));                  // past the range: any valid unit, masked later
@@ -201,7 +202,7 @@ __global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs 
       }
 #pragma unroll
     for (int kb = 0; kb < UB * 4; ++kb)
-      q.a[kb] = *(const u32x4_t*)(abase + (int64_t)(uc * UB * 4 + kb) * 1024);
+      q.a[kb] = *(const u32x4_t*)(abase + (int64_t)(uc * UB * 4 + kb) * (DOWN ? 1024 : 32));
     if constexpr (DOWN) {
       const uint16_t* sb = p.scales + (int64_t)(rb >> 2) * p.Kp + uc * 64 + 8 * c2;
 #pragma unroll
@@ -327,19 +328,23 @@ __global__ void __launch_bounds__(256) skinny_stream_q_kernel(const SkinnyQArgs 
 #pragma unroll
       for (int w = 1; w < 4; ++w) o[e] += red[w][i][4 * wave + e][lane];
     }
-    float4* dst = (float4*)p.part + ((int64_t)((p.slot0 + sp) * p.n_rb + rb + i) * 4 + wave) * 64 + lane;
+    float4* dst = (float4*)p.part + ((int64_t)((p.slot0 + sp) * p.n_rb_part + p.rb_out0 + rb + i) * 4 + wave) * 64 + lane;
     *dst = make_float4(o[0], o[1], o[2], o[3]);
   }
 }
 
-// X [M <= 32, d] row-major -> one tiled row block (1 KiB per 16 columns; rows past M repeat
-// row M - 1, which the later steps never store)
-__global__ void tile_rows_kernel(const uint16_t* X, int M, int d, u32x4_t* out) {
-  const int id = blockIdx.x * blockDim.x + threadIdx.x;
-  if (id >= (d / 16) * 64) return;
-  const int kb = id >> 6, lane = id & 63;
-  const int row = min(lane & 31, M - 1);
-  out[id] = *(const u32x4_t*)(X + (int64_t)row * d + kb * 16 + 8 * (lane >> 5));
+// One launch for the 8-bit and the 3-bit part of a product: workgroups [0, wg8) take the
+// first, the rest the second.
+struct SkinnyQ2Args {
+  SkinnyQArgs s8, s3;
+  int wg8;
+};
+
+template <bool DOWN>
+__global__ void __launch_bounds__(256) skinny_stream_q2_kernel(const SkinnyQ2Args p) {
+  extern __shared__ float red_mem[];
+  if ((int)blockIdx.x < p.wg8) skinny_q_body<8, DOWN>(p.s8, (int)blockIdx.x, red_mem);
+  else skinny_q_body<3, DOWN>(p.s3, (int)blockIdx.x - p.wg8, red_mem);
 }
 
 __device__ __forceinline__ float sk_silu(float z) { return z / (1.0f + __expf(-z)); }
@@ -355,6 +360,7 @@ struct SkinnyReduceArgs {
   int64_t ldc0, ldc1;
   int c0_tiled, c1_tiled, n_store;
   int f16_out;   // destinations hold fp16 (saturating) instead of bf16
+  int rb_split, n_split_b;   // row blocks from rb_split on have n_split_b ranges
 };
 
 __device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi) {
@@ -386,13 +392,14 @@ __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceAr
     const float4* src = (const float4*)p.part + ((int64_t)b * 4 + g) * 64 + lane;
     // eight independent loads at a time, added in range order
     const int64_t step = (int64_t)p.n_rb * 256;
-    for (int sp = 0; sp < p.n_split; sp += 8) {
+    const int ns = b < p.rb_split ? p.n_split : p.n_split_b;
+    for (int sp = 0; sp < ns; sp += 8) {
       float4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(sp + u, p.n_split - 1) * step];
+      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(sp + u, ns - 1) * step];
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        if (sp + u < p.n_split) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+        if (sp + u < ns) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
     }
     return s;
   };
@@ -460,8 +467,13 @@ int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) 
 }
 
 int launch_skinny_reduce(const GemmArgs& g, int act, const float* part, int n_split, int f16_out, hipStream_t st) {
+  return launch_skinny_reduce2(g, act, part, n_split, g.N / 32, n_split, f16_out, st);
+}
+
+int launch_skinny_reduce2(const GemmArgs& g, int act, const float* part, int n_split, int rb_split, int n_split_b,
+                          int f16_out, hipStream_t st) {
   SkinnyReduceArgs r = {};
-  r.f16_out = f16_out;
+  r.f16_out = f16_out; r.rb_split = rb_split; r.n_split_b = n_split_b;
   r.part = part; r.n_rb = g.N / 32; r.n_split = n_split; r.M = g.M; r.N = g.N;
   r.act = act; r.act_cols = g.act_cols; r.split_col = g.split_col;
   r.C0 = g.C0; r.C1 = g.C1; r.ldc0 = g.ldc0; r.ldc1 = g.ldc1;
@@ -471,26 +483,22 @@ int launch_skinny_reduce(const GemmArgs& g, int act, const float* part, int n_sp
 }
 
 constexpr int SKQ_MAX_SPLIT = 32;
-int launch_skinny_tile_rows(const void* X, int M, int d, void* out, hipStream_t st) {
-  if (M <= 0 || M > 32 || (d & 15)) return -1;
-  const int n = (d / 16) * 64;
-  hipLaunchKernelGGL(tile_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (const uint16_t*)X, M, d, (u32x4_t*)out);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
-}
-
 size_t skinny_q_part_bytes(int n_max) {
   // two streamed segments per product, each at most SKQ_MAX_SPLIT ranges of one 4 KiB tile per row block
   return (size_t)2 * SKQ_MAX_SPLIT * ((n_max + 31) / 32) * 4096;
 }
 
-int launch_skinny_q_stream(const GemmArgs& g, const SkinnyQ& q, float* part, int slot0, int* n_split, hipStream_t st) {
-  *n_split = 0;
-  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return 0;
-  if (g.M > 32 || (g.K & 63) || (q.bits != 3 && q.bits != 8)) return -1;
-  if (!g.a_tiled || (!q.down && (g.K & 127))) return -1;
+// kernel arguments and workgroup count of one part (0 workgroups if it is empty)
+static int q_part_args(const GemmArgs& g, const SkinnyQ& q, float* part, int slot0, int rb_out0, int n_rb_part,
+                       SkinnyQArgs* out, int* wgs) {
+  *wgs = 0;
+  SkinnyQArgs a = {};
+  *out = a;
+  if (g.N <= 0 || g.K <= 0) return 0;
+  if (g.M <= 0 || g.M > 32 || (g.K & 63) || (q.bits != 3 && q.bits != 8)) return -1;
+  if ((q.down != 0) != (g.a_tiled != 0) || (!q.down && (g.K & 127))) return -1;
   const int rbs = q.bits == 3 ? (q.down ? 4 : 2) : (q.down ? 2 : 1);   // QShape::RB
   if (g.N % (32 * rbs)) return -1;
-  SkinnyQArgs a = {};
   a.A = g.A; a.lda = g.lda; a.M = g.M;
   a.n_rb = g.N / 32;
   const int n_rbg = a.n_rb / rbs;
@@ -507,19 +515,37 @@ int launch_skinny_q_stream(const GemmArgs& g, const SkinnyQ& q, float* part, int
   if (S < 1) S = 1;
   a.nu_per = (a.nu_total + S - 1) / S;
   a.n_split = (a.nu_total + a.nu_per - 1) / a.nu_per;
-  a.slot0 = slot0;
+  a.slot0 = slot0; a.rb_out0 = rb_out0; a.n_rb_part = n_rb_part;
   a.codes = (const char*)q.codes; a.scales = (const uint16_t*)q.scales; a.G = q.G; a.Kp = q.Kp;
   a.part = part;
-  const dim3 grid(n_rbg * a.n_split), blk(256);
-  if (q.bits == 8) {
-    if (q.down) hipLaunchKernelGGL((skinny_stream_q_kernel<8, true>), grid, blk, 0, st, a);
-    else hipLaunchKernelGGL((skinny_stream_q_kernel<8, false>), grid, blk, 0, st, a);
+  *out = a;
+  *wgs = n_rbg * a.n_split;
+  return 0;
+}
+
+int launch_skinny_q_pair(const GemmArgs& g8, const SkinnyQ& q8, const GemmArgs& g3, const SkinnyQ& q3, float* part,
+                         int n_split[2], hipStream_t st) {
+  n_split[0] = n_split[1] = 0;
+  const bool down = (g8.N > 0 && g8.K > 0) ? q8.down != 0 : q3.down != 0;
+  SkinnyQ2Args a = {};
+  int w8 = 0, w3 = 0;
+  if (down) {
+    // same rows, two segments of the reduction: the 3-bit ranges follow the 8-bit ones
+    const int n_rb = (g8.N > 0 ? g8.N : g3.N) / 32;
+    if (q_part_args(g8, q8, part, 0, 0, n_rb, &a.s8, &w8)) return -1;
+    if (q_part_args(g3, q3, part, a.s8.n_split, 0, n_rb, &a.s3, &w3)) return -1;
   } else {
-    if (q.down) hipLaunchKernelGGL((skinny_stream_q_kernel<3, true>), grid, blk, 0, st, a);
-    else hipLaunchKernelGGL((skinny_stream_q_kernel<3, false>), grid, blk, 0, st, a);
+    // two row ranges of one output: the 3-bit rows follow the 8-bit rows
+    const int n_rb = (g8.N > 0 ? g8.N / 32 : 0) + (g3.N > 0 ? g3.N / 32 : 0);
+    if (q_part_args(g8, q8, part, 0, 0, n_rb, &a.s8, &w8)) return -1;
+    if (q_part_args(g3, q3, part, 0, g8.N > 0 ? g8.N / 32 : 0, n_rb, &a.s3, &w3)) return -1;
   }
+  if (w8 + w3 == 0) return 0;
+  a.wg8 = w8;
+  if (down) hipLaunchKernelGGL(skinny_stream_q2_kernel<true>, dim3(w8 + w3), dim3(256), 65536, st, a);
+  else hipLaunchKernelGGL(skinny_stream_q2_kernel<false>, dim3(w8 + w3), dim3(256), 32768, st, a);
   if (hipGetLastError() != hipSuccess) return -1;
-  *n_split = a.n_split;
+  n_split[0] = a.s8.n_split; n_split[1] = a.s3.n_split;
   return 0;
 }
 
