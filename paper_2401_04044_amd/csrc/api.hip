@@ -71,6 +71,13 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     return launch_gemm_bf16(g, a, false, shape, n_split, st);
   };
   const int big_m = M > 1024;   // 256-row tiles only pay off with enough rows
+  // Share (percent) of the CU slots that 256x256 tiles keep busy: one workgroup per CU, whole
+  // rounds of 256.  Measured: where that share is high the large tile beats the smaller ones
+  // by 10-25 % (its main loop reads LDS half as often per MFMA), below about half it loses.
+  auto fill256 = [](int m, int n) -> int {
+    const int tiles = ((m + 255) / 256) * ((n + 255) / 256);
+    return tiles > 0 ? 100 * tiles / (256 * ((tiles + 255) / 256)) : 0;
+  };
 
   // G1: X * [W1h | P1] (SwiGLU: [gate/up heavy pairs | Pg | P1]) -> h1 (activated) and t
   if (L.n1 > 0) {
@@ -83,7 +90,8 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
     g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
     g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
-    FFS_TRY(run(g, act, big_m ? (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_DEEP) : GEMM_128x128, 1));
+    const int wide = fill256(M, L.n1) >= 50 ? GEMM_256x256 : (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_DEEP);
+    FFS_TRY(run(g, act, big_m ? wide : GEMM_128x128, 1));
   }
   if (rem_lr) {
     // G2: t * Q1 -> activation -> h2
@@ -94,7 +102,9 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
     g.act_cols = g.N; g.split_col = L.mp;
     g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
-    FFS_TRY(run(g, act, big_m ? GEMM_256x128 : GEMM_128x128, 1));
+    // (a short reduction leaves a 256x256 tile's epilogue uncovered: one workgroup per CU)
+    const int g2s = (!glu && g.K >= 1024 && fill256(M, g.N) >= 90) ? GEMM_256x256 : GEMM_256x128;
+    FFS_TRY(run(g, act, big_m ? g2s : GEMM_128x128, 1));
     // G3: h2 * P2 -> t2 into cat[:, kp:]  (long reduction: split-K, fixed-order sum)
     g = {};
     g.A = h2; g.lda = L.mp; g.a_tiled = L.tiled;
@@ -119,7 +129,7 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.Bt = sp + L.off_b4 + koff_bytes(koff); g.ldb = L.k4;
     g.M = M; g.N = dm; g.K = klen;
     g.split_col = dm; g.C0 = out; g.ldc0 = dm; g.n_store = dm;
-    return run(g, ACT_NONE, GEMM_128x128, 1);
+    return run(g, ACT_NONE, (big_m && fill256(M, dm) >= 90) ? GEMM_256x256 : GEMM_128x128, 1);
   };
   if (L.k4 > 0) {
     FFS_TRY(down(Y, 0, L.k4));
