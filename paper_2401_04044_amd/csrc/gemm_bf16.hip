@@ -590,8 +590,8 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
   if (score) {
     // calibration: row-major tokens, column sums of the activations in the epilogue
     if (a.a_tiled) return -1;
-    if (act == ACT_GELU) return launch_dl_cfg<256, 128, 32, 2, 2, 1, 3, ACT_GELU, false, true, false>(a, 1, st);
-    if (act == ACT_GLU) return launch_dl_cfg<256, 128, 32, 2, 2, 1, 3, ACT_GLU, false, true, false>(a, 1, st);
+    if (act == ACT_GELU) return launch_dl_cfg<256, 256, 32, 2, 4, 1, 3, ACT_GELU, false, true, false>(a, 1, st);
+    if (act == ACT_GLU) return launch_dl_cfg<256, 256, 32, 2, 4, 1, 3, ACT_GLU, false, true, false>(a, 1, st);
     return -1;
   }
   switch (shape) {
