@@ -1,6 +1,7 @@
 // Bit-exact top-k of the neuron scores (heavy-hitter selection, Sec. 4.1/5.1.1).
 // Integer work only: scores are mapped to order-preserving uint32 keys, the k-th
-// largest key is found by a 4-pass radix select, the chosen elements are
+// largest key is found by a 32-step search over its bits (each step one count over the
+// keys, which a workgroup of 1024 threads holds in registers), the chosen elements are
 // compacted in index order (equal keys: lowest indices first) and finally ranked
 // by counting, which yields the order (score descending, index ascending).
 #include "prep.h"
@@ -14,18 +15,46 @@ __device__ __forceinline__ uint32_t score_key(float s, int* saw_nan) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);  // monotone in the float order
 }
 
+// Exclusive prefix sum of v over the 1024 threads of a block, in thread order.  wsum: 16 ints
+// of LDS.  Every thread must call it.
+__device__ __forceinline__ int block_scan_1024(int v, int* wsum) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < 16; ++w) before += w < wave ? wsum[w] : 0;
+  return before + inc - v;
+}
+
+template <int KPT>
 __global__ void __launch_bounds__(1024) select_compact_kernel(const float* scores, int n, int k, uint32_t* keys,
                                                               uint32_t* cand_key, int32_t* cand_idx, int32_t* perm,
                                                               int32_t* nan_flag) {
-  __shared__ int hist[256];
   __shared__ int wsum[16];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_need, s_nan;
-  const int tid = threadIdx.x;
-  if (tid == 0) { s_nan = 0; s_prefix = 0; s_need = k; }
+  __shared__ int csum[2][16];
+  __shared__ int s_nan;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_nan = 0;
   __syncthreads();
+  // every thread owns a contiguous run of elements; the first KPT keys of the run stay in
+  // registers (key 0 = no element: real keys are > 0), longer runs continue in `keys`
+  const int run = (n + 1023) / 1024;
+  const int i0 = min(n, tid * run), i1 = min(n, i0 + run);
+  uint32_t kreg[KPT];
   int saw = 0;
-  for (int i = tid; i < n; i += 1024) keys[i] = score_key(scores[i], &saw);
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int i = i0 + j;
+    kreg[j] = (j < run && i < i1) ? score_key(scores[i], &saw) : 0u;
+  }
+  for (int i = i0 + KPT; i < i1; ++i) keys[i] = score_key(scores[i], &saw);
   if (saw) s_nan = 1;
   __syncthreads();
   if (tid == 0 && nan_flag) *nan_flag = s_nan ? -7 : 0;
@@ -33,69 +62,84 @@ __global__ void __launch_bounds__(1024) select_compact_kernel(const float* score
     if (perm) for (int i = tid; i < n; i += 1024) perm[i] = i;
     return;
   }
-  // radix select, most significant byte first
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
+  // number of keys >= c (c > 0), the same value in every thread; buf alternates so that one
+  // barrier per call is enough
+  int buf = 0;
+  auto count_ge = [&](uint32_t c) -> int {
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) cnt += kreg[j] >= c;
+    for (int i = i0 + KPT; i < i1; ++i) cnt += keys[i] >= c;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    if (lane == 0) csum[buf][wave] = cnt;
     __syncthreads();
-    const uint32_t prefix = s_prefix;
-    for (int i = tid; i < n; i += 1024) {
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += csum[buf][w];
+    buf ^= 1;
+    return tot;
+  };
+  // the k-th largest key, bit by bit from the top: the largest P with at least k keys >= P
+  uint32_t thr = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t c = thr | (1u << bit);
+    if (count_ge(c) >= k) thr = c;
+  }
+  const int above = thr == 0xffffffffu ? 0 : count_ge(thr + 1u);
+  const int need = k - above;  // how many keys equal to thr are taken (lowest indices)
+  // Compaction in index order over the threads' runs: two block scans (equal keys, then
+  // selected elements).
+  int eq_cnt = 0;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) eq_cnt += kreg[j] == thr;     // thr > 0: empty slots never match
+  for (int i = i0 + KPT; i < i1; ++i) eq_cnt += keys[i] == thr;
+  int eq_before = block_scan_1024(eq_cnt, wsum);
+  int sel_cnt = 0;
+  {
+    int e = eq_before;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+      const bool eq = kreg[j] == thr;
+      sel_cnt += kreg[j] > thr || (eq && e < need);
+      e += eq;
+    }
+    for (int i = i0 + KPT; i < i1; ++i) {
       const uint32_t key = keys[i];
-      const bool match = pass == 0 ? true : ((key >> (shift + 8)) == prefix);
-      if (match) atomicAdd(&hist[(key >> shift) & 255], 1);
+      const bool eq = key == thr;
+      sel_cnt += key > thr || (eq && e < need);
+      e += eq;
     }
-    __syncthreads();
-    if (tid == 0) {
-      int need = s_need, cum = 0, b = 255;
-      for (; b > 0; --b) {
-        if (cum + hist[b] >= need) break;
-        cum += hist[b];
-      }
-      s_need = need - cum;
-      s_prefix = (prefix << 8) | (uint32_t)b;
-    }
-    __syncthreads();
   }
-  const uint32_t thr = s_prefix;
-  const int need = s_need;  // how many keys equal to thr are taken (lowest indices)
-  int eq_base = 0, sel_base = 0, rest_base = 0;
-  for (int base = 0; base < n; base += 1024) {
-    const int i = base + tid;
-    const bool in = i < n;
-    const uint32_t key = in ? keys[i] : 0u;
-    const bool eq = in && key == thr;
-    int tot;
-    const int eq_rank = eq_base + block_prefix_1024(eq, wsum, &tot);
-    eq_base += tot;
-    const bool sel = in && (key > thr || (eq && eq_rank < need));
-    const int pos = sel_base + block_prefix_1024(sel, wsum, &tot);
-    sel_base += tot;
-    const bool rest = in && !sel;
-    const int rpos = rest_base + block_prefix_1024(rest, wsum, &tot);
-    rest_base += tot;
-    if (sel) { cand_key[pos] = key; cand_idx[pos] = i; }
-    if (rest && perm) perm[k + rpos] = i;
-  }
+  int sp = block_scan_1024(sel_cnt, wsum);   // selected elements before this thread's run
+  auto place = [&](uint32_t key, int i) {
+    const bool eq = key == thr;
+    const bool sel = key > thr || (eq && eq_before < need);
+    eq_before += eq;
+    if (sel) { cand_key[sp] = key; cand_idx[sp] = i; ++sp; }
+    else if (perm) perm[k + (i - sp)] = i;     // i - sp = elements before i that were not selected
+  };
+#pragma unroll
+  for (int j = 0; j < KPT; ++j)
+    if (i0 + j < i1 && j < run) place(kreg[j], i0 + j);
+  for (int i = i0 + KPT; i < i1; ++i) place(keys[i], i);
 }
 
-// rank of candidate a = #(keys greater) + #(equal keys at an earlier position)
+// rank of candidate a = #(keys greater) + #(equal keys at an earlier position); one wavefront
+// per candidate, the lanes share the comparisons
 __global__ void __launch_bounds__(256) select_rank_kernel(const uint32_t* cand_key, const int32_t* cand_idx, int k,
                                                           int32_t* idx, int32_t* perm) {
-  __shared__ uint32_t tile[256];
-  const int a = blockIdx.x * 256 + threadIdx.x;
-  const uint32_t ka = a < k ? cand_key[a] : 0u;
+  const int a = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (a >= k) return;
+  const uint32_t ka = cand_key[a];
   int rank = 0;
-  for (int b0 = 0; b0 < k; b0 += 256) {
-    __syncthreads();
-    tile[threadIdx.x] = (b0 + threadIdx.x) < k ? cand_key[b0 + threadIdx.x] : 0u;
-    __syncthreads();
-    const int lim = min(256, k - b0);
-    for (int b = 0; b < lim; ++b) {
-      const uint32_t kb = tile[b];
-      rank += (kb > ka) || (kb == ka && (b0 + b) < a);
-    }
+  for (int b = lane; b < k; b += 64) {
+    const uint32_t kb = cand_key[b];
+    rank += (kb > ka) || (kb == ka && b < a);
   }
-  if (a < k) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) rank += __shfl_xor(rank, o);
+  if (lane == 0) {
     const int32_t v = cand_idx[a];
     idx[rank] = v;
     if (perm) perm[rank] = v;
@@ -110,11 +154,16 @@ int launch_select(const float* scores, int d_ff, int k, int32_t* idx, int32_t* p
   uint32_t* keys = (uint32_t*)ws;
   uint32_t* cand_key = keys + d_ff;
   int32_t* cand_idx = (int32_t*)(cand_key + d_ff);
-  hipLaunchKernelGGL(select_compact_kernel, dim3(1), dim3(1024), 0, st, scores, d_ff, k, keys, cand_key, cand_idx,
-                     perm, nan_flag);
+  // registers for the whole run where it is short (the search makes 33 passes over them)
+  if (d_ff <= 8 * 1024)
+    hipLaunchKernelGGL(select_compact_kernel<8>, dim3(1), dim3(1024), 0, st, scores, d_ff, k, keys, cand_key,
+                       cand_idx, perm, nan_flag);
+  else
+    hipLaunchKernelGGL(select_compact_kernel<32>, dim3(1), dim3(1024), 0, st, scores, d_ff, k, keys, cand_key,
+                       cand_idx, perm, nan_flag);
   if (hipGetLastError() != hipSuccess) return -1;
   if (k > 0) {
-    hipLaunchKernelGGL(select_rank_kernel, dim3((k + 255) / 256), dim3(256), 0, st, cand_key, cand_idx, k, idx, perm);
+    hipLaunchKernelGGL(select_rank_kernel, dim3((k + 3) / 4), dim3(256), 0, st, cand_key, cand_idx, k, idx, perm);
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;
