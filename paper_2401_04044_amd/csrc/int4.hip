@@ -23,9 +23,6 @@
 // MFMA operand per lane and 32-element step).
 #include "int4.h"
 #include <type_traits>
-#ifdef FFS_TRACE
-#include <cstdlib>
-#endif
 
 namespace ffsplit {
 
@@ -361,15 +358,7 @@ struct Phase1Args {
   int hl, h_off_q;
   unsigned* counters;     // the second kernel's arrival counters, cleared here
   int n_counters;
-#ifdef FFS_TRACE
-  unsigned long long* trace;
-#endif
 };
-#ifdef FFS_TRACE
-#define FFS_TR(k) do { if (tid == 0) p.trace[(int64_t)blockIdx.x * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define FFS_TR(k) do { } while (0)
-#endif
 
 
 template <int GPW, int NWV, int NUP>
@@ -380,7 +369,6 @@ __global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args 
   const int n = lane & 15, q = lane >> 4;
   const int wg = blockIdx.x;
   const bool heavy = wg < p.n_htiles;
-  FFS_TR(0);
 
   // The first workgroup also clears what the second kernel expects to be zero: the arrival
   // counters, and the columns of h that no neuron writes (padding up to whole 128-blocks).
@@ -463,7 +451,6 @@ __global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args 
     xsum[i] = s;
   }
 
-  FFS_TR(1);
   // cross-wave sum of `nt` tiles' partials, activation, store of h (bf16 pairs)
   auto finish = [&](int nt, int col0, int col_step) {
     __syncthreads();
@@ -505,9 +492,7 @@ __global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args 
       red[0][wave][0][lane * 4 + r] = au[r];
       red[0][wave][1][lane * 4 + r] = ag[r];
     }
-    FFS_TR(2);
     finish(1, wg * 16, 0);
-    FFS_TR(3);
     return;
   }
 
@@ -552,16 +537,12 @@ __global__ void __launch_bounds__(NWV * 64) int4_phase1_kernel(const Phase1Args 
   int qt = qt0;
   for (; qt + 1 < qt_end; ++qt) {
     tile(qt, std::true_type{});
-    FFS_TR(2 + 2 * (qt - qt0));
     finish(1, p.h_off_q + qt * 16, 16);
     __syncthreads();   // red is reused
-    FFS_TR(3 + 2 * (qt - qt0));
   }
   if (qt < qt_end) {
     tile(qt, std::false_type{});
-    FFS_TR(2 + 2 * (qt - qt0));
     finish(1, p.h_off_q + qt * 16, 16);
-    FFS_TR(3 + 2 * (qt - qt0));
   }
 }
 
@@ -596,9 +577,6 @@ struct Phase2Args {
   int JBr, jp128;
   float* part;             // [G][S][2][16][128] fp32 (heavy, remainder)
   unsigned* counters;      // [G] arrivals, zero on entry
-#ifdef FFS_TRACE
-  unsigned long long* trace;
-#endif
   bf16_t* Y;
   bf16_t* Yh;
   bf16_t* Yr;
@@ -615,11 +593,6 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
   const int cg = blockIdx.x, sp = blockIdx.y;
-#ifdef FFS_TRACE
-#undef FFS_TR
-#define FFS_TR(k) do { if (tid == 0) p.trace[((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#endif
-  FFS_TR(0);
 
   const int NJ = p.JBr > sp ? (p.JBr - sp + p.S - 1) / p.S : 0;           // int4 blocks sp, sp+S, ...
   const int NHq = p.JBh * 4 > sp ? (p.JBh * 4 - sp + p.S - 1) / p.S : 0;  // heavy steps sp, sp+S, ...
@@ -674,7 +647,6 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
     }
     // 2. the weights
     load_down(pass);
-    if (pass == 0) FFS_TR(1);
     // 3. operands into LDS (the P2_MAXJ + P2_MAXH weight loads may still be in flight)
 #pragma unroll
     for (int i = 0; i < HPW; ++i) {
@@ -704,9 +676,7 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
         if (!hv) hsum += part;
       }
     }
-    FFS_TR(2 + 3 * pass);
     __syncthreads();
-    FFS_TR(3 + 3 * pass);
     static_for<0, P2_MAXJ>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       wait_loads<P2_MAXJ - 1 - i + P2_MAXH>(w2[i]);
@@ -729,7 +699,6 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
         acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc_h, 0, 0, 0);
       }
     });
-    FFS_TR(4 + 3 * pass);
   }
   // the constant 136 of the offset-binary codes: subtract 136 * (sum of this workgroup's scaled activations)
   hsum += __shfl_xor(hsum, 16);
@@ -759,10 +728,8 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's device-scope stores are done
   __syncthreads();
-  FFS_TR(8);
   if (tid == 0) flag_s = atomicAdd(&p.counters[cg], 1u) == (unsigned)(p.S - 1);
   __syncthreads();
-  FFS_TR(9);
   if (!flag_s) return;
   // last workgroup of the column group: fixed-order sum over the splits, two outputs per thread
   for (int o = 2 * tid; o < 16 * 128; o += 1024) {
@@ -787,7 +754,6 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
     if (p.Yh) *(uint32_t*)(p.Yh + oi) = pack_bf16x2(a0, a1);
     if (p.Yr) *(uint32_t*)(p.Yr + oi) = pack_bf16x2(b0, b1);
   }
-  FFS_TR(10);
 }
 
 // ---------------------------------------------------------------- expansion for large batches
@@ -948,9 +914,6 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     w.off_cnt = off; off = align256(off + (size_t)L.groups * 4);
     w.off_part = off; off = align256(off + (size_t)L.groups * S * 2 * 16 * 128 * 4);
     w.n_split = S;
-#ifdef FFS_TRACE
-    off = align256(off + (1u << 20));
-#endif
     w.total_bytes = off;
     return w;
   }
@@ -1042,9 +1005,6 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
     a.n_qtiles = n_q; a.tpw = tpw;
     a.h = (bf16_t*)(ws + w.off_h); a.hl = hl; a.h_off_q = L.kp128;
     a.counters = (unsigned*)(ws + w.off_cnt); a.n_counters = G;
-#ifdef FFS_TRACE
-    a.trace = (unsigned long long*)(ws + w.off_part);
-#endif
     if (grid1 > 0) {
       int rc;
       if (gpw <= 1) rc = launch_phase1<1, 8>(a, grid1, st);
@@ -1065,10 +1025,6 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
     b.Y = (bf16_t*)Y + (int64_t)t0 * dm;
     b.Yh = Y_heavy ? (bf16_t*)Y_heavy + (int64_t)t0 * dm : nullptr;
     b.Yr = Y_rem ? (bf16_t*)Y_rem + (int64_t)t0 * dm : nullptr;
-#ifdef FFS_TRACE
-    if (getenv("FFS_ONLY_P1")) continue;
-    b.trace = (unsigned long long*)(ws + w.total_bytes - (1u << 20));
-#endif
     hipLaunchKernelGGL(int4_phase2_kernel, dim3(G, S), dim3(512), 0, st, b);
     if (hipGetLastError() != hipSuccess) return -1;
   }
