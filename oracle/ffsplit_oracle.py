@@ -13,7 +13,9 @@ Pins (tests/test_oracle_pins.py): dense special cases (heavy = all neurons,
 full-rank factors), Y = Y1 + Y2, the neuron-removal identity of Sec. 4.1 by
 brute force, exhaustive ranking for top-k, enumeration of the levels of the 3-,
 4- and 8-bit quantiser,
-closed-form identities of GeLU/SiLU, the parameter-count figure of Sec. 5.1.1.
+closed-form identities of GeLU/SiLU, the parameter-count figure of Sec. 5.1.1;
+the randomised factorisation against exact recovery, the projector identities,
+Eckart-Young from below and the published expected-error bound from above.
 Forward outputs at the full workload shapes have no pin beyond those identities
 holding at full shape: parity unpinned there (the oracle is the definition).
 
@@ -301,6 +303,58 @@ def forward_split(X, W1, W2, Wg, idx, act, rem_kind, factors=None, group=128, bi
     else:
         raise ValueError(rem_kind)
     return Y1 + Y2, Y1, Y2
+
+
+# ---------------------------------------------------------------- remainder factorisation on the device's plan
+
+def _fmix32(h):
+    """Finaliser of the public MurmurHash3 (32-bit), on uint64 arrays holding 32-bit values."""
+    m = np.uint64(0xFFFFFFFF)
+    h = h & m
+    h ^= h >> np.uint64(16)
+    h = (h * np.uint64(0x85EBCA6B)) & m
+    h ^= h >> np.uint64(13)
+    h = (h * np.uint64(0xC2B2AE35)) & m
+    h ^= h >> np.uint64(16)
+    return h
+
+
+def rademacher(seed, stream, n_rows, n_cols):
+    """Test matrix of the randomised range finder: entry (i, j) = +1 / -1 from the top bit of
+    fmix32(index * 0x9E3779B1 + fmix32(seed + 0x9E3779B9 * stream)), index = i * n_cols + j.
+    A counter-based generator, so that the device draws exactly the same signs."""
+    m = np.uint64(0xFFFFFFFF)
+    key = _fmix32(np.array([(int(seed) + 0x9E3779B9 * int(stream)) & 0xFFFFFFFF], np.uint64))[0]
+    idx = np.arange(n_rows * n_cols, dtype=np.uint64)
+    h = _fmix32(((idx * np.uint64(0x9E3779B1)) & m) + key)
+    return np.where((h >> np.uint64(31)) & np.uint64(1), -1.0, 1.0).reshape(n_rows, n_cols)
+
+
+def range_finder(Z, r, seed, stream):
+    """Randomised range finder (Halko, Martinsson, Tropp 2011, Alg. 4.1) for Z [d, m], m
+    columns: Y = Z Omega^T with a Rademacher test matrix Omega [r, m], B = an orthonormal basis
+    of range(Y) [d, r]; the rank-r approximation is B (B^T Z).  Stands in for the SVD of
+    Sec. 5.1.1 where the split is built on the device.  Returns (B, B^T Z)."""
+    Z = np.asarray(Z, F64)
+    Om = rademacher(seed, stream, r, Z.shape[1])
+    B, _ = np.linalg.qr(Z @ Om.T)
+    return B, B.T @ Z
+
+
+def factorize_remainder(W1, W2, Wg, idx, r, seed):
+    """Rank-r factors of each remainder matrix on its own (Sec. 4.2 / 5.1.1), by the range
+    finder above on the d_model side of every matrix: streams 0 (W1), 1 (Wg), 2 (W2).
+    Same conventions as the factors forward_remainder_lowrank takes."""
+    sw = split_weights(W1, W2, Wg, idx)
+    out = {}
+    B, C = range_finder(sw["W1r"], r, seed, 0)
+    out["P1"], out["Q1"] = B, C
+    if sw["Wgr"] is not None:
+        B, C = range_finder(sw["Wgr"], r, seed, 1)
+        out["Pg"], out["Qg"] = B, C
+    B, C = range_finder(sw["W2r"].T, r, seed, 2)
+    out["P2"], out["Q2"] = C.T, B.T
+    return out
 
 
 # ---------------------------------------------------------------- layer stack

@@ -385,6 +385,74 @@ def test_w3h8_forward_uses_dequantised_heavy_and_remainder():
         assert (not Y1a.any()) if len(ids) == 0 else (not Y2a.any())
 
 
+# ----------------------------------------------------------------- randomised remainder factorisation
+
+def test_rademacher_is_counter_based_and_balanced():
+    a = orc.rademacher(7, 2, 33, 129)
+    assert set(np.unique(a)) == {-1.0, 1.0}
+    assert np.array_equal(a, orc.rademacher(7, 2, 33, 129))
+    assert not np.array_equal(a, orc.rademacher(7, 1, 33, 129)) and not np.array_equal(a, orc.rademacher(8, 2, 33, 129))
+    assert abs(a.mean()) < 0.05 and abs((a[:, :-1] * a[:, 1:]).mean()) < 0.05     # no bias, no lag-1 correlation
+    # entry (i, j) by the scalar recipe, plain Python integers
+    def fmix(h):
+        h &= 0xFFFFFFFF; h ^= h >> 16; h = (h * 0x85EBCA6B) & 0xFFFFFFFF; h ^= h >> 13
+        h = (h * 0xC2B2AE35) & 0xFFFFFFFF; h ^= h >> 16
+        return h
+    key = fmix(7 + 0x9E3779B9 * 2)
+    for i, j in ((0, 0), (5, 17), (32, 128)):
+        h = fmix(((i * 129 + j) * 0x9E3779B1 & 0xFFFFFFFF) + key)
+        assert a[i, j] == (-1.0 if h >> 31 else 1.0)
+
+
+def test_range_finder_recovers_low_rank_and_obeys_the_bounds():
+    rng = np.random.default_rng(31)
+    d, m, r = 24, 60, 8
+    # (a) rank(Z) <= r: exact recovery
+    Z = rng.standard_normal((d, 5)) @ rng.standard_normal((5, m))
+    B, C = orc.range_finder(Z, r, seed=3, stream=0)
+    assert np.allclose(B.T @ B, np.eye(r), atol=1e-12)
+    assert np.allclose(B @ C, Z, atol=1e-10)
+    # (b) general matrix with known singular values: B B^T is a projector, the error is at
+    # least the optimal rank-r error (Eckart-Young) and, averaged over seeds, within the
+    # published bound E||Z - B B^T Z||_F <= sqrt(1 + k / (p - 1)) * tail_k for k = r - p
+    sv = 2.0 ** -np.arange(d)
+    U, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    V, _ = np.linalg.qr(rng.standard_normal((m, d)))
+    Z = (U * sv) @ V.T
+    errs = []
+    for seed in range(40):
+        B, C = orc.range_finder(Z, r, seed, 1)
+        P = B @ B.T
+        assert np.allclose(P @ P, P, atol=1e-12) and np.allclose(P, P.T, atol=1e-12)
+        assert np.allclose(C, B.T @ Z, atol=1e-12)
+        errs.append(np.linalg.norm(Z - B @ C))
+    best = np.sqrt(np.sum(sv[r:] ** 2))
+    assert min(errs) >= best * (1 - 1e-9)
+    k, p_over = r - 4, 4
+    bound = np.sqrt(1 + k / (p_over - 1)) * np.sqrt(np.sum(sv[k:] ** 2))
+    assert np.mean(errs) <= bound
+
+
+def test_factorize_remainder_conventions():
+    X, W1, W2, Wg = tiny("swiglu", T=4, d=8, f=20, seed=41)
+    idx = np.array([3, 11], np.int32)
+    fac = orc.factorize_remainder(W1, W2, Wg, idx, 8, seed=5)       # r = d: the d_model side is spanned
+    rest = wl.remainder_order(idx, 20)
+    assert fac["P1"].shape == (8, 8) and fac["Q1"].shape == (8, 18) and fac["P2"].shape == (18, 8)
+    assert np.allclose(fac["P1"] @ fac["Q1"], W1[:, rest], atol=1e-12)
+    assert np.allclose(fac["Pg"] @ fac["Qg"], Wg[:, rest], atol=1e-12)
+    assert np.allclose(fac["P2"] @ fac["Q2"], W2[rest, :], atol=1e-12)
+    # hence the split with these factors is the dense layer
+    Y, _, _ = orc.forward_split(X, W1, W2, Wg, idx, "swiglu", "lowrank", fac)
+    assert np.allclose(Y, orc.dense_ffn(X, W1, W2, Wg, "swiglu"), atol=1e-12)
+    # at lower rank: the product is the projection onto the basis, each matrix on its own stream
+    fac = orc.factorize_remainder(W1, W2, Wg, idx, 3, seed=5)
+    B = fac["P1"]
+    assert np.allclose(fac["P1"] @ fac["Q1"], B @ B.T @ W1[:, rest], atol=1e-12)
+    Bd = fac["Q2"].T
+    assert np.allclose(fac["P2"] @ fac["Q2"], W2[rest, :] @ Bd @ Bd.T, atol=1e-12)
+
+
 # ----------------------------------------------------------------- stack reading
 
 def test_token_rms_normalise():
