@@ -50,7 +50,8 @@ enum { FFSPLIT_REM_NONE = 0,      /* FFN_2 dropped                              
 enum { FFSPLIT_SCORE_SUMSQ = 0,   /* Eq. 3: ||sigma(X U[:,j])||_F^2 * ||V[j,:]||_F^2      */
        FFSPLIT_SCORE_MEAN_L2 = 1, /* mean_t ||sigma(x_t U[:,j]) V[j,:]||_2                */
        FFSPLIT_SCORE_ACT_ONLY = 2 /* ||sigma(X U[:,j])||_F^2 (Sec. 2's heavy-hitter norm) */ };
-enum { FFSPLIT_WS_SCORE = 0, FFSPLIT_WS_SELECT = 1, FFSPLIT_WS_BUILD = 2, FFSPLIT_WS_FORWARD = 3 };
+enum { FFSPLIT_WS_SCORE = 0, FFSPLIT_WS_SELECT = 1, FFSPLIT_WS_BUILD = 2, FFSPLIT_WS_FORWARD = 3,
+       FFSPLIT_WS_FACTORIZE = 4 };
 
 enum { FFSPLIT_OK = 0,
        FFSPLIT_E_NULLPTR = -1,     /* a required pointer is NULL                          */
@@ -144,6 +145,31 @@ int ffsplit_select_heavy(const float* scores, int32_t d_ff, int32_t k,
 int ffsplit_build_split(const ffsplit_desc_t* desc, const void* W1, const void* Wg,
                         const void* W2, const int32_t* idx, const void* const* factors,
                         void* split, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Rank-r factors of the remainder matrices, computed on the device, in the form
+ * ffsplit_build_split takes for LOWRANK (Sec. 4.2 / 5.1.1: a low-rank
+ * decomposition of U2 and V2, each matrix on its own).  In place of a full SVD
+ * this is the randomised range finder of Halko, Martinsson and Tropp (2011,
+ * Alg. 4.1) on the d_model side of each matrix: with Z [d_model, m] =
+ * W1[:, rest], Wg[:, rest] or W2[rest, :]^T (rest = the non-heavy neurons
+ * ascending), Y = Z Omega^T for a Rademacher test matrix Omega [r, m], B an
+ * orthonormal basis of range(Y), the approximation is Z ~= B (B^T Z).
+ *   P1 = B, Q1 = B^T Z (likewise Pg, Qg);  Q2 = B^T, P2 = Z^T B.
+ * Omega(i, j) = +1 / -1 from the top bit of
+ *   fmix32((i m + j) * 0x9E3779B1 + fmix32(seed + 0x9E3779B9 * stream)),
+ * fmix32 = the 32-bit finaliser of MurmurHash3, stream = 0 (W1), 1 (Wg), 2 (W2):
+ * the same signs on every machine.  All arithmetic in fp32; the factors are
+ * written in desc->dtype.  Only their products are determined (the basis B is
+ * fixed up to a rotation).  desc: rem_kind LOWRANK, 0 < rank <= min(d_model, m).
+ * factors: HOST array of 6 device pointers P1 [d_model, r], Q1 [r, m], Pg, Qg,
+ * P2 [m, r], Q2 [r, d_model] (Pg, Qg may be NULL unless SWIGLU), written.
+ * workspace: ffsplit_workspace_bytes(desc, FFSPLIT_WS_FACTORIZE, 0).
+ */
+int ffsplit_factorize_remainder(const ffsplit_desc_t* desc, const void* W1, const void* Wg,
+                                const void* W2, const int32_t* idx, uint32_t seed,
+                                void* const* factors, void* workspace, size_t workspace_bytes,
+                                void* stream);
 
 /*
  * Split forward pass (Eq. 2):  Y = FFN_1(X) + FFN_2~(X), with

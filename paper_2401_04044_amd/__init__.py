@@ -6,9 +6,10 @@ HIP kernels.  PyTorch supplies device memory and the stream, nothing else.
 There is no CPU fallback: a missing library raises at import of `binding`.
 """
 from .binding import (  # noqa: F401
-    ACT_GELU, ACT_SWIGLU, F32, BF16, REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4,
+    ACT_GELU, ACT_SWIGLU, F32, BF16, REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4, REM_W3H8,
     SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY,
-    WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD,
+    WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE,
     Desc, FFSplitError, lib, lib_path, status_string, make_desc,
     workspace_bytes, split_bytes, score_neurons, select_heavy, build_split, forward, split_export,
+    factorize_remainder,
 )

@@ -8,7 +8,7 @@ ACT_GELU, ACT_SWIGLU = 0, 1
 F32, BF16 = 0, 1
 REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4, REM_W3H8 = 0, 1, 2, 3, 4
 SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY = 0, 1, 2
-WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD = 0, 1, 2, 3
+WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE = 0, 1, 2, 3, 4
 E_NONFINITE = -7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -51,6 +51,8 @@ def _load():
     L.ffsplit_build_split.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
     L.ffsplit_forward.restype = ctypes.c_int
     L.ffsplit_forward.argtypes = [dp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.ffsplit_factorize_remainder.restype = ctypes.c_int
+    L.ffsplit_factorize_remainder.argtypes = [dp, vp, vp, vp, vp, ctypes.c_uint32, ctypes.POINTER(vp), vp, sz, vp]
     L.ffsplit_split_export.restype = ctypes.c_int
     L.ffsplit_split_export.argtypes = [dp, vp, i32, vp, vp, vp]
     return L
@@ -144,6 +146,25 @@ def build_split(desc, W1, Wg, W2, idx, factors=None, split=None, workspace=None)
                                  _ptr(ws), ws.numel(), _stream())
     _check(rc, "ffsplit_build_split")
     return split
+
+
+def factorize_remainder(desc, W1, Wg, W2, idx, seed=0, workspace=None):
+    """Rank-r factors of the remainder on the device: dict P1, Q1, Pg, Qg, P2, Q2 (device tensors)."""
+    dev = W1.device
+    d, m, r = desc.d_model, desc.d_ff - desc.k, desc.rank
+    glu = Wg is not None
+    shapes = {"P1": (d, r), "Q1": (r, m), "Pg": (d, r), "Qg": (r, m), "P2": (m, r), "Q2": (r, d)}
+    out = {nm: (torch.empty(sh, dtype=W1.dtype, device=dev) if (glu or nm not in ("Pg", "Qg")) else None)
+           for nm, sh in shapes.items()}
+    arr = (ctypes.c_void_p * 6)()
+    for i, nm in enumerate(("P1", "Q1", "Pg", "Qg", "P2", "Q2")):
+        arr[i] = None if out[nm] is None else out[nm].data_ptr()
+    ws = _ws(workspace_bytes(desc, WS_FACTORIZE, 0), workspace, dev)
+    rc = lib.ffsplit_factorize_remainder(ctypes.byref(desc), _ptr(W1), _ptr(Wg), _ptr(W2),
+                                         _ptr(idx) if idx is not None and idx.numel() > 0 else None,
+                                         ctypes.c_uint32(seed), arr, _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_factorize_remainder")
+    return out
 
 
 def forward(desc, split, X, Y=None, want_parts=False, workspace=None):

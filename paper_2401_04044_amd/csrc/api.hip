@@ -5,6 +5,7 @@
 #include "prep.h"
 #include "int4.h"
 #include "quant.h"
+#include "factor.h"
 
 using namespace ffsplit;
 
@@ -179,6 +180,10 @@ size_t ffsplit_workspace_bytes(const ffsplit_desc_t* d, int32_t call_id, int64_t
     return w.total_bytes;
   }
   if (call_id == FFSPLIT_WS_BUILD) return build_ws_bytes(*d);
+  if (call_id == FFSPLIT_WS_FACTORIZE) {
+    if (d->rem_kind != FFSPLIT_REM_LOWRANK) return 0;
+    return build_ws_bytes(*d) + factorize_ws_bytes(*d);
+  }
   if (call_id == FFSPLIT_WS_FORWARD) {
     const Layout L = make_layout(*d);
     const FwdWs w = make_fwd_ws(*d, L, T);
@@ -374,6 +379,32 @@ int ffsplit_build_split(const ffsplit_desc_t* d, const void* W1, const void* Wg,
     return FFSPLIT_OK;
   }
   return FFSPLIT_E_UNSUPPORTED;
+}
+
+int ffsplit_factorize_remainder(const ffsplit_desc_t* d, const void* W1, const void* Wg, const void* W2,
+                                const int32_t* idx, uint32_t seed, void* const* factors, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  int rc = check_desc(d, true);
+  if (rc) return rc;
+  if (d->rem_kind != FFSPLIT_REM_LOWRANK) return FFSPLIT_E_BADDESC;
+  const bool glu = d->act == FFSPLIT_ACT_SWIGLU;
+  const int m = d->d_ff - d->k;
+  if (m <= 0) return FFSPLIT_OK;
+  if (!W1 || !W2 || (glu && !Wg) || (d->k > 0 && !idx) || !factors) return FFSPLIT_E_NULLPTR;
+  for (int i = 0; i < 6; ++i) {
+    const bool gate = (i == 2 || i == 3);
+    if ((!gate || glu) && !factors[i]) return FFSPLIT_E_NULLPTR;
+    if (misaligned(factors[i])) return FFSPLIT_E_ALIGN;
+  }
+  if (misaligned(W1) || misaligned(Wg) || misaligned(W2)) return FFSPLIT_E_ALIGN;
+  const size_t pre = build_ws_bytes(*d);
+  if (!workspace || workspace_bytes < pre + factorize_ws_bytes(*d)) return FFSPLIT_E_WORKSPACE;
+  if ((uintptr_t)workspace & 255u) return FFSPLIT_E_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* rest = (int32_t*)workspace;
+  FFS_TRY(launch_rest_order(idx, d->k, d->d_ff, rest, (int32_t*)workspace + d->d_ff, st));
+  FFS_TRY(launch_factorize(*d, W1, Wg, W2, rest, seed, factors, (char*)workspace + pre, st));
+  return FFSPLIT_OK;
 }
 
 int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, int64_t T, void* Y, void* Y_heavy,

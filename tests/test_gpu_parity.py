@@ -347,3 +347,53 @@ def test_w3h8_edge_sets(ff):
             torch.cuda.synchronize()
             want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "w3h8", group=128)
             assert relf(host(Y), want[0]) < TOL["bf16"], T
+
+
+# ---------------------------------------------------------------- remainder factorisation on the device
+
+FACT_CASES = [
+    ("gelu_f32", f32_variant(reduced(C2, 96, 160, rank=16)), 1e-4),
+    ("swiglu_f32_ragged", f32_variant(reduced(C3, 64, 203, rank=18)), 1e-4),
+    ("gelu_f32_full_side", f32_variant(reduced(C2, 64, 200, rank=64)), 1e-4),
+    ("swiglu_bf16", reduced(C3, 192, 700, rank=64), 6e-3),
+    ("gelu_bf16", reduced(C2, 256, 1000, rank=100), 6e-3),
+]
+
+
+@pytest.mark.parametrize("name,cfg,tol", FACT_CASES, ids=[c[0] for c in FACT_CASES])
+def test_factorize_remainder_matches_oracle(ff, name, cfg, tol):
+    """Only the products are determined (the basis is fixed up to a rotation): P Q against the
+    oracle's, the basis orthonormal, and the split built from the device's factors against the
+    oracle's forward on those same factors."""
+    L = wl.make_layer(cfg)
+    idx = L["planted"]
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc = desc_for(ff, cfg, "lowrank")
+    idx_d = torch.from_numpy(idx).cuda()
+    fd = ff.factorize_remainder(desc, Ld["W1"], Ld["Wg"], Ld["W2"], idx_d, seed=11)
+    fd2 = ff.factorize_remainder(desc, Ld["W1"], Ld["Wg"], Ld["W2"], idx_d, seed=11)
+    torch.cuda.synchronize()
+    got = {k: host(v) for k, v in fd.items() if v is not None}
+    assert all(torch.equal(fd[k], fd2[k]) for k in got)                         # deterministic
+    want = orc.factorize_remainder(L["W1"], L["W2"], L["Wg"], idx, cfg.rank, seed=11)
+    for p, q in (("P1", "Q1"), ("Pg", "Qg"), ("P2", "Q2")):
+        if p not in want:
+            continue
+        e = relf(got[p] @ got[q], want[p] @ want[q])
+        assert e < tol, (p, e)
+    B = got["P1"]
+    assert np.linalg.norm(B.T @ B - np.eye(cfg.rank)) / np.sqrt(cfg.rank) < (1e-4 if cfg.dtype == "f32" else 6e-3)
+    if name == "gelu_f32_full_side":                                             # r = d_model: nothing is lost
+        rest = wl.remainder_order(idx, cfg.d_ff)
+        assert relf(got["P1"] @ got["Q1"], L["W1"][:, rest]) < 1e-4
+    else:                                                                        # the seed matters
+        other = orc.factorize_remainder(L["W1"], L["W2"], L["Wg"], idx, cfg.rank, seed=12)
+        assert relf(other["P1"] @ other["Q1"], want["P1"] @ want["Q1"]) > 10 * tol
+    # the device's factors through build and forward
+    T = 50
+    X = wl.make_tokens(cfg, T)
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], idx_d, fd)
+    Y = ff.forward(desc, split, dev(X, cfg.dtype))
+    torch.cuda.synchronize()
+    ref = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "lowrank", got)
+    assert relf(host(Y), ref[0]) < TOL[cfg.dtype]
