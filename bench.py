@@ -120,6 +120,9 @@ def main():
     facd = {k: dev(v) for k, v in fac.items()}
     split0 = ff.build_split(desc, W1, None, W2, idx, facd)
     t_build, _ = timed(lambda: ff.build_split(desc, W1, None, W2, idx, facd, split0), 3, 1)
+    ws_fact = torch.empty(ff.workspace_bytes(desc, ff.WS_FACTORIZE, 0), dtype=torch.uint8, device="cuda")
+    t_fact, _ = timed(lambda: ff.factorize_remainder(desc, W1, None, W2, idx, 1, ws_fact), 2, 1)
+    del ws_fact
     splits = [split0] + [split0.clone() for _ in range(max(args.copies, 1) - 1)]
     Xe_h = wl.make_tokens(cfg, T)
     Xs = [dev(Xe_h)] + [dev(wl.make_tokens(cfg, T, wl.gen.S_EVAL, layer=i)) for i in range(1, len(splits))]
@@ -169,7 +172,8 @@ def main():
         "parity": {"rel_frobenius_vs_oracle_32_rows": rel_err, "heavy_set_equals_planted": heavy_ok},
         "pipeline": {"score_us_T4096": t_score * 1e6,
                      "score_tflops": 2.0 * cfg.calib_T * cfg.d_model * cfg.d_ff / t_score / 1e12,
-                     "select_us": t_select * 1e6, "build_split_us": t_build * 1e6},
+                     "select_us": t_select * 1e6, "build_split_us": t_build * 1e6,
+                     "factorize_on_device_ms": t_fact * 1e3},
     }
 
     # ------------------------------------------------------------ cpu baseline: the oracle as it stands

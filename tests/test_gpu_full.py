@@ -91,6 +91,31 @@ def test_c2_opt13b_shape_full_pipeline(ff):
     assert torch.isfinite(Y.float()).all()
 
 
+def test_c2_opt13b_shape_factorize_on_device(ff):
+    """The rank-512 factors of the C2 remainder computed by the library itself: products
+    against the oracle's, then build + forward on them (sampled rows)."""
+    cfg = C2
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    idx_h = L["planted"]
+    idx = torch.from_numpy(idx_h).cuda()
+    desc = desc_for(ff, cfg)
+    fd = ff.factorize_remainder(desc, Ld["W1"], None, Ld["W2"], idx, seed=2024)
+    torch.cuda.synchronize()
+    got = {k: host(v) for k, v in fd.items() if v is not None}
+    want = orc.factorize_remainder(L["W1"], L["W2"], None, idx_h, cfg.rank, seed=2024)
+    for p, q in (("P1", "Q1"), ("P2", "Q2")):
+        e = relf(got[p] @ got[q], want[p] @ want[q])
+        assert e < 6e-3, (p, e)                      # two bf16-rounded factors
+    split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, fd)
+    X = wl.make_tokens(cfg, cfg.prefill_T)
+    Y = ff.forward(desc, split, dev(X, "bf16"))
+    torch.cuda.synchronize()
+    rows = sampled_rows(cfg.prefill_T, 32)
+    ref = orc.forward_split(X[rows], L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", got)
+    assert relf(host(Y[torch.from_numpy(rows).cuda()]), ref[0]) < TOL["bf16"]
+
+
 def test_c3_llama7b_shape_prefill_and_decode(ff):
     cfg = C3
     L = wl.make_layer(cfg)
