@@ -80,6 +80,22 @@ def test_argument_errors_are_found_on_the_host():
     assert L.ffsplit_score_neurons(ref(good), fake, 4, fake, None, fake, fake, ref(tt), None, 0, fake, 16, None) == -5
     # missing factors for a low-rank build
     assert L.ffsplit_build_split(ref(good), fake, None, fake, fake, None, fake, fake, 1 << 30, None) == -1
+    # device factorisation: wrong remainder kind, missing outputs, misaligned output, small workspace
+    vp6 = ctypes.c_void_p * 6
+    outs = vp6(fake, fake, None, None, fake, fake)
+    dense = ff.make_desc(64, 256, "gelu", "bf16", 16, "dense")
+    assert L.ffsplit_factorize_remainder(ref(dense), fake, None, fake, fake, 1, outs, fake, 1 << 30, None) == -2
+    assert L.ffsplit_factorize_remainder(ref(good), fake, None, fake, fake, 1, None, fake, 1 << 30, None) == -1
+    assert L.ffsplit_factorize_remainder(ref(good), fake, None, fake, fake, 1, vp6(fake, None, None, None, fake, fake),
+                                         fake, 1 << 30, None) == -1
+    assert L.ffsplit_factorize_remainder(ref(good), fake, None, fake, fake, 1, vp6(fake, odd, None, None, fake, fake),
+                                         fake, 1 << 30, None) == -4
+    assert L.ffsplit_factorize_remainder(ref(good), fake, None, fake, fake, 1, outs, fake, 64, None) == -5
+    assert ff.workspace_bytes(good, ff.WS_FACTORIZE, 0) > 0 and ff.workspace_bytes(dense, ff.WS_FACTORIZE, 0) == 0
+    w3 = ff.make_desc(256, 1024, "swiglu", "bf16", 16, "w3h8", 0, 128)
+    assert ff.split_bytes(w3) > 0 and ff.workspace_bytes(w3, ff.WS_FORWARD, 8) > 0
+    assert L.ffsplit_forward(ref(ff.make_desc(256, 1024, "swiglu", "f32", 16, "w3h8", 0, 128)), fake, fake, 4, fake, None,
+                             None, fake, 1 << 30, None) == -6
     # T = 0 is a valid no-op that launches nothing
     assert L.ffsplit_forward(ref(good), fake, fake, 0, fake, None, None, None, 0, None) == 0
     assert tt.value == 0
