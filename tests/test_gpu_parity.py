@@ -397,3 +397,49 @@ def test_factorize_remainder_matches_oracle(ff, name, cfg, tol):
     torch.cuda.synchronize()
     ref = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "lowrank", got)
     assert relf(host(Y), ref[0]) < TOL[cfg.dtype]
+
+
+# ---------------------------------------------------------------- seeded sweep over odd shapes
+
+def _sweep_cases():
+    rng = np.random.default_rng(2401)
+    cases = []
+    for i in range(24):
+        kind = ("lowrank", "dense", "none", "int4", "w3h8")[i % 5]
+        act = "swiglu" if rng.random() < 0.5 else "gelu"
+        quant = kind in ("int4", "w3h8")
+        d = int(rng.choice([128, 256, 384])) if quant else int(rng.choice([64, 72, 136, 200, 256]))
+        d_ff = int(rng.integers(40, 900))
+        k = int(rng.choice([0, 1, rng.integers(1, max(2, d_ff // 4)), d_ff if i % 11 == 0 else 5]))
+        k = min(k, d_ff)
+        m = d_ff - k
+        r = int(rng.integers(1, max(2, min(d, m)))) if (kind == "lowrank" and m > 0) else 0
+        T = int(rng.choice([1, 2, 17, 32, 33, 64, 129, 200, 260, 1100]))
+        cases.append((f"{i}_{kind}_{act}_d{d}_f{d_ff}_k{k}_r{r}_T{T}", kind, act, d, d_ff, k, r, T))
+    return cases
+
+
+@pytest.mark.parametrize("name,kind,act,d,d_ff,k,r,T", _sweep_cases(), ids=[c[0] for c in _sweep_cases()])
+def test_forward_sweep(ff, name, kind, act, d, d_ff, k, r, T):
+    base = C3 if act == "swiglu" else C2
+    cfg = base.__class__(**{**base.__dict__, "name": name, "d_model": d, "d_ff": d_ff, "k": k, "rank": max(r, 1),
+                            "rem_kind": kind, "group": 128, "dtype": "bf16"})
+    L = wl.make_layer(cfg)
+    idx = np.asarray(L["planted"][::-1], np.int32).copy()
+    assert len(idx) == k
+    Ld = layer_to_dev(L, "bf16")
+    desc = desc_for(ff, cfg, kind, k=k, rank=r)
+    fac = None
+    if kind == "lowrank" and d_ff - k > 0:
+        fac = wl.make_factors(cfg, L, idx, rank=r)
+    fd = None if fac is None else {kk: dev(v, "bf16") for kk, v in fac.items()}
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda(), fd)
+    X = wl.make_tokens(cfg, T)
+    Y, Yh, Yr = ff.forward(desc, split, dev(X, "bf16"), want_parts=True)
+    torch.cuda.synchronize()
+    want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, act, kind, fac, group=128)
+    for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
+        if np.linalg.norm(w) == 0:
+            assert not host(g).any(), nm
+        else:
+            assert relf(host(g), w) < TOL["bf16"], (nm, relf(host(g), w))
