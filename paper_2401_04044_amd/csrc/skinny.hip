@@ -369,48 +369,18 @@ __device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi) {
   return v.u;
 }
 
-__global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceArgs p) {
-  const int id = blockIdx.x * 256 + threadIdx.x;
-  if (id >= p.n_rb * 256) return;
-  const int rb = id >> 8, g = (id >> 6) & 3, lane = id & 63;
+// Activation and store of four consecutive output columns (registers 4 g .. 4 g + 3 of row
+// block rb, token row lane & 31): v the block's sums, u the up block's sums for a (gate, up) pair.
+__device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int g, int lane, float v[4], const float u[4]) {
   const int cb = rb * 32;
   const bool act_here = cb < p.act_cols;
   const bool glu = p.act == ACT_GLU;
-  int oc;
-  if (glu) {
-    if (act_here) {
-      if (rb & 1) return;   // the pair is written from its gate block
-      oc = cb / 2;
-    } else {
-      oc = cb - p.act_cols / 2;
-    }
-  } else {
-    oc = cb;
-  }
-  auto sum_block = [&](int b) {
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4* src = (const float4*)p.part + ((int64_t)b * 4 + g) * 64 + lane;
-    // eight independent loads at a time, added in range order
-    const int64_t step = (int64_t)p.n_rb * 256;
-    const int ns = b < p.rb_split ? p.n_split : p.n_split_b;
-    for (int sp = 0; sp < ns; sp += 8) {
-      float4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(sp + u, ns - 1) * step];
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (sp + u < ns) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
-    }
-    return s;
-  };
-  const float4 z0 = sum_block(rb);
-  float v[4] = {z0.x, z0.y, z0.z, z0.w};
+  int oc = cb;
+  if (glu) oc = act_here ? cb / 2 : cb - p.act_cols / 2;
   if (act_here) {
     if (glu) {
-      const float4 u = sum_block(rb + 1);
-      const float uu[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = sk_silu(v[e]) * uu[e];
+      for (int e = 0; e < 4; ++e) v[e] = sk_silu(v[e]) * u[e];
     } else if (p.act == ACT_GELU) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
@@ -434,6 +404,147 @@ __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceAr
   }
 }
 
+__global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceArgs p) {
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  if (id >= p.n_rb * 256) return;
+  const int rb = id >> 8, g = (id >> 6) & 3, lane = id & 63;
+  const bool pair = p.act == ACT_GLU && rb * 32 < p.act_cols;
+  if (pair && (rb & 1)) return;   // the pair is written from its gate block
+  auto sum_block = [&](int b) {
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4* src = (const float4*)p.part + ((int64_t)b * 4 + g) * 64 + lane;
+    // eight independent loads at a time, added in range order
+    const int64_t step = (int64_t)p.n_rb * 256;
+    const int ns = b < p.rb_split ? p.n_split : p.n_split_b;
+    for (int sp = 0; sp < ns; sp += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(sp + u, ns - 1) * step];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (sp + u < ns) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+    return s;
+  };
+  const float4 z0 = sum_block(rb);
+  float v[4] = {z0.x, z0.y, z0.z, z0.w};
+  float uu[4] = {0.f, 0.f, 0.f, 0.f};
+  if (pair) {
+    const float4 u = sum_block(rb + 1);
+    uu[0] = u.x; uu[1] = u.y; uu[2] = u.z; uu[3] = u.w;
+  }
+  sk_emit(p, rb, g, lane, v, uu);
+}
+
+// The whole product in one launch, where it has enough 32-row blocks to fill the machine
+// without cutting the reduction across workgroups: a workgroup of NW wavefronts owns RB
+// adjacent row blocks (RB = 2: a (gate, up) pair, or two blocks that share the activation
+// blocks) over the whole reduction, the wavefronts take an NW-th each with the same two-deep
+// register prefetch as skinny_stream_kernel, add their accumulators through LDS in a fixed
+// order, and wavefront g < 4 applies the activation to accumulator registers 4 g .. and stores.
+// DUAL: the odd block of the pair reads the second left operand.
+struct SkinnyFusedArgs {
+  SkinnyArgs s;
+  SkinnyReduceArgs e;
+};
+
+template <bool A_TILED, int RB, int NW, bool DUAL>
+__global__ void __launch_bounds__(NW * 64) skinny_fused_kernel(const SkinnyFusedArgs q) {
+  constexpr int U = DUAL ? 4 : 8;   // blocks per register group (register budget)
+  constexpr int NA = DUAL ? 2 : 1;
+  extern __shared__ float red_mem[];
+  float (*red)[RB][16][64] = (float (*)[RB][16][64])red_mem;   // [NW][RB][16][64]
+  const SkinnyArgs& p = q.s;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int rb0 = blockIdx.x * RB;
+  const int kb_total = (p.K + 15) / 16;
+  const int per = (kb_total + NW - 1) / NW;
+  const int kb0 = wave * per;
+  const int kb1 = min(kb_total, kb0 + per);      // may be empty: the wavefront then adds zeros
+  const int kb_last = kb_total - 1;
+
+  const char* wbase[RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i) wbase[i] = (const char*)p.Bt + ((int64_t)(rb0 + i) * (p.ldb / 16) * 64 + lane) * 16;
+  const char* abase[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    abase[i] = (const char*)(i ? p.A1 : p.A);
+    if (A_TILED) abase[i] += (int64_t)lane * 16;
+    else abase[i] += ((int64_t)min(lane & 31, p.M - 1) * p.lda + (lane >> 5) * 8) * 2;
+  }
+  auto wload = [&](int i, int kb) { return *(const u32x4_t*)(wbase[i] + (int64_t)min(kb, kb_last) * 1024); };
+  auto aload = [&](int i, int kb) {
+    const int k = min(kb, kb_last);
+    if (A_TILED) return *(const u32x4_t*)(abase[i] + (int64_t)k * 1024);
+    const int col = k * 16 + (lane >> 5) * 8;     // a chunk past K reads the row's first chunk (weights are zero there)
+    return *(const u32x4_t*)(abase[i] + (col < p.K ? (int64_t)k * 32 : -(int64_t)((lane >> 5) * 16)));
+  };
+  f32x16_t acc[RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  u32x4_t w0[RB][U], a0[NA][U], w1[RB][U], a1[NA][U];
+  auto load = [&](u32x4_t (*w)[U], u32x4_t (*a)[U], int kb) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < RB; ++i) w[i][u] = wload(i, kb + u);
+#pragma unroll
+      for (int i = 0; i < NA; ++i) a[i][u] = aload(i, kb + u);
+    }
+  };
+  auto compute = [&](u32x4_t (*w)[U], u32x4_t (*a)[U], int kb) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        SFrag wf, af;
+        wf.u = w[i][u];
+        af.u = (kb + u < kb1) ? a[DUAL ? i : 0][u] : u32x4_t{0, 0, 0, 0};
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, af.v, acc[i], 0, 0, 0);
+      }
+  };
+  load(w0, a0, kb0);
+  for (int kb = kb0; kb < kb1; kb += 2 * U) {
+    // (the scheduling barriers keep each batch of loads ahead of the arithmetic of the batch before)
+    load(w1, a1, kb + U);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(w0, a0, kb);
+    __builtin_amdgcn_sched_barrier(0);
+    load(w0, a0, kb + 2 * U);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(w1, a1, kb + U);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][i][v][lane] = acc[i][v];
+  __syncthreads();
+  if (wave >= 4) return;
+  const int g = wave;
+  float sum[RB][4];
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float t = red[0][i][4 * g + e][lane];
+      for (int w = 1; w < NW; ++w) t += red[w][i][4 * g + e][lane];
+      sum[i][e] = t;
+    }
+  const bool pair = q.e.act == ACT_GLU && rb0 * 32 < q.e.act_cols;
+  if (RB == 2 && pair) {
+    sk_emit(q.e, rb0, g, lane, sum[0], sum[RB - 1]);
+  } else {
+    const float none[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < RB; ++i) sk_emit(q.e, rb0 + i, g, lane, sum[i], none);
+  }
+}
+
 }  // namespace
 
 size_t skinny_part_bytes(int n_max) {
@@ -443,6 +554,46 @@ size_t skinny_part_bytes(int n_max) {
 
 // g as for the large-batch launcher (M <= 32; destinations tiled with one row block, or
 // row-major); part: scratch of skinny_part_bytes(N) bytes.
+static void fill_reduce_args(SkinnyReduceArgs& r, const GemmArgs& g, int act) {
+  r.n_rb = g.N / 32; r.M = g.M; r.N = g.N;
+  r.act = act; r.act_cols = g.act_cols; r.split_col = g.split_col;
+  r.C0 = g.C0; r.C1 = g.C1; r.ldc0 = g.ldc0; r.ldc1 = g.ldc1;
+  r.c0_tiled = g.c0_tiled; r.c1_tiled = g.c1_tiled; r.n_store = g.n_store;
+}
+
+template <bool AT, int RB, int NW, bool DUAL>
+static int launch_fused_cfg(const SkinnyFusedArgs& q, hipStream_t st) {
+  hipLaunchKernelGGL((skinny_fused_kernel<AT, RB, NW, DUAL>), dim3(q.s.n_rb / RB), dim3(NW * 64), (size_t)NW * RB * 4096,
+                     st, q);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// 0 launched, -1 failed, 1 not applicable (too few row blocks for one workgroup per RB of them,
+// or a reduction too short to share among the wavefronts)
+static int launch_skinny_fused(const SkinnyArgs& a, const GemmArgs& g, int act, int kb_total, hipStream_t st) {
+  SkinnyFusedArgs q = {};
+  q.s = a;
+  fill_reduce_args(q.e, g, act);
+  const bool at = g.a_tiled != 0, dual = g.A1 != nullptr, glu = act == ACT_GLU;
+  const int n_rb = a.n_rb;
+  if (dual) {
+    if (!at || !glu || (n_rb & 1) || n_rb / 2 < 256 || kb_total < 4 * 4) return 1;
+    return launch_fused_cfg<true, 2, 4, true>(q, st);
+  }
+  if (!(n_rb & 1) && n_rb / 2 >= 256 && kb_total >= 4 * 8)
+    return at ? launch_fused_cfg<true, 2, 4, false>(q, st) : launch_fused_cfg<false, 2, 4, false>(q, st);
+  // Fewer than about a hundred workgroups cannot pull the weights fast enough (measured: 40-66
+  // workgroups of 8-16 wavefronts took 1.4-2x the time of the split version with its reduce).
+  if (glu) {   // (gate, up) pairs stay in one workgroup
+    if (!(n_rb & 1) && n_rb / 2 >= 96 && kb_total >= 8 * 8)
+      return at ? launch_fused_cfg<true, 2, 8, false>(q, st) : launch_fused_cfg<false, 2, 8, false>(q, st);
+    return 1;
+  }
+  if (n_rb >= 96 && kb_total >= 8 * 8)
+    return at ? launch_fused_cfg<true, 1, 8, false>(q, st) : launch_fused_cfg<false, 1, 8, false>(q, st);
+  return 1;
+}
+
 int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return 0;
   if (g.M > 32 || (g.N & 31) || g.partial) return -1;
@@ -451,6 +602,10 @@ int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) 
   a.M = g.M; a.N = g.N; a.K = g.K; a.a_tiled = g.a_tiled;
   a.n_rb = g.N / 32;
   const int kb_total = (g.K + 15) / 16;
+  {
+    const int fused = launch_skinny_fused(a, g, act, kb_total, st);
+    if (fused <= 0) return fused;   // launched (0) or failed (-1); 1 = not applicable
+  }
   // enough ranges for about 2048 wavefronts, at least 32 blocks (32 KiB of weights) each
   int S = 2048 / a.n_rb;
   const int max_s = kb_total / 32 > 0 ? kb_total / 32 : 1;
