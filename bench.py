@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-decode", action="store_true", help="skip the decode sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-yardsticks", action="store_true",
+                    help="skip the machine yardsticks (device copy, vendor-library GEMMs through torch)")
     ap.add_argument("--copies", type=int, default=4, help="split copies rotated through in the prefill loop")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for scaling rocprofv3's "
@@ -320,6 +322,43 @@ def main():
                                                   "layer (k=819, rank 1280): heavy bf16 + low-rank factors, seeded "
                                                   "Gaussian factors", **dl}
 
+    # ------------------------------------------------------------ yardsticks of this machine (not the product path)
+    # What the same box gives to a plain device copy and to the vendor BLAS behind torch.matmul:
+    # auditable denominators next to the datasheet peaks the fractions above are quoted against.
+    if not args.no_yardsticks:
+        torch.cuda.empty_cache()
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        tc, _ = timed(lambda: dst.copy_(src), 10, 3)
+        del src, dst
+        a8 = torch.randn(8192, 8192, dtype=bf, device="cuda")
+        b8 = torch.randn(8192, 8192, dtype=bf, device="cuda")
+        tg, _ = timed(lambda: torch.matmul(a8, b8), 10, 3)
+        del a8, b8
+        # the four products of the C2 chain as plain library GEMMs plus a separate GeLU pass
+        c2 = C2
+        Tq, dq, kq, rq = c2.prefill_T, c2.d_model, c2.k, c2.rank
+        mq = c2.d_ff - kq
+        xq = torch.randn(Tq, dq, dtype=bf, device="cuda")
+        w1q = torch.randn(dq, kq + rq, dtype=bf, device="cuda")
+        q1q = torch.randn(rq, mq, dtype=bf, device="cuda")
+        p2q = torch.randn(mq, rq, dtype=bf, device="cuda")
+        w4q = torch.randn(kq + rq, dq, dtype=bf, device="cuda")
+
+        def lib_chain():
+            z = torch.matmul(xq, w1q)
+            h = torch.nn.functional.gelu(torch.matmul(z[:, kq:], q1q))
+            t2 = torch.matmul(h, p2q)
+            return torch.matmul(torch.cat([torch.nn.functional.gelu(z[:, :kq]), t2], dim=1), w4q)
+
+        tl, _ = timed(lib_chain, 20, 5)
+        out["yardsticks"] = {"device_copy_1GiB_GBps_read_plus_write": 2.0 * (1 << 30) / tc / 1e9,
+                             "torch_matmul_bf16_8192_TFLOPs": 2.0 * 8192 ** 3 / tg / 1e12,
+                             "c2_chain_as_torch_ops_us": tl * 1e6,
+                             "note": "vendor library / torch kernels, measurement only; not used by the product path"}
+        note(f"yardsticks: copy {out['yardsticks']['device_copy_1GiB_GBps_read_plus_write']:.0f} GB/s, "
+             f"matmul 8192^3 {out['yardsticks']['torch_matmul_bf16_8192_TFLOPs']:.0f} TFLOP/s, "
+             f"C2 chain as torch ops {tl*1e6:.0f} us")
     print(json.dumps(out))
 
 
