@@ -116,6 +116,39 @@ def test_c2_opt13b_shape_factorize_on_device(ff):
     assert relf(host(Y[torch.from_numpy(rows).cuda()]), ref[0]) < TOL["bf16"]
 
 
+def test_c2_opt13b_shape_65536_tokens(ff):
+    """A batch sixteen times the benchmark's (more than 2^31 elements in h2's address range in
+    bytes): index arithmetic at scale, checked on sampled rows against the oracle and on the
+    first and last block of 4096 rows against a 4096-token call (rows are independent)."""
+    cfg = C2
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    idx_h = L["planted"]
+    fac = wl.make_factors(cfg, L, idx_h)
+    desc = desc_for(ff, cfg)
+    split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], torch.from_numpy(idx_h).cuda(),
+                           {k: dev(v, "bf16") for k, v in fac.items()})
+    T = 65536
+    rows = sampled_rows(T, 16, seed=3)
+    Xs = wl.make_tokens(cfg, 4096)
+    Xd = dev(Xs, "bf16").repeat(T // 4096, 1)
+    # make the sampled rows distinct from the repeats
+    Xr = wl.make_tokens(cfg, len(rows), wl.gen.S_EVAL, layer=7)
+    Xd[torch.from_numpy(rows).cuda()] = dev(Xr, "bf16")
+    Y = ff.forward(desc, split, Xd)
+    Y4 = ff.forward(desc, split, Xd[:4096].contiguous())
+    torch.cuda.synchronize()
+    ref = orc.forward_split(Xr, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
+    assert relf(host(Y[torch.from_numpy(rows).cuda()]), ref) < TOL["bf16"]
+    keep = np.setdiff1d(np.arange(4096), rows)
+    # (tile shapes and the split of the long reduction depend on T, so the sums are ordered
+    # differently: equal up to the rounding of the bf16 intermediates, not bit for bit)
+    assert relf(host(Y[:4096][torch.from_numpy(keep).cuda()]), host(Y4[torch.from_numpy(keep).cuda()])) < 3e-3
+    blk = Y[4096 * 15:4096 * 16]
+    keep15 = np.setdiff1d(keep, rows[rows >= 4096 * 15] - 4096 * 15)
+    assert relf(host(blk[torch.from_numpy(keep15).cuda()]), host(Y4[torch.from_numpy(keep15).cuda()])) < 3e-3
+
+
 def test_c3_llama7b_shape_prefill_and_decode(ff):
     cfg = C3
     L = wl.make_layer(cfg)
