@@ -62,8 +62,8 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
   // Column offset inside a K-contiguous buffer: elements (row-major) or whole 16-wide
   // k blocks of 1 KiB (tiled).
   auto koff_bytes = [&](int koff) -> size_t { return L.tiled ? (size_t)(koff / 16) * 1024 : (size_t)koff * esz; };
-  // batches of at most 32 rows are bound by streaming the weights: dedicated kernels
-  const bool small_m = bf16 && M <= 32;
+  // small batches are bound by streaming the weights: dedicated kernels
+  const bool small_m = bf16 && M <= SKINNY_MAX_M;
   auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
     if (g.group_m <= 0) g.group_m = 8;
     g.m_pad = w.t_pad;

@@ -100,9 +100,11 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
 int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
                          hipStream_t st);
 int bf16_score_tile_m();
-// small-batch path (M <= 32, N a multiple of 32): weight-streaming kernel + fixed-order reduce;
-// part: scratch of skinny_part_bytes(N) bytes
-size_t skinny_part_bytes(int n_max);
+// small-batch path (M <= SKINNY_MAX_M, N a multiple of 32): weight-streaming kernels, one or two
+// blocks of 32 tokens per pass over the weights (four blocks were measured no better than the
+// tiled GEMM at 128 rows); part: scratch of skinny_part_bytes(N, M) bytes
+constexpr int SKINNY_MAX_M = 64;
+size_t skinny_part_bytes(int n_max, int M);
 int launch_skinny_bf16(const GemmArgs& a, int act, float* part, hipStream_t st);
 // the reduce half alone: sum of n_split ranges of partial tiles, activation, stores
 // (f16_out: the destinations hold fp16, saturating, instead of bf16)

@@ -951,18 +951,18 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     if (sp < 1) sp = 1;
     w.g3_split = sp;
     size_t scratch = sp > 1 ? (size_t)sp * T * L.rp * 4 : 0;
-    if (T <= 32) {
+    if (T <= SKINNY_MAX_M) {
       // small batches take the weight-streaming kernels: room for their partial tiles
       int n_max = L.n1 > L.n_up * L.mp ? L.n1 : L.n_up * L.mp;
       if (L.dn > n_max) n_max = L.dn;
       if (L.rp > n_max) n_max = L.rp;
-      const size_t sk = skinny_part_bytes(n_max);
+      const size_t sk = skinny_part_bytes(n_max, (int)T);
       if (sk > scratch) scratch = sk;
     }
     if (scratch > 0) off = align256(off + scratch);
-  } else if (L.tiled && T > 0 && T <= 32) {
+  } else if (L.tiled && T > 0 && T <= SKINNY_MAX_M) {
     int n_max = L.n1 > L.dn ? L.n1 : L.dn;
-    off = align256(off + skinny_part_bytes(n_max));
+    off = align256(off + skinny_part_bytes(n_max, (int)T));
   }
   w.total_bytes = off > 0 ? off : 256;
   return w;

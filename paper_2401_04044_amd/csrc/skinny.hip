@@ -41,11 +41,13 @@ struct SkinnyArgs {
   int n_rb;           // 32-row blocks of the weights
   int n_split;        // ranges of the reduction
   int kb_per;         // 16-element k blocks per range
-  float* part;        // [n_split][n_rb][4][64] float4: accumulator order
+  int n_tb;           // 32-token blocks of the activations (at most NT of the kernel)
+  float* part;        // [n_split][n_rb][NT][4][64] float4: accumulator order
 };
 
-template <bool A_TILED>
+template <bool A_TILED, int NT>
 __global__ void __launch_bounds__(256) skinny_stream_kernel(const SkinnyArgs p) {
+  constexpr int U = SK_U;   // blocks per register group
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (task >= p.n_rb * p.n_split) return;
@@ -56,57 +58,80 @@ __global__ void __launch_bounds__(256) skinny_stream_kernel(const SkinnyArgs p) 
   const int kb_last = kb1 - 1;
 
   const char* wbase = (const char*)p.Bt + ((int64_t)rb * (p.ldb / 16) * 64 + lane) * 16;
-  const char* abase = (const char*)((p.A1 != nullptr && (rb & 1)) ? p.A1 : p.A);
-  if (A_TILED) {
-    abase += (int64_t)lane * 16;
-  } else {
-    const int row = min(lane & 31, p.M - 1);
-    abase += ((int64_t)row * p.lda + (lane >> 5) * 8) * 2;
+  // one activation base per block of 32 tokens (a block past the batch repeats the last one;
+  // its results are never read)
+  const char* abase[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int tb = min(t, p.n_tb - 1);
+    abase[t] = (const char*)((p.A1 != nullptr && (rb & 1)) ? p.A1 : p.A);
+    if (A_TILED) {
+      abase[t] += ((int64_t)tb * (p.lda / 16) * 64 + lane) * 16;
+    } else {
+      const int row = min(tb * 32 + (lane & 31), p.M - 1);
+      abase[t] += ((int64_t)row * p.lda + (lane >> 5) * 8) * 2;
+    }
   }
   // block kb of the weights / of the activations; past the range: the last block again (its
   // product is masked out below), so that the loads stay unconditional
   auto wload = [&](int kb) { return *(const u32x4_t*)(wbase + (int64_t)min(kb, kb_last) * 1024); };
-  auto aload = [&](int kb) {
+  auto aload = [&](int t, int kb) {
     const int k = min(kb, kb_last);
-    if (A_TILED) return *(const u32x4_t*)(abase + (int64_t)k * 1024);
+    if (A_TILED) return *(const u32x4_t*)(abase[t] + (int64_t)k * 1024);
     // row-major: a chunk past K (K is a multiple of 8) reads the row's first chunk instead;
     // the weights are zero there
     const int col = k * 16 + (lane >> 5) * 8;
-    return *(const u32x4_t*)(abase + (col < p.K ? (int64_t)k * 32 : -(int64_t)((lane >> 5) * 16)));
+    return *(const u32x4_t*)(abase[t] + (col < p.K ? (int64_t)k * 32 : -(int64_t)((lane >> 5) * 16)));
   };
 
-  f32x16_t acc;
+  f32x16_t acc[NT];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-  u32x4_t w0[SK_U], a0[SK_U], w1[SK_U], a1[SK_U];
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  u32x4_t w0[U], a0[NT][U], w1[U], a1[NT][U];
+  auto load = [&](u32x4_t* w, u32x4_t (*a)[U], int kb) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      w[u] = wload(kb + u);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) a[t][u] = aload(t, kb + u);
+    }
+  };
+  auto compute = [&](const u32x4_t* w, u32x4_t (*a)[U], int kb) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      SFrag wf;
+      wf.u = w[u];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        SFrag af;
+        af.u = (kb + u < kb1) ? a[t][u] : u32x4_t{0, 0, 0, 0};
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, af.v, acc[t], 0, 0, 0);
+      }
+    }
+  };
   if (kb0 < kb1) {
-#pragma unroll
-    for (int u = 0; u < SK_U; ++u) { w0[u] = wload(kb0 + u); a0[u] = aload(kb0 + u); }
-    for (int kb = kb0; kb < kb1; kb += 2 * SK_U) {
-#pragma unroll
-      for (int u = 0; u < SK_U; ++u) { w1[u] = wload(kb + SK_U + u); a1[u] = aload(kb + SK_U + u); }
-#pragma unroll
-      for (int u = 0; u < SK_U; ++u) {
-        SFrag w, a;
-        w.u = w0[u];
-        a.u = (kb + u < kb1) ? a0[u] : u32x4_t{0, 0, 0, 0};
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.v, a.v, acc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int u = 0; u < SK_U; ++u) { w0[u] = wload(kb + 2 * SK_U + u); a0[u] = aload(kb + 2 * SK_U + u); }
-#pragma unroll
-      for (int u = 0; u < SK_U; ++u) {
-        SFrag w, a;
-        w.u = w1[u];
-        a.u = (kb + SK_U + u < kb1) ? a1[u] : u32x4_t{0, 0, 0, 0};
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.v, a.v, acc, 0, 0, 0);
-      }
+    load(w0, a0, kb0);
+    for (int kb = kb0; kb < kb1; kb += 2 * U) {
+      load(w1, a1, kb + U);
+      if (NT > 1) __builtin_amdgcn_sched_barrier(0);   // keep the batch of loads ahead of the arithmetic
+      compute(w0, a0, kb);
+      if (NT > 1) __builtin_amdgcn_sched_barrier(0);
+      load(w0, a0, kb + 2 * U);
+      if (NT > 1) __builtin_amdgcn_sched_barrier(0);
+      compute(w1, a1, kb + U);
+      if (NT > 1) __builtin_amdgcn_sched_barrier(0);
     }
   }
   // lane: row (token) = lane & 31; columns 8 g + 4 (lane >> 5) + 0..3 of the block in acc[4 g ..]
-  float4* dst = (float4*)p.part + ((int64_t)(sp * p.n_rb + rb) * 4) * 64 + lane;
 #pragma unroll
-  for (int g = 0; g < 4; ++g) dst[g * 64] = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+  for (int t = 0; t < NT; ++t) {
+    float4* dst = (float4*)p.part + ((int64_t)((sp * p.n_rb + rb) * NT + t) * 4) * 64 + lane;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      dst[g * 64] = make_float4(acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]);
+  }
 }
 
 // The same product with the weights in the quantised tiled format (32 x 64 blocks of 8- or
@@ -361,6 +386,7 @@ struct SkinnyReduceArgs {
   int c0_tiled, c1_tiled, n_store;
   int f16_out;   // destinations hold fp16 (saturating) instead of bf16
   int rb_split, n_split_b;   // row blocks from rb_split on have n_split_b ranges
+  int n_tb, nt;              // 32-token blocks to write / token blocks per row block in part
 };
 
 __device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi) {
@@ -371,7 +397,8 @@ __device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi) {
 
 // Activation and store of four consecutive output columns (registers 4 g .. 4 g + 3 of row
 // block rb, token row lane & 31): v the block's sums, u the up block's sums for a (gate, up) pair.
-__device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int g, int lane, float v[4], const float u[4]) {
+__device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int tb, int g, int lane, float v[4],
+                                        const float u[4]) {
   const int cb = rb * 32;
   const bool act_here = cb < p.act_cols;
   const bool glu = p.act == ACT_GLU;
@@ -386,7 +413,7 @@ __device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int g
       for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
     }
   }
-  const int row = lane & 31;
+  const int row = tb * 32 + (lane & 31);
   const int col0 = oc + 8 * g + 4 * (lane >> 5);   // first of this thread's four output columns
   char* base;
   int64_t ld;
@@ -396,8 +423,8 @@ __device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int g
   const uint2 val = p.f16_out ? make_uint2(pack_f16x2_sat(v[0], v[1]), pack_f16x2_sat(v[2], v[3]))
                               : make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
   if (tiled) {
-    // (the destination has one 32-row block; rows past M hold repeats of row M - 1, finite)
-    const int64_t chunk = ((int64_t)(col / 16) * 64) + ((col >> 3) & 1) * 32 + row;
+    // (rows past M in the last 32-row block hold repeats of row M - 1, finite)
+    const int64_t chunk = ((int64_t)tb * (ld / 16) + col / 16) * 64 + ((col >> 3) & 1) * 32 + (lane & 31);
     *(uint2*)(base + chunk * 16 + (col & 7) * 2) = val;
   } else if (row < p.M && col < p.n_store) {
     *(uint2*)(base + ((int64_t)row * ld + col) * 2) = val;
@@ -406,15 +433,15 @@ __device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int g
 
 __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceArgs p) {
   const int id = blockIdx.x * 256 + threadIdx.x;
-  if (id >= p.n_rb * 256) return;
-  const int rb = id >> 8, g = (id >> 6) & 3, lane = id & 63;
+  if (id >= p.n_rb * p.n_tb * 256) return;
+  const int rb = (id >> 8) / p.n_tb, tb = (id >> 8) % p.n_tb, g = (id >> 6) & 3, lane = id & 63;
   const bool pair = p.act == ACT_GLU && rb * 32 < p.act_cols;
   if (pair && (rb & 1)) return;   // the pair is written from its gate block
   auto sum_block = [&](int b) {
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4* src = (const float4*)p.part + ((int64_t)b * 4 + g) * 64 + lane;
+    const float4* src = (const float4*)p.part + (((int64_t)b * p.nt + tb) * 4 + g) * 64 + lane;
     // eight independent loads at a time, added in range order
-    const int64_t step = (int64_t)p.n_rb * 256;
+    const int64_t step = (int64_t)p.n_rb * p.nt * 256;
     const int ns = b < p.rb_split ? p.n_split : p.n_split_b;
     for (int sp = 0; sp < ns; sp += 8) {
       float4 v[8];
@@ -433,7 +460,7 @@ __global__ void __launch_bounds__(256) skinny_reduce_kernel(const SkinnyReduceAr
     const float4 u = sum_block(rb + 1);
     uu[0] = u.x; uu[1] = u.y; uu[2] = u.z; uu[3] = u.w;
   }
-  sk_emit(p, rb, g, lane, v, uu);
+  sk_emit(p, rb, tb, g, lane, v, uu);
 }
 
 // The whole product in one launch, where it has enough 32-row blocks to fill the machine
@@ -537,19 +564,21 @@ __global__ void __launch_bounds__(NW * 64) skinny_fused_kernel(const SkinnyFused
     }
   const bool pair = q.e.act == ACT_GLU && rb0 * 32 < q.e.act_cols;
   if (RB == 2 && pair) {
-    sk_emit(q.e, rb0, g, lane, sum[0], sum[RB - 1]);
+    sk_emit(q.e, rb0, 0, g, lane, sum[0], sum[RB - 1]);
   } else {
     const float none[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < RB; ++i) sk_emit(q.e, rb0 + i, g, lane, sum[i], none);
+    for (int i = 0; i < RB; ++i) sk_emit(q.e, rb0 + i, 0, g, lane, sum[i], none);
   }
 }
 
 }  // namespace
 
-size_t skinny_part_bytes(int n_max) {
-  // at most ~2048 wavefront tasks: n_rb * n_split <= 2048 + n_rb, one 4 KiB tile each
-  return (size_t)(2048 + (n_max + 31) / 32) * 4096;
+int skinny_token_blocks(int M) { return M <= 32 ? 1 : 2; }
+
+size_t skinny_part_bytes(int n_max, int M) {
+  // at most ~2048 wavefront tasks: n_rb * n_split <= 2048 + n_rb, one 4 KiB tile each per block of 32 tokens
+  return (size_t)(2048 + (n_max + 31) / 32) * 4096 * skinny_token_blocks(M);
 }
 
 // g as for the large-batch launcher (M <= 32; destinations tiled with one row block, or
@@ -574,6 +603,7 @@ static int launch_skinny_fused(const SkinnyArgs& a, const GemmArgs& g, int act, 
   SkinnyFusedArgs q = {};
   q.s = a;
   fill_reduce_args(q.e, g, act);
+  q.e.n_tb = 1; q.e.nt = 1;
   const bool at = g.a_tiled != 0, dual = g.A1 != nullptr, glu = act == ACT_GLU;
   const int n_rb = a.n_rb;
   if (dual) {
@@ -596,13 +626,15 @@ static int launch_skinny_fused(const SkinnyArgs& a, const GemmArgs& g, int act, 
 
 int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return 0;
-  if (g.M > 32 || (g.N & 31) || g.partial) return -1;
+  if (g.M > SKINNY_MAX_M || (g.N & 31) || g.partial) return -1;
+  const int nt = skinny_token_blocks(g.M);
   SkinnyArgs a = {};
+  a.n_tb = (g.M + 31) / 32;
   a.A = g.A; a.A1 = g.A1; a.Bt = g.Bt; a.lda = g.lda; a.ldb = g.ldb;
   a.M = g.M; a.N = g.N; a.K = g.K; a.a_tiled = g.a_tiled;
   a.n_rb = g.N / 32;
   const int kb_total = (g.K + 15) / 16;
-  {
+  if (nt == 1) {
     const int fused = launch_skinny_fused(a, g, act, kb_total, st);
     if (fused <= 0) return fused;   // launched (0) or failed (-1); 1 = not applicable
   }
@@ -615,10 +647,21 @@ int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) 
   a.n_split = (kb_total + a.kb_per - 1) / a.kb_per;
   a.part = part;
   const int tasks = a.n_rb * a.n_split;
-  if (g.a_tiled) hipLaunchKernelGGL(skinny_stream_kernel<true>, dim3((tasks + 3) / 4), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(skinny_stream_kernel<false>, dim3((tasks + 3) / 4), dim3(256), 0, st, a);
+  const dim3 grid((tasks + 3) / 4), blk(256);
+  if (g.a_tiled) {
+    if (nt == 1) hipLaunchKernelGGL((skinny_stream_kernel<true, 1>), grid, blk, 0, st, a);
+    else hipLaunchKernelGGL((skinny_stream_kernel<true, 2>), grid, blk, 0, st, a);
+  } else {
+    if (nt == 1) hipLaunchKernelGGL((skinny_stream_kernel<false, 1>), grid, blk, 0, st, a);
+    else hipLaunchKernelGGL((skinny_stream_kernel<false, 2>), grid, blk, 0, st, a);
+  }
   if (hipGetLastError() != hipSuccess) return -1;
-  return launch_skinny_reduce(g, act, part, a.n_split, 0, st);
+  SkinnyReduceArgs r = {};
+  fill_reduce_args(r, g, act);
+  r.part = part; r.n_split = a.n_split; r.rb_split = r.n_rb; r.n_split_b = a.n_split;
+  r.n_tb = a.n_tb; r.nt = nt;
+  hipLaunchKernelGGL(skinny_reduce_kernel, dim3(r.n_rb * r.n_tb), dim3(256), 0, st, r);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_skinny_reduce(const GemmArgs& g, int act, const float* part, int n_split, int f16_out, hipStream_t st) {
@@ -628,7 +671,7 @@ int launch_skinny_reduce(const GemmArgs& g, int act, const float* part, int n_sp
 int launch_skinny_reduce2(const GemmArgs& g, int act, const float* part, int n_split, int rb_split, int n_split_b,
                           int f16_out, hipStream_t st) {
   SkinnyReduceArgs r = {};
-  r.f16_out = f16_out; r.rb_split = rb_split; r.n_split_b = n_split_b;
+  r.f16_out = f16_out; r.rb_split = rb_split; r.n_split_b = n_split_b; r.n_tb = 1; r.nt = 1;
   r.part = part; r.n_rb = g.N / 32; r.n_split = n_split; r.M = g.M; r.N = g.N;
   r.act = act; r.act_cols = g.act_cols; r.split_col = g.split_col;
   r.C0 = g.C0; r.C1 = g.C1; r.ldc0 = g.ldc0; r.ldc1 = g.ldc1;

@@ -131,6 +131,12 @@ FWD_CASES = [
     ("small_batch_swiglu_8", reduced(C3, 192, 700, rank=64), 8),
     ("small_batch_swiglu_31", reduced(C3, 328, 1500, rank=40), 31),
     ("small_batch_long_k", reduced(C5, 128, 9000, rank=48), 3),
+    # 33..64 rows: the same kernels with two blocks of 32 tokens per pass over the weights (and beyond)
+    ("mid_batch_gelu_64", reduced(C2, 320, 1111, rank=72), 64),
+    ("mid_batch_gelu_70", reduced(C5, 256, 1000, rank=64), 70),
+    ("mid_batch_swiglu_50", reduced(C3, 192, 700, rank=64), 50),
+    ("mid_batch_swiglu_64", reduced(C3, 328, 1500, rank=40), 64),
+    ("mid_batch_swiglu_65", reduced(C3, 328, 1500, rank=40), 65),
     # more than 1024 rows: 256-row tiles, split-K of the long reduction, dual-operand SwiGLU
     ("c2_reduced_tall", reduced(C2, 256, 2100, rank=128), 1300),
     ("c3_reduced_tall", reduced(C3, 192, 1500, rank=64), 1059),
