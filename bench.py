@@ -28,7 +28,7 @@ MFMA_BF16_PEAK = 2.5e15   # FLOP/s, dense bf16, MI355X datasheet
 HBM_PEAK = 8.0e12         # B/s
 # HBM bytes of one C2 forward (read + written), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/gemm_bf16_chain_C2_prefill.md (scaled by the reference copy there)
-TRAFFIC_C2_PREFILL = 379.1e6   # 269.6 MB read + 109.6 MB written
+TRAFFIC_C2_PREFILL = 379.5e6   # 269.9 MB read + 109.6 MB written
 
 
 def parse():
