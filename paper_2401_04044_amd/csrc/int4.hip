@@ -325,14 +325,8 @@ __device__ __forceinline__ VFrag dequant8v(uint32_t w) {
 }
 
 // partial sums cross workgroups of one launch: device-scope accesses go to the point where
-// the per-XCD L2 caches are coherent, so no cache write-back or invalidate is needed
-__device__ __forceinline__ void st_dev(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_dev(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// two adjacent floats (8-byte aligned) in one device-scope access
+// the per-XCD L2 caches are coherent, so no cache write-back or invalidate is needed;
+// two adjacent floats (8-byte aligned) per access
 __device__ __forceinline__ void st_dev2(float* p, float a, float b) {
   const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
   __hip_atomic_store((unsigned long long*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

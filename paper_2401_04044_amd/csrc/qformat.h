@@ -98,15 +98,4 @@ __device__ __forceinline__ uint32_t q_pair(const QPacked<8>& p, int j, int i, ui
   return __builtin_amdgcn_perm(magic_bytes, w, (i & 1) ? 0x04030402u : 0x04010400u);
 }
 
-// eight dequantised weights of operand block j (static) as one MFMA operand register set:
-// bf16(s[e] * q), s per element
-template <int BITS>
-__device__ __forceinline__ q_u32x4 q_operand(const QPacked<BITS>& p, int j, const float s[8]) {
-  q_u32x4 o;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    o[i] = pack_bf16x2((float)q_get(p, 8 * j + 2 * i) * s[2 * i], (float)q_get(p, 8 * j + 2 * i + 1) * s[2 * i + 1]);
-  return o;
-}
-
 }  // namespace ffsplit
