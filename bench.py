@@ -58,7 +58,7 @@ def main():
     import paper_2401_04044_amd as ff
     import workloads as wl
     import dataclasses
-    from workloads.configs import C2, C3, C4, C5
+    from workloads.configs import C1, C2, C3, C4, C5
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
@@ -321,6 +321,25 @@ def main():
         out["decode_lowrank_bf16"] = {"workload": "C3 Llama-2-7B-shaped (k=550, rank 1024) and one C5 OPT-13B-shaped "
                                                   "layer (k=819, rank 1280): heavy bf16 + low-rank factors, seeded "
                                                   "Gaussian factors", **dl}
+
+    # ------------------------------------------------------------ extra: C1, the fp32 correctness config
+    if not args.no_decode:
+        torch.cuda.empty_cache()
+        c1 = C1
+        L1 = wl.make_layer(c1)
+        f1 = wl.make_factors(c1, L1, L1["planted"])
+        f32 = torch.float32
+        d1 = ff.make_desc(c1.d_model, c1.d_ff, c1.act, c1.dtype, c1.k, "lowrank", c1.rank)
+        s1 = ff.build_split(d1, dev(L1["W1"], f32), None, dev(L1["W2"], f32), torch.from_numpy(L1["planted"]).cuda(),
+                            {k: dev(v, f32) for k, v in f1.items()})
+        x1 = dev(wl.make_tokens(c1, c1.prefill_T), f32)
+        y1 = torch.empty((c1.prefill_T, c1.d_model), dtype=f32, device="cuda")
+        w1s = torch.empty(ff.workspace_bytes(d1, ff.WS_FORWARD, c1.prefill_T), dtype=torch.uint8, device="cuda")
+        t1, _ = timed(lambda: ff.forward(d1, s1, x1, y1, False, w1s), 100, 20)
+        note(f"C1 fp32 forward T={c1.prefill_T}: {t1*1e6:.1f} us")
+        out["c1_fp32"] = {"workload": "C1 BERT-base-shaped layer, fp32, T=128 (correctness config; launch-latency bound)",
+                          "us": t1 * 1e6, "tokens_per_s": c1.prefill_T / t1,
+                          "GFLOPs": c1.flops_per_token() * c1.prefill_T / t1 / 1e9}
 
     # ------------------------------------------------------------ yardsticks of this machine (not the product path)
     # What the same box gives to a plain device copy and to the vendor BLAS behind torch.matmul:

@@ -67,7 +67,7 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
   auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
     if (g.group_m <= 0) g.group_m = 8;
     g.m_pad = w.t_pad;
-    if (!bf16) return launch_gemm_f32(g, a, false, st);
+    if (!bf16) return launch_gemm_f32(g, a, false, st, n_split);
     if (small_m && !g.partial && (g.N & 31) == 0) return launch_skinny_bf16(g, a, (float*)(ws + w.off_kpart), st);
     return launch_gemm_bf16(g, a, false, shape, n_split, st);
   };
@@ -113,11 +113,12 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.M = M; g.N = L.rp; g.K = L.mp;
     g.split_col = L.rp;
     g.group_m = 1;   // h2 is the large operand
-    if (bf16 && w.g3_split > 1 && !small_m) {
+    if (w.g3_split > 1 && !small_m) {
       float* part = (float*)(ws + w.off_kpart);
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
       FFS_TRY(run(g, ACT_NONE, big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128, w.g3_split));
-      FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, 1, st));
+      FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, L.tiled, st,
+                                   bf16 ? 0 : 1));
     } else {
       g.C0 = cat + koff_bytes(L.kp); g.ldc0 = L.k4; g.c0_tiled = L.tiled;
       FFS_TRY(run(g, ACT_NONE, big_m ? GEMM_256x128 : GEMM_128x128, 1));

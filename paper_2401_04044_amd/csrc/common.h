@@ -86,7 +86,8 @@ struct GemmArgs {
   int n_out;
 };
 
-int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st);
+// n_split > 1: only with a.partial and no activation: fp32 partials [split][M][ldc0] into C0
+int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st, int n_split = 1);
 // tile configurations of the bf16 kernel
 enum {
   GEMM_256x128 = 0,        // 4 wavefronts, 3 stages: the default for large products
@@ -97,8 +98,9 @@ enum {
 };
 // n_split > 1 only with a.partial
 int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_split, hipStream_t st);
+// sum of the partials in a fixed order -> C (bf16, tiled or row-major; f32_out: fp32 row-major)
 int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
-                         hipStream_t st);
+                         hipStream_t st, int f32_out = 0);
 int bf16_score_tile_m();
 // small-batch path (M <= SKINNY_MAX_M, N a multiple of 32): weight-streaming kernels, one or two
 // blocks of 32 tokens per pass over the weights (four blocks were measured no better than the

@@ -46,12 +46,21 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-  for (int k0 = 0; k0 < p.K; k0 += BK) {
-    const bool ok = (k0 + lk) < p.K;
-    float4 va[NA], vb;
+  // gridDim.y > 1 (only with p.partial): this workgroup's range of the reduction, whole slabs
+  const int slabs = (p.K + BK - 1) / BK;
+  const int per = (slabs + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int k_begin = (int)blockIdx.y * per * BK;
+  const int k_end = min(p.K, k_begin + per * BK);
+  // the next slab's global loads are in flight while this one is multiplied
+  float4 va[NA], vb;
+  auto fetch = [&](int k0) {
+    const bool ok = k0 < k_end && (k0 + lk) < p.K;
 #pragma unroll
     for (int s = 0; s < NA; ++s) va[s] = ok ? *(const float4*)(a_src[s] + k0) : make_float4(0, 0, 0, 0);
     vb = ok ? *(const float4*)(b_src + k0) : make_float4(0, 0, 0, 0);
+  };
+  fetch(k_begin);
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < NA; ++s) {
@@ -60,6 +69,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs p) {
     }
     sB[lk + 0][lrow] = vb.x; sB[lk + 1][lrow] = vb.y; sB[lk + 2][lrow] = vb.z; sB[lk + 3][lrow] = vb.w;
     __syncthreads();
+    fetch(k0 + BK);
 #pragma unroll
     for (int k = 0; k < BK; ++k) {
       float a[NA][4], b[4];
@@ -91,6 +101,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs p) {
       int64_t ld;
       if (oc < p.split_col) { base = (float*)p.C0 + oc; ld = p.ldc0; }
       else { base = (float*)p.C1 + (oc - p.split_col); ld = p.ldc1; }
+      if (p.partial) base += (int64_t)blockIdx.y * p.M * p.ldc0;   // fp32 partials [split][M][ldc0]
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = m0 + ty + 16 * i;
@@ -136,24 +147,25 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs p) {
 // ------------------------------------------------------------------ host launchers
 
 template <int ACT, bool DUAL, bool SCORE>
-static int launch_f32(const GemmArgs& a, hipStream_t st) {
+static int launch_f32(const GemmArgs& a, int n_split, hipStream_t st) {
   const int tiles = ((a.M + 63) / 64) * ((a.N + 63) / 64);
-  hipLaunchKernelGGL((gemm_f32_kernel<ACT, DUAL, SCORE>), dim3(tiles), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((gemm_f32_kernel<ACT, DUAL, SCORE>), dim3(tiles, n_split), dim3(256), 0, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st) {
+int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st, int n_split) {
   if (a.M <= 0 || a.N <= 0) return 0;
   const bool dual = a.A1 != nullptr;
+  if (n_split > 1 && !(a.partial && act == ACT_NONE && !score)) return -1;
   if (score) {
-    if (act == ACT_GELU) return launch_f32<ACT_GELU, false, true>(a, st);
-    if (act == ACT_GLU) return launch_f32<ACT_GLU, false, true>(a, st);
+    if (act == ACT_GELU) return launch_f32<ACT_GELU, false, true>(a, 1, st);
+    if (act == ACT_GLU) return launch_f32<ACT_GLU, false, true>(a, 1, st);
     return -1;
   }
-  if (act == ACT_NONE) return launch_f32<ACT_NONE, false, false>(a, st);
-  if (act == ACT_GELU) return launch_f32<ACT_GELU, false, false>(a, st);
-  if (act == ACT_GLU && !dual) return launch_f32<ACT_GLU, false, false>(a, st);
-  if (act == ACT_GLU && dual) return launch_f32<ACT_GLU, true, false>(a, st);
+  if (act == ACT_NONE) return launch_f32<ACT_NONE, false, false>(a, n_split, st);
+  if (act == ACT_GELU) return launch_f32<ACT_GELU, false, false>(a, 1, st);
+  if (act == ACT_GLU && !dual) return launch_f32<ACT_GLU, false, false>(a, 1, st);
+  if (act == ACT_GLU && dual) return launch_f32<ACT_GLU, true, false>(a, 1, st);
   return -1;
 }
 

@@ -504,7 +504,7 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
 
 // Sum of fp32 split-K partials [n_split][M][N] (fixed order) -> bf16, tiled or row-major.
 __global__ void splitk_reduce_kernel(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc,
-                                     int tiled) {
+                                     int tiled, int f32_out) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 8-column chunk each
   const int cpr = N / 8;
   if (id >= (int64_t)m_pad * cpr) return;
@@ -516,6 +516,14 @@ __global__ void splitk_reduce_kernel(const float* part, int n_split, int M, int 
       const float4 b = *(const float4*)(part + ((int64_t)s * M + row) * N + c8 + 4);
       v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w; v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
     }
+  if (f32_out) {
+    if (row < M) {
+      float* dst = (float*)C + (int64_t)row * ldc + c8;
+      *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+      *(float4*)(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    return;
+  }
   const uint4 val = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
                                pack_bf16x2(v[6], v[7]));
   if (tiled) {
@@ -527,11 +535,11 @@ __global__ void splitk_reduce_kernel(const float* part, int n_split, int M, int 
 }
 
 int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
-                         hipStream_t st) {
+                         hipStream_t st, int f32_out) {
   const int64_t n = (int64_t)m_pad * (N / 8);
   if (n <= 0) return 0;
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, n_split, M, N,
-                     m_pad, C, ldc, tiled);
+                     m_pad, C, ldc, tiled, f32_out);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

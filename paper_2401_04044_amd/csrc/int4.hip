@@ -918,6 +918,17 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
   w.off_h2 = off; off = align256(off + (size_t)w.t_pad * L.mp * L.esz);
   w.g3_split = 1;
   w.off_kpart = off;
+  if (!L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
+    // fp32: the product h2 * P2 has few 64 x 64 tiles and a long reduction: split it so that
+    // about 256 workgroups exist, at least 8 slabs of 16 each
+    const int tiles64 = (int)((T + 63) / 64) * ((L.rp + 63) / 64);
+    int sp = 256 / (tiles64 > 0 ? tiles64 : 1);
+    if (sp > L.mp / 128) sp = L.mp / 128;
+    if (sp > 32) sp = 32;
+    if (sp < 1) sp = 1;
+    w.g3_split = sp;
+    if (sp > 1) off = align256(off + (size_t)sp * T * L.rp * 4);
+  }
   if (L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
     // Split the long reduction of h2 * P2 across workgroups (more splits cost more partial-sum
     // traffic than they gain: measured).  Narrow products (rank <= 512 at 4096 rows) use 128x128
