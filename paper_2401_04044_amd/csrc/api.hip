@@ -69,6 +69,19 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.m_pad = w.t_pad;
     if (!bf16) return launch_gemm_f32(g, a, false, st, n_split);
     if (small_m && !g.partial && (g.N & 31) == 0) return launch_skinny_bf16(g, a, (float*)(ws + w.off_kpart), st);
+    if (!small_m && M <= 1024 && !g.partial && !g.A1) {
+      // a few hundred rows and few tiles: split the reduction, epilogue in a second launch
+      const int sp = mid_split(M, g.N, g.K);
+      if (sp > 1) {
+        float* part = (float*)(ws + w.off_kpart);
+        const int ldp = round_up(g.N, 32);
+        GemmArgs gp = g;
+        gp.partial = 1; gp.C0 = part; gp.ldc0 = ldp; gp.split_col = ldp; gp.act_cols = 0;
+        gp.c0_tiled = 0; gp.c1_tiled = 0;
+        if (launch_gemm_bf16(gp, ACT_NONE, false, GEMM_128x128, sp, st) != 0) return -1;
+        return launch_splitk_epilogue(part, sp, ldp, g, a, st);
+      }
+    }
     return launch_gemm_bf16(g, a, false, shape, n_split, st);
   };
   const int big_m = M > 1024;   // 256-row tiles only pay off with enough rows

@@ -101,6 +101,9 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
 // sum of the partials in a fixed order -> C (bf16, tiled or row-major; f32_out: fp32 row-major)
 int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad, void* C, int64_t ldc, int tiled,
                          hipStream_t st, int f32_out = 0);
+// sum of the fp32 partials [n_split][a.M][ldp] of a whole product (written with a.partial, no
+// activation, GEMM column order) + the store epilogue described by a (activation act)
+int launch_splitk_epilogue(const float* part, int n_split, int ldp, const GemmArgs& a, int act, hipStream_t st);
 int bf16_score_tile_m();
 // small-batch path (M <= SKINNY_MAX_M, N a multiple of 32): weight-streaming kernels, one or two
 // blocks of 32 tokens per pass over the weights (four blocks were measured no better than the

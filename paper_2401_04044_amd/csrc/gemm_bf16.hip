@@ -543,6 +543,79 @@ int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// Sum of fp32 split-K partials [n_split][M][ldp] of a whole product (GEMM column order) followed
+// by the store epilogue of the large-batch kernel: activation (GeLU, or SwiGLU on (gate, up)
+// pairs of 32-column blocks), routing to two destinations, bf16, tiled or row-major.  Used for
+// products with few tiles at a few hundred rows, which are split along the reduction to fill
+// the machine.  One thread per (row, 8 output columns).
+struct SplitEpiArgs {
+  const float* part;
+  int n_split, M, ldp, n_out, rows;   // rows: rows to write (padded to 32 for tiled destinations)
+  int act, act_cols, split_col;
+  void* C0;
+  void* C1;
+  int64_t ldc0, ldc1;
+  int c0_tiled, c1_tiled, n_store;
+};
+
+__global__ void __launch_bounds__(256) splitk_epilogue_kernel(const SplitEpiArgs p) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int cpr = p.n_out / 8;
+  if (id >= (int64_t)p.rows * cpr) return;
+  const int row = (int)(id / cpr), oc = (int)(id % cpr) * 8;
+  const bool glu = p.act == ACT_GLU;
+  const bool pair = glu && oc < p.act_cols / 2;
+  int c = oc;                                   // GEMM column of the (gate) values
+  if (glu) c = pair ? (oc / 32) * 64 + (oc & 31) : oc + p.act_cols / 2;
+  float v[8] = {0, 0, 0, 0, 0, 0, 0, 0}, u[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (row < p.M) {
+    for (int s = 0; s < p.n_split; ++s) {
+      const float* src = p.part + ((int64_t)s * p.M + row) * p.ldp + c;
+      const float4 a = *(const float4*)src, b = *(const float4*)(src + 4);
+      v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w; v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+      if (pair) {
+        const float4 e = *(const float4*)(src + 32), f = *(const float4*)(src + 36);
+        u[0] += e.x; u[1] += e.y; u[2] += e.z; u[3] += e.w; u[4] += f.x; u[5] += f.y; u[6] += f.z; u[7] += f.w;
+      }
+    }
+    if (pair) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = silu_fast(v[e]) * u[e];
+    } else if (p.act == ACT_GELU && c < p.act_cols) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = gelu_fast(v[e]);
+    }
+  }
+  char* base;
+  int64_t ld;
+  int col, tiled;
+  if (oc < p.split_col) { base = (char*)p.C0; ld = p.ldc0; col = oc; tiled = p.c0_tiled; }
+  else { base = (char*)p.C1; ld = p.ldc1; col = oc - p.split_col; tiled = p.c1_tiled; }
+  const uint4 val = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                               pack_bf16x2(v[6], v[7]));
+  if (tiled) {
+    const int64_t blk = (int64_t)(row / 32) * (ld / 16) + col / 16;
+    *(uint4*)(base + ((blk * 64) + ((col >> 3) & 1) * 32 + (row & 31)) * 16) = val;
+  } else if (row < p.M && col < p.n_store) {
+    *(uint4*)(base + ((int64_t)row * ld + col) * 2) = val;
+  }
+}
+
+int launch_splitk_epilogue(const float* part, int n_split, int ldp, const GemmArgs& g, int act, hipStream_t st) {
+  SplitEpiArgs a = {};
+  a.part = part; a.n_split = n_split; a.M = g.M; a.ldp = ldp;
+  a.n_out = act == ACT_GLU ? g.N - g.act_cols / 2 : g.N;
+  a.rows = (g.c0_tiled || g.c1_tiled) ? (g.M + 31) / 32 * 32 : g.M;
+  a.act = act; a.act_cols = g.act_cols; a.split_col = g.split_col;
+  a.C0 = g.C0; a.C1 = g.C1; a.ldc0 = g.ldc0; a.ldc1 = g.ldc1;
+  a.c0_tiled = g.c0_tiled; a.c1_tiled = g.c1_tiled; a.n_store = g.n_store;
+  if ((a.n_out & 7) || (g.split_col & 7) || (g.act_cols & 63)) return -1;
+  const int64_t n = (int64_t)a.rows * (a.n_out / 8);
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(splitk_epilogue_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 // ------------------------------------------------------------------ host launcher
 
 template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>

@@ -123,6 +123,18 @@ inline ScoreWs make_score_ws(const ffsplit_desc_t& d, int64_t T) {
   return w;
 }
 
+// A few hundred rows (above the weight-streaming kernels, up to 1024): a product with fewer than
+// 128 tiles of 128 x 128 is split along its reduction into about 256 workgroups (at least 256
+// reduction elements each); its fp32 partials then take the epilogue in a second launch.
+inline int mid_split(int64_t T, int N, int K) {
+  const int tiles = (int)((T + 127) / 128) * ((N + 127) / 128);
+  if (tiles <= 0 || tiles >= 128) return 1;
+  int sp = 256 / tiles;
+  if (sp > K / 256) sp = K / 256;
+  if (sp > 16) sp = 16;
+  return sp > 1 ? sp : 1;
+}
+
 struct FwdWs {
   size_t off_cat, off_t, off_h2, off_kpart;
   int t_pad;       // rows of the intermediates (T, padded to 32 when tiled)
