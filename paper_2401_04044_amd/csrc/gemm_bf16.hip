@@ -262,6 +262,10 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
   const int nk = min(kt_total, kt0 + kt_per) - kt0;
 
   // ---- the LPW blocks this wavefront moves per slab: block b = wave + i NW of the stage
+  // Row-major A with 32-deep slabs: one load instruction covers 16 rows x 64 contiguous bytes
+  // (16 cache lines) instead of 32 rows x 32 bytes; the chunks are placed so that the fragment
+  // reads stay free of bank conflicts.
+  constexpr bool rows16 = !A_TILED && !DUAL && KB == 2 && KG == 1;
   const char* src[LPW];
   const char* a_row[LA];   // row-major A: start of the lane's row (substitute for chunks past K)
   int a_col[LA];           // row-major A: column of the lane's chunk inside the slab
@@ -278,11 +282,27 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
       a_row[i] = nullptr; a_col[i] = 0;
     } else {
       int row = m0 + rb * 32 + (lane & 31);
-      row = row < p.M ? row : p.M - 1;
       a_col[i] = kb * 16 + (lane >> 5) * 8;
+      if (rows16) {
+        // block (rb, kb) holds rows 16 kb .. 16 kb + 15 of the row block with all four 16-byte
+        // chunks of the slab: lane = 4 rowl + position, chunk = position ^ ((rowl >> 2) & 3)
+        const int rowl = lane >> 2;
+        row = m0 + rb * 32 + kb * 16 + rowl;
+        a_col[i] = ((lane & 3) ^ ((rowl >> 2) & 3)) * 8;
+      }
+      row = row < p.M ? row : p.M - 1;
       a_row[i] = base + (int64_t)row * p.lda * 2;
       src[i] = a_row[i] + ((int64_t)kt0 * BK + a_col[i]) * 2;
     }
+  }
+  // LDS offset (16-byte units) of the lane's A fragment inside a row block's KB blocks, per k block
+  int a_frag[2];
+  a_frag[0] = lane; a_frag[1] = 64 + lane;
+  if (rows16) {
+    const int r = lane & 31, c = lane >> 5, rowl = r & 15, sw = (rowl >> 2) & 3;
+    const int x0 = (sw & 2) + (c ^ (sw & 1));
+    a_frag[0] = (r >> 4) * 64 + rowl * 4 + x0;
+    a_frag[1] = (r >> 4) * 64 + rowl * 4 + (x0 ^ 2);
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
@@ -335,7 +355,12 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int s = 0; s < NA; ++s) fa[set][s][i].u = sA[((s * (BM / 32) + wm * TM + i) * KB + ks) * 64 + lane];
+      for (int s = 0; s < NA; ++s) {
+        if (rows16)
+          fa[set][s][i].u = sA[(wm * TM + i) * KB * 64 + a_frag[ls]];
+        else
+          fa[set][s][i].u = sA[((s * (BM / 32) + wm * TM + i) * KB + ks) * 64 + lane];
+      }
 #pragma unroll
     for (int jj = 0; jj < TN; ++jj) fb[set][jj].u = sB[((wn * TN + jj) * KB + ks) * 64 + lane];
   };
