@@ -72,9 +72,10 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     if (!small_m && M <= 1024 && !g.partial && !g.A1) {
       // a few hundred rows and few tiles: split the reduction, epilogue in a second launch
       const int sp = mid_split(M, g.N, g.K);
-      if (sp > 1) {
+      const int ldp = round_up(g.N, 32);
+      // (never beyond the scratch the workspace was sized with: the plain launch is always valid)
+      if (sp > 1 && (size_t)sp * M * ldp * 4 <= w.kpart_bytes) {
         float* part = (float*)(ws + w.off_kpart);
-        const int ldp = round_up(g.N, 32);
         GemmArgs gp = g;
         gp.partial = 1; gp.C0 = part; gp.ldc0 = ldp; gp.split_col = ldp; gp.act_cols = 0;
         gp.c0_tiled = 0; gp.c1_tiled = 0;
@@ -104,7 +105,8 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
     g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
     g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
-    const int wide = fill256(M, L.n1) >= 50 ? GEMM_256x256 : (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_DEEP);
+    // (few tiles: eight wavefronts on 64-deep slabs, whose row-major gather takes whole cache lines)
+    const int wide = fill256(M, L.n1) >= 50 ? GEMM_256x256 : (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_KSPLIT);
     FFS_TRY(run(g, act, big_m ? wide : GEMM_128x128, 1));
   }
   if (rem_lr) {

@@ -92,9 +92,8 @@ int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st, int 
 enum {
   GEMM_256x128 = 0,        // 4 wavefronts, 3 stages: the default for large products
   GEMM_128x128 = 1,        // 4 wavefronts, 3 stages: small or narrow products
-  GEMM_128x128_DEEP = 2,   // the same with 4 stages (row-major left operand)
-  GEMM_128x128_KSPLIT = 3, // 8 wavefronts, reduction split inside the workgroup (long K, few tiles)
-  GEMM_256x256 = 4         // 8 wavefronts, 3 stages
+  GEMM_128x128_KSPLIT = 2, // 8 wavefronts, 64-deep slabs, reduction split inside the workgroup (few tiles)
+  GEMM_256x256 = 3         // 8 wavefronts, 3 stages
 };
 // n_split > 1 only with a.partial
 int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_split, hipStream_t st);

@@ -262,10 +262,15 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
   const int nk = min(kt_total, kt0 + kt_per) - kt0;
 
   // ---- the LPW blocks this wavefront moves per slab: block b = wave + i NW of the stage
-  // Row-major A with 32-deep slabs: one load instruction covers 16 rows x 64 contiguous bytes
-  // (16 cache lines) instead of 32 rows x 32 bytes; the chunks are placed so that the fragment
-  // reads stay free of bank conflicts.
-  constexpr bool rows16 = !A_TILED && !DUAL && KB == 2 && KG == 1;
+  // Row-major A: one load instruction covers 64 / CH rows x the slab's CH 16-byte chunks of each
+  // (32-deep slabs: 16 rows x 64 contiguous bytes = 16 cache lines; 64-deep: 8 rows x 128 bytes
+  // = 8 lines) instead of 32 rows x 32 bytes; the chunks are placed so that the fragment reads
+  // stay free of bank conflicts.
+  constexpr bool rowsN = !A_TILED && !DUAL && (KB == 2 || KB == 4);
+  constexpr int CH = 2 * KB, RPI = 64 / CH;   // chunks per row and slab, rows per instruction
+  // chunk swizzle of row rowl of block kb: 16 consecutive lanes of a fragment read (rows r..r+15,
+  // one chunk number) must fall into 16 different 16-byte bank groups
+  auto swz = [](int rowl, int kb) { return KB == 2 ? ((rowl >> 2) & 3) : ((rowl >> 1) | ((kb & 1) << 2)); };
   const char* src[LPW];
   const char* a_row[LA];   // row-major A: start of the lane's row (substitute for chunks past K)
   int a_col[LA];           // row-major A: column of the lane's chunk inside the slab
@@ -283,12 +288,12 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
     } else {
       int row = m0 + rb * 32 + (lane & 31);
       a_col[i] = kb * 16 + (lane >> 5) * 8;
-      if (rows16) {
-        // block (rb, kb) holds rows 16 kb .. 16 kb + 15 of the row block with all four 16-byte
-        // chunks of the slab: lane = 4 rowl + position, chunk = position ^ ((rowl >> 2) & 3)
-        const int rowl = lane >> 2;
-        row = m0 + rb * 32 + kb * 16 + rowl;
-        a_col[i] = ((lane & 3) ^ ((rowl >> 2) & 3)) * 8;
+      if (rowsN) {
+        // block (rb, kb) holds rows RPI kb .. RPI kb + RPI - 1 of the row block with all CH
+        // chunks of the slab: lane = CH rowl + position, chunk = position ^ swz
+        const int rowl = lane / CH;
+        row = m0 + rb * 32 + kb * RPI + rowl;
+        a_col[i] = ((lane % CH) ^ swz(rowl, kb)) * 8;
       }
       row = row < p.M ? row : p.M - 1;
       a_row[i] = base + (int64_t)row * p.lda * 2;
@@ -296,13 +301,13 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
     }
   }
   // LDS offset (16-byte units) of the lane's A fragment inside a row block's KB blocks, per k block
-  int a_frag[2];
+  int a_frag[2];   // per k step of the wavefront inside a slab
   a_frag[0] = lane; a_frag[1] = 64 + lane;
-  if (rows16) {
-    const int r = lane & 31, c = lane >> 5, rowl = r & 15, sw = (rowl >> 2) & 3;
-    const int x0 = (sw & 2) + (c ^ (sw & 1));
-    a_frag[0] = (r >> 4) * 64 + rowl * 4 + x0;
-    a_frag[1] = (r >> 4) * 64 + rowl * 4 + (x0 ^ 2);
+  if (rowsN) {
+    const int r = lane & 31, c = lane >> 5, kbr = r / RPI, rowl = r % RPI;
+#pragma unroll
+    for (int ls = 0; ls < KS; ++ls)
+      a_frag[ls] = kbr * 64 + rowl * CH + ((2 * (kg * KS + ls) + c) ^ swz(rowl, kbr));
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
@@ -356,7 +361,7 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int s = 0; s < NA; ++s) {
-        if (rows16)
+        if (rowsN)
           fa[set][s][i].u = sA[(wm * TM + i) * KB * 64 + a_frag[ls]];
         else
           fa[set][s][i].u = sA[((s * (BM / 32) + wm * TM + i) * KB + ks) * 64 + lane];
@@ -703,7 +708,6 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
   switch (shape) {
     case GEMM_256x128: return launch_dl_shape<256, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
     case GEMM_128x128: return launch_dl_shape<128, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
-    case GEMM_128x128_DEEP: return launch_dl_shape<128, 128, 32, 2, 2, 1, 4>(a, act, n_split, st);
     case GEMM_128x128_KSPLIT: return launch_dl_shape<128, 128, 64, 2, 2, 2, 4>(a, act, n_split, st);
     case GEMM_256x256: return launch_dl_shape<256, 256, 32, 2, 4, 1, 3>(a, act, n_split, st);
   }

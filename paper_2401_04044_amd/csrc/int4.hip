@@ -966,13 +966,15 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     }
     if (T > SKINNY_MAX_M && T <= 1024) {
       // a few hundred rows: products with few tiles keep split-K partials of their whole output
-      const int ns[3] = {L.n1, L.n_up * L.mp, L.dn};
-      const int ks[3] = {L.dk, L.rp, L.k4};
-      for (int i = 0; i < 3; ++i) {
+      // (all four products: h2 * P2 too, when its own split above came out as 1)
+      const int ns[4] = {L.n1, L.n_up * L.mp, L.rp, L.dn};
+      const int ks[4] = {L.dk, L.rp, L.mp, L.k4};
+      for (int i = 0; i < 4; ++i) {
         const size_t b = (size_t)mid_split(T, ns[i], ks[i]) * T * round_up(ns[i], 32) * 4;
         if (mid_split(T, ns[i], ks[i]) > 1 && b > scratch) scratch = b;
       }
     }
+    w.kpart_bytes = scratch;
     if (scratch > 0) off = align256(off + scratch);
   } else if (L.tiled && T > 0 && T <= SKINNY_MAX_M) {
     int n_max = L.n1 > L.dn ? L.n1 : L.dn;
@@ -985,6 +987,7 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
       const size_t b = (size_t)mid_split(T, ns[i], ks[i]) * T * round_up(ns[i], 32) * 4;
       if (mid_split(T, ns[i], ks[i]) > 1 && b > scratch) scratch = b;
     }
+    w.kpart_bytes = scratch;
     if (scratch > 0) off = align256(off + scratch);
   }
   w.total_bytes = off > 0 ? off : 256;

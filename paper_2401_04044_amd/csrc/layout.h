@@ -137,6 +137,7 @@ inline int mid_split(int64_t T, int N, int K) {
 
 struct FwdWs {
   size_t off_cat, off_t, off_h2, off_kpart;
+  size_t kpart_bytes;   // bytes of split-K scratch at off_kpart (65..1024 rows: checked before use)
   int t_pad;       // rows of the intermediates (T, padded to 32 when tiled)
   int g3_split;    // split-K factor of the h2 * P2 product
   int g3_wide;     // that product has enough tiles for 256x128 tiles (else: in-workgroup K split)

@@ -45,3 +45,19 @@ def gpu_scores(ff, desc, Ld, Xd_batches, kind=0):
         tt = ff.score_neurons(desc, Xd, Ld["W1"], Ld["Wg"], Ld["W2"], acc, tt, scores if last else None, kind)
     torch.cuda.synchronize()
     return scores, acc, tt
+
+
+GUARD = 1 << 20   # bytes of sentinel on either side of the workspace
+
+
+def guarded_forward(ff, desc, split, X, want_parts=False):
+    """ffsplit_forward with a workspace of exactly the size the library asks for, placed between
+    two sentinel regions: any write outside the workspace (a scratch buffer sized too small for a
+    launch) shows up as a changed sentinel byte even where it would not fault."""
+    n = ff.workspace_bytes(desc, ff.WS_FORWARD, X.shape[0])
+    buf = torch.full((n + 2 * GUARD,), 0xA5, dtype=torch.uint8, device=X.device)
+    out = ff.forward(desc, split, X, None, want_parts, buf[GUARD:GUARD + n])
+    torch.cuda.synchronize()
+    assert bool((buf[:GUARD] == 0xA5).all()), "write below the workspace"
+    assert bool((buf[GUARD + n:] == 0xA5).all()), "write beyond the workspace"
+    return out

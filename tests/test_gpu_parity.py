@@ -9,7 +9,7 @@ import torch
 from oracle import ffsplit_oracle as orc
 import workloads as wl
 from workloads.configs import C1, C2, C3, C4, C5, reduced
-from gpu_util import TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores
+from gpu_util import TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores, guarded_forward
 
 pytestmark = pytest.mark.gpu
 
@@ -149,9 +149,8 @@ def run_forward(ff, cfg, L, idx, T, rem_kind, factors=None, rank=None, X=None):
     desc = desc_for(ff, cfg, rem_kind, k=len(idx), rank=rank)
     fd = None if factors is None else {k: dev(v, cfg.dtype) for k, v in factors.items()}
     split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(np.asarray(idx, np.int32)).cuda(), fd)
-    Y, Yh, Yr = ff.forward(desc, split, dev(X, cfg.dtype), want_parts=True)
-    Y_only = ff.forward(desc, split, dev(X, cfg.dtype))
-    torch.cuda.synchronize()
+    Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, cfg.dtype), want_parts=True)
+    Y_only = guarded_forward(ff, desc, split, dev(X, cfg.dtype))
     assert torch.equal(Y, Y_only)
     want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], np.asarray(idx), cfg.act, rem_kind, factors,
                              group=cfg.group or 128)
@@ -160,12 +159,6 @@ def run_forward(ff, cfg, L, idx, T, rem_kind, factors=None, rank=None, X=None):
 
 @pytest.mark.parametrize("name,cfg,T", FWD_CASES, ids=[c[0] for c in FWD_CASES])
 def test_forward_lowrank_matches_oracle(ff, name, cfg, T):
-    if name == "mid_batch_gelu_70":
-        # One run of this case ended with the GPU reported faulted although pytest itself finished and
-        # although every launch of the case (grids, operand sizes, scratch) is the same as in all the
-        # runs it passed before and after; no out-of-bounds access was found by reading.  Kept off the
-        # GPU until a cause is shown; 65, 96, 129, 130 and 131 rows cover the same kernels.
-        pytest.skip("kept off the GPU: one unexplained device fault report on this case")
     L = wl.make_layer(cfg)
     idx = L["planted"][::-1].copy()             # any order of the heavy set is allowed
     fac = wl.make_factors(cfg, L, idx)
@@ -257,7 +250,7 @@ def test_int4_codes_scales_and_forward(ff, name, cfg, Bs):
         assert np.array_equal(s.cpu().numpy().view(np.uint16), qw[nm][1].view(np.uint16)), nm
     for B in Bs:
         X = wl.make_tokens(cfg, B)
-        Y, Yh, Yr = ff.forward(desc, split, dev(X, cfg.dtype), want_parts=True)
+        Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, cfg.dtype), want_parts=True)
         torch.cuda.synchronize()
         want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=cfg.group)
         for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
@@ -273,7 +266,7 @@ def test_int4_edge_sets(ff):
         split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
         for T in (4, 250):                      # decode kernels / expanded weights
             X = wl.make_tokens(cfg, T)
-            Y = ff.forward(desc, split, dev(X, cfg.dtype))
+            Y = guarded_forward(ff, desc, split, dev(X, cfg.dtype))
             torch.cuda.synchronize()
             want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "int4", group=128)
             assert relf(host(Y), want[0]) < TOL["bf16"], T
@@ -337,8 +330,8 @@ def test_w3h8_codes_scales_and_forward(ff, name, cfg, Ts):
         assert np.array_equal(s.cpu().numpy().view(np.uint16), src[nm][1].view(np.uint16)), nm
     for T in Ts:
         X = wl.make_tokens(cfg, T)
-        Y, Yh, Yr = ff.forward(desc, split, dev(X, cfg.dtype), want_parts=True)
-        Y_only = ff.forward(desc, split, dev(X, cfg.dtype))
+        Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, cfg.dtype), want_parts=True)
+        Y_only = guarded_forward(ff, desc, split, dev(X, cfg.dtype))
         torch.cuda.synchronize()
         assert torch.equal(Y, Y_only)
         want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "w3h8", group=128)
@@ -355,7 +348,7 @@ def test_w3h8_edge_sets(ff):
         split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda())
         for T in (4, 250):
             X = wl.make_tokens(cfg, T)
-            Y = ff.forward(desc, split, dev(X, cfg.dtype))
+            Y = guarded_forward(ff, desc, split, dev(X, cfg.dtype))
             torch.cuda.synchronize()
             want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "w3h8", group=128)
             assert relf(host(Y), want[0]) < TOL["bf16"], T
@@ -405,7 +398,7 @@ def test_factorize_remainder_matches_oracle(ff, name, cfg, tol):
     T = 50
     X = wl.make_tokens(cfg, T)
     split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], idx_d, fd)
-    Y = ff.forward(desc, split, dev(X, cfg.dtype))
+    Y = guarded_forward(ff, desc, split, dev(X, cfg.dtype))
     torch.cuda.synchronize()
     ref = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, cfg.act, "lowrank", got)
     assert relf(host(Y), ref[0]) < TOL[cfg.dtype]
@@ -434,6 +427,8 @@ def _sweep_cases():
 # 65..1024 rows with reductions of 512 and more: products with few tiles are split along the
 # reduction (fp32 partials, then activation / routing / store in a second launch)
 _FEW_HUNDRED = [
+    ("lowrank_gelu_T70_g3_unsplit", "lowrank", "gelu", 256, 1000, 40, 64, 70),
+    ("lowrank_swiglu_T90_g3_unsplit", "lowrank", "swiglu", 128, 560, 50, 64, 90),
     ("lowrank_gelu_T200", "lowrank", "gelu", 1032, 1500, 90, 520, 200),
     ("lowrank_swiglu_T130", "lowrank", "swiglu", 1024, 1400, 70, 300, 130),
     ("lowrank_swiglu_T65_ragged_d", "lowrank", "swiglu", 1160, 900, 600, 100, 65),
@@ -467,8 +462,7 @@ def test_forward_sweep(ff, name, kind, act, d, d_ff, k, r, T):
     fd = None if fac is None else {kk: dev(v, "bf16") for kk, v in fac.items()}
     split = ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], torch.from_numpy(idx).cuda(), fd)
     X = wl.make_tokens(cfg, T)
-    Y, Yh, Yr = ff.forward(desc, split, dev(X, "bf16"), want_parts=True)
-    torch.cuda.synchronize()
+    Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "bf16"), want_parts=True)
     want = orc.forward_split(X, L["W1"], L["W2"], L["Wg"], idx, act, kind, fac, group=128)
     for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
         if np.linalg.norm(w) == 0:
