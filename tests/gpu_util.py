@@ -61,3 +61,17 @@ def guarded_forward(ff, desc, split, X, want_parts=False):
     assert bool((buf[:GUARD] == 0xA5).all()), "write below the workspace"
     assert bool((buf[GUARD + n:] == 0xA5).all()), "write beyond the workspace"
     return out
+
+
+class Guarded:
+    """A device buffer of exactly n bytes between two sentinel regions (256-byte aligned start)."""
+
+    def __init__(self, n, device="cuda"):
+        self.n = int(n)
+        self.buf = torch.full((self.n + 2 * GUARD,), 0xA5, dtype=torch.uint8, device=device)
+        self.view = self.buf[GUARD:GUARD + self.n]
+
+    def check(self, what):
+        torch.cuda.synchronize()
+        assert bool((self.buf[:GUARD] == 0xA5).all()), f"{what}: write below the buffer"
+        assert bool((self.buf[GUARD + self.n:] == 0xA5).all()), f"{what}: write beyond the buffer"

@@ -9,7 +9,7 @@ import torch
 from oracle import ffsplit_oracle as orc
 import workloads as wl
 from workloads.configs import C1, C2, C3, C4, C5, reduced
-from gpu_util import TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores, guarded_forward
+from gpu_util import TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores, guarded_forward, Guarded
 
 pytestmark = pytest.mark.gpu
 
@@ -469,3 +469,43 @@ def test_forward_sweep(ff, name, kind, act, d, d_ff, k, r, T):
             assert not host(g).any(), nm
         else:
             assert relf(host(g), w) < TOL["bf16"], (nm, relf(host(g), w))
+
+
+# ---------------------------------------------------------------- every call inside its buffers
+
+@pytest.mark.parametrize("act,dtype", [("gelu", "bf16"), ("swiglu", "bf16"), ("gelu", "f32")])
+def test_calls_stay_inside_workspace_and_split(ff, act, dtype):
+    """Score, select, build (every remainder kind), factorise: workspace and packed split of exactly
+    the sizes the library reports, each between sentinel regions that must come back unchanged."""
+    base = C3 if act == "swiglu" else C2
+    cfg = base.__class__(**{**base.__dict__, "name": "guard", "d_model": 256, "d_ff": 777, "k": 70, "rank": 40,
+                            "rem_kind": "lowrank", "group": 128, "dtype": dtype})
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, dtype)
+    T = 300
+    Xd = dev(wl.make_tokens(cfg, T, wl.gen.S_CALIB), dtype)
+    d0 = desc_for(ff, cfg, "none")
+    acc = torch.zeros(2 * cfg.d_ff, dtype=torch.float32, device="cuda")
+    scores = torch.empty(cfg.d_ff, dtype=torch.float32, device="cuda")
+    g = Guarded(ff.workspace_bytes(d0, ff.WS_SCORE, T))
+    ff.score_neurons(d0, Xd, Ld["W1"], Ld["Wg"], Ld["W2"], acc, 0, scores, 0, g.view)
+    g.check("score_neurons")
+    g = Guarded(ff.workspace_bytes(d0, ff.WS_SELECT, 0))
+    idx, _, _ = ff.select_heavy(scores, cfg.k, True, g.view)
+    g.check("select_heavy")
+    kinds = ["none", "dense", "lowrank"] + (["int4", "w3h8"] if dtype == "bf16" else [])
+    for kind in kinds:
+        desc = desc_for(ff, cfg, kind, k=cfg.k, rank=cfg.rank)
+        fd = None
+        if kind == "lowrank":
+            g = Guarded(ff.workspace_bytes(desc, ff.WS_FACTORIZE, 0))
+            fd = ff.factorize_remainder(desc, Ld["W1"], Ld["Wg"], Ld["W2"], idx, 3, g.view)
+            g.check("factorize_remainder")
+        g = Guarded(ff.workspace_bytes(desc, ff.WS_BUILD, 0))
+        sp = Guarded(ff.split_bytes(desc))
+        ff.build_split(desc, Ld["W1"], Ld["Wg"], Ld["W2"], idx, fd, sp.view, g.view)
+        g.check("build_split workspace " + kind)
+        sp.check("build_split split " + kind)
+        for Tf in (3, 40, 150, 1100):
+            guarded_forward(ff, desc, sp.view, Xd[:Tf].contiguous() if Tf <= T else dev(wl.make_tokens(cfg, Tf), dtype))
+        sp.check("forward split " + kind)
