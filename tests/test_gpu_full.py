@@ -10,7 +10,7 @@ import torch
 from oracle import ffsplit_oracle as orc
 import workloads as wl
 from workloads.configs import C1, C2, C3, C4, C5
-from gpu_util import TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores
+from gpu_util import guarded_forward, TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
@@ -56,7 +56,7 @@ def test_c1_bert_shape_fp32_full(ff):
     desc = desc_for(ff, cfg)
     split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, {k: dev(v, "f32") for k, v in fac.items()})
     X = wl.make_tokens(cfg, cfg.prefill_T)
-    Y, Yh, Yr = ff.forward(desc, split, dev(X, "f32"), want_parts=True)
+    Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "f32"), want_parts=True)
     torch.cuda.synchronize()
     want = orc.forward_split(X, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)
     for g, w in zip((Y, Yh, Yr), want):
@@ -78,8 +78,8 @@ def test_c2_opt13b_shape_full_pipeline(ff):
     split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, {k: dev(v, "bf16") for k, v in fac.items()})
     T = cfg.prefill_T
     X = wl.make_tokens(cfg, T)
-    Y, Yh, Yr = ff.forward(desc, split, dev(X, "bf16"), want_parts=True)
-    Y2 = ff.forward(desc, split, dev(X, "bf16"))
+    Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "bf16"), want_parts=True)
+    Y2 = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
     assert torch.equal(Y, Y2)                              # deterministic
     rows = sampled_rows(T, 48)
@@ -109,7 +109,7 @@ def test_c2_opt13b_shape_factorize_on_device(ff):
         assert e < 6e-3, (p, e)                      # two bf16-rounded factors
     split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, fd)
     X = wl.make_tokens(cfg, cfg.prefill_T)
-    Y = ff.forward(desc, split, dev(X, "bf16"))
+    Y = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
     rows = sampled_rows(cfg.prefill_T, 32)
     ref = orc.forward_split(X[rows], L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", got)
@@ -136,7 +136,7 @@ def test_c2_opt13b_shape_65536_tokens(ff):
     Xr = wl.make_tokens(cfg, len(rows), wl.gen.S_EVAL, layer=7)
     Xd[torch.from_numpy(rows).cuda()] = dev(Xr, "bf16")
     Y = ff.forward(desc, split, Xd)
-    Y4 = ff.forward(desc, split, Xd[:4096].contiguous())
+    Y4 = guarded_forward(ff, desc, split, Xd[:4096].contiguous())
     torch.cuda.synchronize()
     ref = orc.forward_split(Xr, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
     assert relf(host(Y[torch.from_numpy(rows).cuda()]), ref) < TOL["bf16"]
@@ -162,7 +162,7 @@ def test_c3_llama7b_shape_prefill_and_decode(ff):
     torch.cuda.empty_cache()
     T = cfg.prefill_T
     X = wl.make_tokens(cfg, T)
-    Y = ff.forward(desc, split, dev(X, "bf16"))
+    Y = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
     rows = sampled_rows(T, 24)
     want = orc.forward_split(X[rows], L["W1"], L["W2"], L["Wg"], idx_h, "swiglu", "lowrank", fac)[0]
@@ -170,7 +170,7 @@ def test_c3_llama7b_shape_prefill_and_decode(ff):
     assert e < TOL["bf16"], e
     for B in cfg.decode_B:
         Xb = wl.make_tokens(cfg, B, wl.gen.S_EVAL, layer=B)
-        Yb = ff.forward(desc, split, dev(Xb, "bf16"))
+        Yb = guarded_forward(ff, desc, split, dev(Xb, "bf16"))
         torch.cuda.synchronize()
         wb = orc.forward_split(Xb, L["W1"], L["W2"], L["Wg"], idx_h, "swiglu", "lowrank", fac)[0]
         e = relf(host(Yb), wb)
@@ -193,7 +193,7 @@ def test_c4_llama7b_shape_int4_decode(ff):
         assert np.array_equal(s.cpu().numpy().view(np.uint16), qw[nm][1].view(np.uint16)), nm
     for B in cfg.decode_B:
         Xb = wl.make_tokens(cfg, B, wl.gen.S_EVAL, layer=B)
-        Yb, Yh, Yr = ff.forward(desc, split, dev(Xb, "bf16"), want_parts=True)
+        Yb, Yh, Yr = guarded_forward(ff, desc, split, dev(Xb, "bf16"), want_parts=True)
         torch.cuda.synchronize()
         Y1 = orc.forward_heavy(Xb, sw, "swiglu")
         Y2 = orc.forward_remainder_int4(Xb, qw, cfg.group, "swiglu")
@@ -213,7 +213,7 @@ def test_c4_llama7b_shape_int4_many_tokens(ff):
     del Ld
     T = 4096
     X = wl.make_tokens(cfg, T)
-    Y, Yh, Yr = ff.forward(desc, split, dev(X, "bf16"), want_parts=True)
+    Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "bf16"), want_parts=True)
     torch.cuda.synchronize()
     rows = sampled_rows(T, 24)
     sw = orc.split_weights(L["W1"], L["W2"], L["Wg"], idx_h)
@@ -251,13 +251,13 @@ def test_c4_llama7b_shape_w3h8(ff):
 
     for B in (1, 16, 32):
         Xb = wl.make_tokens(cfg, B, wl.gen.S_EVAL, layer=B)
-        got = ff.forward(desc, split, dev(Xb, "bf16"), want_parts=True)
+        got = guarded_forward(ff, desc, split, dev(Xb, "bf16"), want_parts=True)
         torch.cuda.synchronize()
         for g, w, nm in zip(got, want(Xb), ("Y", "Y_heavy", "Y_rem")):
             assert relf(host(g), w) < TOL["bf16"], (B, nm, relf(host(g), w))
     T = 4096
     X = wl.make_tokens(cfg, T)
-    Y = ff.forward(desc, split, dev(X, "bf16"))
+    Y = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
     rows = sampled_rows(T, 24)
     assert relf(host(Y[torch.from_numpy(rows).cuda()]), want(X[rows])[0]) < TOL["bf16"]
@@ -299,8 +299,8 @@ def test_c5_opt13b_shape_layers_teacher_forced(ff):
         # prefill: 4096 tokens, the first 64 of them are the oracle's sample
         xn = wl.bf16_round(orc.token_rms_normalise(x_fwd))
         Xfull = np.concatenate([xn, wl.make_tokens(cfg, cfg.prefill_T - 64, wl.gen.S_EVAL, layer=layer + 1)])
-        Y = ff.forward(desc, split, dev(Xfull, "bf16"))
-        Yd = ff.forward(desc, split, dev(xn[:16], "bf16"))       # decode batch of 16
+        Y = guarded_forward(ff, desc, split, dev(Xfull, "bf16"))
+        Yd = guarded_forward(ff, desc, split, dev(xn[:16], "bf16"))       # decode batch of 16
         torch.cuda.synchronize()
         want = orc.forward_split(xn, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
         assert relf(host(Y[:64]), want) < TOL["bf16"]
