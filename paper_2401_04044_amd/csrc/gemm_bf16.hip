@@ -170,7 +170,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
           const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
           const float z = acc[i][(ACT == ACT_GLU) ? j + 1 : j][v];
           const float gt = acc[i][j][v];
-          float h = (ACT == ACT_GLU) ? silu_f(gt) * z : gelu_f(z);   // exact forms for the scores
+          // same activation forms as the forward epilogue: the scores rank what the forward computes
+          // (the erf form costs about a fifth of the calibration pass, nothing hides it at one
+          // workgroup per CU)
+          float h = act_bf16<ACT>(z, gt);
           h = row < p.M ? h : 0.f;
           s2 += h * h;
           s1 += fabsf(h);
