@@ -99,3 +99,44 @@ def test_argument_errors_are_found_on_the_host():
     # T = 0 is a valid no-op that launches nothing
     assert L.ffsplit_forward(ref(good), fake, fake, 0, fake, None, None, None, 0, None) == 0
     assert tt.value == 0
+
+
+def test_forward_workspace_has_room_for_every_split_product():
+    """65..1024 rows of the low-rank chain (bf16): a product with few tiles is split along its
+    reduction and keeps fp32 partials [split][T][N] in the call's workspace.  The size the library
+    reports must cover the intermediates plus the largest of those scratch buffers, for each of
+    the four products (a scratch sized for three of them once let the fourth write past the
+    workspace).  The policy is restated here from its description: fewer than 128 tiles of
+    128 x 128 -> min(256 / tiles, K / 256, 16) splits."""
+    import numpy as np
+    import paper_2401_04044_amd as ff
+
+    def up(v, q):
+        return (v + q - 1) // q * q
+
+    def split_of(T, N, K):
+        tiles = ((T + 127) // 128) * ((N + 127) // 128)
+        if tiles >= 128:
+            return 1
+        return max(1, min(256 // tiles, K // 256, 16))
+
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        glu = bool(rng.integers(0, 2))
+        d = int(rng.integers(8, 400)) * 8
+        d_ff = int(rng.integers(64, 6000))
+        k = int(rng.integers(0, d_ff // 2))
+        m = d_ff - k
+        r = int(rng.integers(1, min(d, m) + 1))
+        T = int(rng.integers(65, 1025))
+        desc = ff.make_desc(d, d_ff, "swiglu" if glu else "gelu", "bf16", k, "lowrank", r)
+        n_up = 2 if glu else 1
+        kp, rp, mp = up(k, 64), up(r, 64), up(m, 64)
+        k4, tp = kp + rp, up(T, 32)
+        inter = sum(up(tp * c * 2, 256) for c in (k4, n_up * rp, mp))
+        products = [(n_up * k4, d), (rp, mp), (d, k4)]          # G1, G3, G4
+        if not glu:
+            products.append((mp, rp))                           # G2 (two left operands: never split)
+        need = max(split_of(T, N, K) * T * up(N, 32) * 4 if split_of(T, N, K) > 1 else 0 for N, K in products)
+        got = ff.workspace_bytes(desc, ff.WS_FORWARD, T)
+        assert got >= inter + need, (d, d_ff, k, r, T, glu, got, inter, need)
