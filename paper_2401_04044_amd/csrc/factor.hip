@@ -122,8 +122,9 @@ __global__ void emit_kernel(const float* src, int64_t lds, int transposed, T* ds
 }
 
 struct FactorWs {
-  size_t off_z, off_zt, off_om, off_xa, off_xb, off_xt, off_s, off_c, off_red, total;
+  size_t off_z, off_zt, off_om, off_xa, off_xb, off_xt, off_s, off_sp, off_c, off_red, total;
   int m4, r4;
+  int s_split;   // split of the reduction of the Gram product X X^T (r x r, few tiles, long K)
 };
 
 FactorWs make_factor_ws(const ffsplit_desc_t& d) {
@@ -140,6 +141,18 @@ FactorWs make_factor_ws(const ffsplit_desc_t& d) {
   w.off_xb = off; off = align256(off + (size_t)w.r4 * dm * 4);
   w.off_xt = off; off = align256(off + (size_t)w.r4 * dm * 4);
   w.off_s = off; off = align256(off + (size_t)w.r4 * w.r4 * 4);
+  // The Gram product has (r / 64)^2 tiles of 64 x 64 and K = d_model: split it so that a few
+  // hundred workgroups exist, at least 16 slabs of 16 each (the partial sums need whole
+  // 8-column chunks).
+  {
+    const int tiles = ((w.r4 + 63) / 64) * ((w.r4 + 63) / 64);
+    int sp = 512 / (tiles > 0 ? tiles : 1);
+    if (sp > (int)dm / 256) sp = (int)dm / 256;
+    if (sp > 16) sp = 16;
+    if (sp < 1 || (w.r4 & 7)) sp = 1;
+    w.s_split = sp;
+  }
+  w.off_sp = off; if (w.s_split > 1) off = align256(off + (size_t)w.s_split * w.r4 * w.r4 * 4);
   w.off_c = off; off = align256(off + (size_t)w.r4 * w.m4 * 4);
   w.off_red = off; off = align256(off + 260 * 4);
   w.total = off;
@@ -176,6 +189,7 @@ int launch_factorize(const ffsplit_desc_t& d, const void* W1, const void* Wg, co
   float* Z = (float*)(ws + w.off_z); float* Zt = (float*)(ws + w.off_zt); float* Om = (float*)(ws + w.off_om);
   float* Xa = (float*)(ws + w.off_xa); float* Xb = (float*)(ws + w.off_xb); float* Xt = (float*)(ws + w.off_xt);
   float* S = (float*)(ws + w.off_s); float* C = (float*)(ws + w.off_c); float* red = (float*)(ws + w.off_red);
+  float* Sp = (float*)(ws + w.off_sp);
   const bool bf = d.dtype == FFSPLIT_BF16;
   // Steps of x <- 1.5 x - 0.5 x^3: a singular value far below 1 grows by 1.5 per step, then
   // converges quadratically (about ten more steps to fp32 accuracy).  Budget: singular values
@@ -205,7 +219,15 @@ int launch_factorize(const ffsplit_desc_t& d, const void* W1, const void* Wg, co
     FKL();
     float* X = Xa; float* Xn = Xb;
     for (int it = 0; it < n_iter; ++it) {
-      FK(gemm_nt(X, dm, X, dm, r4, r4, dm, S, r4, st));
+      if (w.s_split > 1) {
+        GemmArgs g = {};
+        g.A = X; g.lda = dm; g.Bt = X; g.ldb = dm; g.M = r4; g.N = r4; g.K = dm;
+        g.split_col = r4; g.C0 = Sp; g.ldc0 = r4; g.n_store = r4; g.partial = 1;
+        FK(launch_gemm_f32(g, ACT_NONE, false, st, w.s_split));
+        FK(launch_splitk_reduce(Sp, w.s_split, r4, r4, r4, S, r4, 0, st, 1));
+      } else {
+        FK(gemm_nt(X, dm, X, dm, r4, r4, dm, S, r4, st));
+      }
       hipLaunchKernelGGL(ns_update_kernel, dim3((unsigned)(((int64_t)r4 * r4 + 255) / 256)), dim3(256), 0, st, S, r4);
       hipLaunchKernelGGL(transpose_f32_kernel, dim3((r4 + 31) / 32, (dm + 31) / 32), dim3(32, 8), 0, st, X, (int64_t)dm, Xt,
                          (int64_t)r4, dm, r4);

@@ -360,6 +360,10 @@ FACT_CASES = [
     ("gelu_f32", f32_variant(reduced(C2, 96, 160, rank=16)), 1e-4),
     ("swiglu_f32_ragged", f32_variant(reduced(C3, 64, 203, rank=18)), 1e-4),
     ("gelu_f32_full_side", f32_variant(reduced(C2, 64, 200, rank=64)), 1e-4),
+    # d_model >= 512 and a rank that is a multiple of 8: the Gram product of the orthonormalisation
+    # is split along its reduction
+    ("gelu_f32_split_gram", f32_variant(reduced(C2, 512, 300, rank=24)), 1e-4),
+    ("swiglu_f32_split_gram", f32_variant(reduced(C3, 768, 260, rank=40)), 1e-4),
     ("swiglu_bf16", reduced(C3, 192, 700, rank=64), 6e-3),
     ("gelu_bf16", reduced(C2, 256, 1000, rank=100), 6e-3),
 ]
@@ -478,7 +482,7 @@ def test_calls_stay_inside_workspace_and_split(ff, act, dtype):
     """Score, select, build (every remainder kind), factorise: workspace and packed split of exactly
     the sizes the library reports, each between sentinel regions that must come back unchanged."""
     base = C3 if act == "swiglu" else C2
-    cfg = base.__class__(**{**base.__dict__, "name": "guard", "d_model": 256, "d_ff": 777, "k": 70, "rank": 40,
+    cfg = base.__class__(**{**base.__dict__, "name": "guard", "d_model": 512, "d_ff": 777, "k": 70, "rank": 40,
                             "rem_kind": "lowrank", "group": 128, "dtype": dtype})
     L = wl.make_layer(cfg)
     Ld = layer_to_dev(L, dtype)
