@@ -215,6 +215,12 @@ def test_forward_is_deterministic_and_T0_is_noop(ff):
     # small batch: the sum over the ranges of a reduction does not depend on arrival order
     small = [run_forward(ff, cfg, L, L["planted"], 7, "lowrank", fac)[0][0] for _ in range(4)]
     assert all(np.array_equal(small[0], s) for s in small[1:])
+    # a few hundred rows and long reductions: split products, partial sums added in a fixed order
+    cfg2 = reduced(C2, 1032, 1500, rank=520)
+    L2 = wl.make_layer(cfg2)
+    fac2 = wl.make_factors(cfg2, L2, L2["planted"])
+    mid = [run_forward(ff, cfg2, L2, L2["planted"], 200, "lowrank", fac2)[0][0] for _ in range(3)]
+    assert all(np.array_equal(mid[0], s) for s in mid[1:])
     desc = desc_for(ff, cfg, "lowrank")
     assert ff.lib.ffsplit_forward(__import__("ctypes").byref(desc), None, None, 0, None, None, None, None, 0, None) == 0
 
