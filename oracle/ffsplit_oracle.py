@@ -14,6 +14,8 @@ full-rank factors), Y = Y1 + Y2, the neuron-removal identity of Sec. 4.1 by
 brute force, exhaustive ranking for top-k, enumeration of the levels of the 3-,
 4- and 8-bit quantiser,
 closed-form identities of GeLU/SiLU, the parameter-count figure of Sec. 5.1.1;
+the biased layer and the residual against pure-Python loops, the unbiased case and
+a permutation of the neurons together with their biases;
 the randomised factorisation against exact recovery, the projector identities,
 Eckart-Young from below and the published expected-error bound from above.
 Forward outputs at the full workload shapes have no pin beyond those identities
@@ -303,6 +305,54 @@ def forward_split(X, W1, W2, Wg, idx, act, rem_kind, factors=None, group=128, bi
     else:
         raise ValueError(rem_kind)
     return Y1 + Y2, Y1, Y2
+
+
+# ---------------------------------------------------------------- biases and the residual connection
+
+def dense_ffn_biased(X, W1, W2, b1=None, b2=None):
+    """The feed-forward layer as the models of Sec. 5.1 / 5.2 (BERT, OPT) define it, biases
+    included: gelu(X U + b1) V + b2.  Sec. 2's first equation is the case b1 = b2 = 0."""
+    X = np.asarray(X, F64)
+    Z = X @ np.asarray(W1, F64)
+    if b1 is not None:
+        Z = Z + np.asarray(b1, F64)[None, :]
+    Y = gelu(Z) @ np.asarray(W2, F64)
+    if b2 is not None:
+        Y = Y + np.asarray(b2, F64)[None, :]
+    return Y
+
+
+def forward_split_biased(X, W1, W2, idx, rem_kind, factors=None, b1=None, b2=None, residual=None):
+    """Eq. 2 for a GeLU layer with biases and, optionally, the residual connection around it.
+    A neuron's bias belongs to the neuron (it is the constant term of its pre-activation), so
+    it moves with it in the partition: FFN_1 uses b1[h2]; the remainder, whose up projection is
+    compressed, adds b1[rest] to the compressed pre-activation: gelu((X P1) Q1 + b1[rest]).
+    b2 is not a neuron's: it is added once to the sum.  residual [T, d]: the layer's input
+    stream, Y = residual + FFN_1 + FFN_2 + b2 (Sec. 4.1 applies the split at each layer of a
+    model whose layers are wrapped this way).  Returns (Y, Y1, Y2), Y1 and Y2 without b2 and
+    without the residual."""
+    X = np.asarray(X, F64)
+    sw = split_weights(W1, W2, None, idx)
+    k = len(idx)
+    perm = sw["perm"]
+    b1 = np.zeros(np.asarray(W1).shape[1], F64) if b1 is None else np.asarray(b1, F64)
+    bh, br = b1[perm[:k]], b1[perm[k:]]
+    Y1 = gelu(X @ sw["W1h"] + bh[None, :]) @ sw["W2h"]
+    if rem_kind == "none" or sw["W1r"].shape[1] == 0:
+        Y2 = np.zeros_like(Y1)
+    elif rem_kind == "dense":
+        Y2 = gelu(X @ sw["W1r"] + br[None, :]) @ sw["W2r"]
+    elif rem_kind == "lowrank":
+        Z = (X @ np.asarray(factors["P1"], F64)) @ np.asarray(factors["Q1"], F64) + br[None, :]
+        Y2 = (gelu(Z) @ np.asarray(factors["P2"], F64)) @ np.asarray(factors["Q2"], F64)
+    else:
+        raise ValueError(rem_kind)
+    Y = Y1 + Y2
+    if b2 is not None:
+        Y = Y + np.asarray(b2, F64)[None, :]
+    if residual is not None:
+        Y = np.asarray(residual, F64) + Y
+    return Y, Y1, Y2
 
 
 # ---------------------------------------------------------------- remainder factorisation on the device's plan

@@ -27,3 +27,20 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Largest observed errors of the floating-point comparisons, next to their bars."""
+    try:
+        import gpu_util
+    except Exception:
+        return
+    for dt in ("bf16", "f32"):
+        obs = [o for o in gpu_util.OBSERVED if o[0] == dt]
+        if not obs:
+            continue
+        we = max(obs, key=lambda o: o[2])
+        wr = max(obs, key=lambda o: o[3])
+        terminalreporter.write_line(
+            f"[parity {dt}] {len(obs)} comparisons; worst rel-Frobenius {we[2]:.3e} ({we[1]}) bar {gpu_util.TOL[dt]:g}; "
+            f"worst row {wr[3]:.3e} ({wr[1]}) bar {gpu_util.ROW_TOL[dt]:g}")

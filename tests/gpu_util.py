@@ -4,6 +4,11 @@ import numpy as np
 import torch
 
 TOL = {"bf16": 1e-2, "f32": 1e-5}      # relative Frobenius error, from the benchmark spec
+# Per-row guard beside it: max over tokens of ||dY_t|| / ||Y_t||.  The Frobenius bar alone would let
+# a few garbage rows (or one bad column chunk of a few rows) through among thousands of good ones.
+# Bars: the observed per-row maximum is 1.2-1.6 x the whole-tensor figure (the per-row errors of
+# 2048..5120 roundings concentrate), so 2 x the Frobenius bar leaves the same margin.
+ROW_TOL = {"bf16": 2e-2, "f32": 2e-5}
 TDT = {"bf16": torch.bfloat16, "f32": torch.float32}
 
 
@@ -22,6 +27,63 @@ def relf(a, b):
     b = np.asarray(b, np.float64)
     den = np.linalg.norm(b)
     return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
+
+
+OBSERVED = []      # (dtype, what, rel-Frobenius, worst row) of every comparison, for the run's summary
+
+
+def row_err(a, b):
+    """max_t ||a_t - b_t|| / max(||b_t||, 0.5 * rms_t ||b_t||): the worst token.  The floor: a row
+    much smaller than the typical row is a cancellation among contributions of typical size (with
+    a single heavy neuron, a pre-activation near zero), and the rounding errors of those
+    contributions do not shrink with it (observed: 5 % of its own norm for a row at 9 % of the
+    rms norm, from bf16-rounded weights, every row exact to 0.5 % of the rms norm).  A garbage
+    row still scores about 1 or more."""
+    a = np.asarray(a, np.float64).reshape(len(a), -1)
+    b = np.asarray(b, np.float64).reshape(len(b), -1)
+    if a.shape[0] == 0:
+        return 0.0
+    nb = np.linalg.norm(b, axis=1)
+    floor = 0.5 * float(np.sqrt(np.mean(nb * nb)))
+    den = np.maximum(nb, floor)
+    num = np.linalg.norm(a - b, axis=1)
+    if not (den > 0).all():
+        return float(num.max())
+    return float((num / den).max())
+
+
+def assert_close(got, want, dtype, what=""):
+    """Both bars of a floating-point output: relative Frobenius error over the whole tensor and
+    the worst row."""
+    e, r = relf(got, want), row_err(got, want)
+    OBSERVED.append((dtype, what, e, r))
+    assert np.isfinite(np.asarray(got)).all(), (what, "non-finite output")
+    assert e < TOL[dtype], (what, "rel-Frobenius", e)
+    assert r < ROW_TOL[dtype], (what, "worst row", r)
+    return e, r
+
+
+def elem_err(a, b):
+    """max_j |a_j - b_j| / max(|b_j|, 1e-3 * max|b|): the worst entry of a score vector."""
+    a = np.asarray(a, np.float64).ravel()
+    b = np.asarray(b, np.float64).ravel()
+    if a.size == 0:
+        return 0.0
+    den = np.maximum(np.abs(b), 1e-3 * float(np.abs(b).max()))
+    if not (den > 0).all():
+        return float(np.abs(a - b).max())
+    return float((np.abs(a - b) / den).max())
+
+
+def assert_scores_close(got, want, dtype, what=""):
+    """Neuron scores: relative Frobenius error over the vector and the worst neuron (same bars
+    as for the outputs: a score is a sum over tokens of squares of the same activations)."""
+    e, r = relf(got, want), elem_err(got, want)
+    OBSERVED.append((dtype, "scores " + what, e, r))
+    assert np.isfinite(np.asarray(got)).all(), (what, "non-finite score")
+    assert e < TOL[dtype], (what, "rel-Frobenius", e)
+    assert r < ROW_TOL[dtype], (what, "worst neuron", r)
+    return e, r
 
 
 def desc_for(ff, cfg, rem_kind=None, k=None, rank=None):

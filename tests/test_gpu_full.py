@@ -1,8 +1,10 @@
 """Full-size runs of the five workloads in the launch configuration the benchmark
-times, checked on sampled outputs: rows of X are independent, so the oracle's
-result for a sample of rows is exactly what the full run must produce for them.
-Heavy sets are compared in full (bit-exact as sets, and the ranking kernel
-against the oracle's rule on the GPU's own scores)."""
+times.  Forward outputs are compared with the oracle on EVERY row (relative
+Frobenius error and the worst row); only the 65 536-token run and the scores of
+the large layers are checked on samples (rows of X and columns of W1 are
+independent, so the oracle's result for a sample is exactly what the full run
+must produce for it).  Heavy sets are compared in full (bit-exact as sets, and
+the ranking kernel against the oracle's rule on the GPU's own scores)."""
 import numpy as np
 import pytest
 import torch
@@ -10,7 +12,8 @@ import torch
 from oracle import ffsplit_oracle as orc
 import workloads as wl
 from workloads.configs import C1, C2, C3, C4, C5
-from gpu_util import guarded_forward, TOL, dev, host, relf, desc_for, layer_to_dev, gpu_scores
+from gpu_util import (guarded_forward, TOL, dev, host, relf, assert_close, assert_scores_close, desc_for, layer_to_dev,
+                      gpu_scores)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
@@ -50,7 +53,7 @@ def test_c1_bert_shape_fp32_full(ff):
     Xc, scores, idx, idx_h = calibrate_and_select(ff, cfg, L, Ld, n_batches=1)
     acc_o = orc.score_accumulate(orc.new_accumulator(cfg.d_ff), Xc, L["W1"], None, "gelu")
     want_s = orc.neuron_scores(acc_o, L["W2"])
-    assert relf(scores.cpu().numpy(), want_s) < TOL["f32"]
+    assert_scores_close(scores.cpu().numpy(), want_s, "f32", "C1")
     assert np.array_equal(np.sort(idx_h), np.sort(orc.select_heavy(want_s, cfg.k)))
     fac = wl.make_factors(cfg, L, idx_h)
     desc = desc_for(ff, cfg)
@@ -59,8 +62,8 @@ def test_c1_bert_shape_fp32_full(ff):
     Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "f32"), want_parts=True)
     torch.cuda.synchronize()
     want = orc.forward_split(X, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)
-    for g, w in zip((Y, Yh, Yr), want):
-        assert relf(host(g), w) < TOL["f32"]
+    for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
+        assert_close(host(g), w, "f32", f"C1 {nm}")
 
 
 def test_c2_opt13b_shape_full_pipeline(ff):
@@ -72,7 +75,7 @@ def test_c2_opt13b_shape_full_pipeline(ff):
     cols = np.concatenate([L["planted"][:16], np.random.default_rng(1).choice(cfg.d_ff, 48, replace=False)])
     acc_o = orc.score_accumulate(orc.new_accumulator(len(cols)), Xc, L["W1"][:, cols], None, "gelu")
     want_s = orc.neuron_scores(acc_o, L["W2"][cols, :])
-    assert relf(scores.cpu().numpy()[cols], want_s) < TOL["bf16"]
+    assert_scores_close(scores.cpu().numpy()[cols], want_s, "bf16", "C2 sampled neurons")
     fac = wl.make_factors(cfg, L, idx_h)
     desc = desc_for(ff, cfg)
     split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, {k: dev(v, "bf16") for k, v in fac.items()})
@@ -82,13 +85,9 @@ def test_c2_opt13b_shape_full_pipeline(ff):
     Y2 = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
     assert torch.equal(Y, Y2)                              # deterministic
-    rows = sampled_rows(T, 48)
-    want = orc.forward_split(X[rows], L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)
-    r = torch.from_numpy(rows).cuda()
+    want = orc.forward_split(X, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)      # all 4096 rows
     for g, w, nm in zip((Y, Yh, Yr), want, ("Y", "Y_heavy", "Y_rem")):
-        e = relf(host(g[r]), w)
-        assert e < TOL["bf16"], (nm, e)
-    assert torch.isfinite(Y.float()).all()
+        assert_close(host(g), w, "bf16", f"C2 T={T} {nm}")
 
 
 def test_c2_opt13b_shape_factorize_on_device(ff):
@@ -111,9 +110,8 @@ def test_c2_opt13b_shape_factorize_on_device(ff):
     X = wl.make_tokens(cfg, cfg.prefill_T)
     Y = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
-    rows = sampled_rows(cfg.prefill_T, 32)
-    ref = orc.forward_split(X[rows], L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", got)
-    assert relf(host(Y[torch.from_numpy(rows).cuda()]), ref[0]) < TOL["bf16"]
+    ref = orc.forward_split(X, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", got)
+    assert_close(host(Y), ref[0], "bf16", "C2 device factors, all rows")
 
 
 def test_c2_opt13b_shape_65536_tokens(ff):
@@ -139,7 +137,7 @@ def test_c2_opt13b_shape_65536_tokens(ff):
     Y4 = guarded_forward(ff, desc, split, Xd[:4096].contiguous())
     torch.cuda.synchronize()
     ref = orc.forward_split(Xr, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
-    assert relf(host(Y[torch.from_numpy(rows).cuda()]), ref) < TOL["bf16"]
+    assert_close(host(Y[torch.from_numpy(rows).cuda()]), ref, "bf16", "C2 T=65536 sampled rows")
     keep = np.setdiff1d(np.arange(4096), rows)
     # (tile shapes and the split of the long reduction depend on T, so the sums are ordered
     # differently: equal up to the rounding of the bf16 intermediates, not bit for bit)
@@ -154,6 +152,11 @@ def test_c3_llama7b_shape_prefill_and_decode(ff):
     L = wl.make_layer(cfg)
     Ld = layer_to_dev(L, cfg.dtype)
     Xc, scores, idx, idx_h = calibrate_and_select(ff, cfg, L, Ld, n_batches=2)
+    # scores against the oracle on a sample of neurons (columns are independent), all 8192 tokens
+    cols = np.concatenate([L["planted"][:16], np.random.default_rng(3).choice(cfg.d_ff, 48, replace=False)])
+    acc_o = orc.score_accumulate(orc.new_accumulator(len(cols)), Xc, L["W1"][:, cols], L["Wg"][:, cols], "swiglu")
+    assert_scores_close(scores.cpu().numpy()[cols], orc.neuron_scores(acc_o, L["W2"][cols, :]), "bf16",
+                        "C3 sampled neurons")
     del Xc
     fac = wl.make_factors(cfg, L, idx_h)
     desc = desc_for(ff, cfg)
@@ -162,19 +165,23 @@ def test_c3_llama7b_shape_prefill_and_decode(ff):
     torch.cuda.empty_cache()
     T = cfg.prefill_T
     X = wl.make_tokens(cfg, T)
-    Y = guarded_forward(ff, desc, split, dev(X, "bf16"))
+    Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "bf16"), want_parts=True)
     torch.cuda.synchronize()
-    rows = sampled_rows(T, 24)
-    want = orc.forward_split(X[rows], L["W1"], L["W2"], L["Wg"], idx_h, "swiglu", "lowrank", fac)[0]
-    e = relf(host(Y[torch.from_numpy(rows).cuda()]), want)
-    assert e < TOL["bf16"], e
+    sw = {"W1h": L["W1"][:, idx_h].astype(np.float64), "Wgh": L["Wg"][:, idx_h].astype(np.float64),
+          "W2h": L["W2"][idx_h, :].astype(np.float64)}
+
+    def want_for(Xh):      # the two halves of Eq. 2 from the oracle (forward_split would also gather the unused dense rest)
+        Y1 = orc.forward_heavy(Xh, sw, "swiglu")
+        Y2 = orc.forward_remainder_lowrank(Xh, fac, "swiglu")
+        return Y1 + Y2, Y1, Y2
+
+    for g, w, nm in zip((Y, Yh, Yr), want_for(X), ("Y", "Y_heavy", "Y_rem")):               # all 4096 rows
+        assert_close(host(g), w, "bf16", f"C3 T={T} {nm}")
     for B in cfg.decode_B:
         Xb = wl.make_tokens(cfg, B, wl.gen.S_EVAL, layer=B)
         Yb = guarded_forward(ff, desc, split, dev(Xb, "bf16"))
         torch.cuda.synchronize()
-        wb = orc.forward_split(Xb, L["W1"], L["W2"], L["Wg"], idx_h, "swiglu", "lowrank", fac)[0]
-        e = relf(host(Yb), wb)
-        assert e < TOL["bf16"], (B, e)
+        assert_close(host(Yb), want_for(Xb)[0], "bf16", f"C3 decode B={B}")
 
 
 def test_c4_llama7b_shape_int4_decode(ff):
@@ -198,12 +205,11 @@ def test_c4_llama7b_shape_int4_decode(ff):
         Y1 = orc.forward_heavy(Xb, sw, "swiglu")
         Y2 = orc.forward_remainder_int4(Xb, qw, cfg.group, "swiglu")
         for g, w, nm in zip((Yb, Yh, Yr), (Y1 + Y2, Y1, Y2), ("Y", "Y_heavy", "Y_rem")):
-            e = relf(host(g), w)
-            assert e < TOL["bf16"], (B, nm, e)
+            assert_close(host(g), w, "bf16", f"C4 int4 decode B={B} {nm}")
 
 
 def test_c4_llama7b_shape_int4_many_tokens(ff):
-    """4096 tokens through the int4 split (weights expanded to bf16, dense chain), sampled rows."""
+    """4096 tokens through the int4 split (weights expanded to bf16, dense chain), all rows."""
     cfg = C4
     L = wl.make_layer(cfg)
     Ld = layer_to_dev(L, cfg.dtype)
@@ -215,14 +221,12 @@ def test_c4_llama7b_shape_int4_many_tokens(ff):
     X = wl.make_tokens(cfg, T)
     Y, Yh, Yr = guarded_forward(ff, desc, split, dev(X, "bf16"), want_parts=True)
     torch.cuda.synchronize()
-    rows = sampled_rows(T, 24)
     sw = orc.split_weights(L["W1"], L["W2"], L["Wg"], idx_h)
     qw = orc.quantize_remainder(sw, cfg.group)
-    Y1 = orc.forward_heavy(X[rows], sw, "swiglu")
-    Y2 = orc.forward_remainder_int4(X[rows], qw, cfg.group, "swiglu")
+    Y1 = orc.forward_heavy(X, sw, "swiglu")
+    Y2 = orc.forward_remainder_int4(X, qw, cfg.group, "swiglu")
     for g, w, nm in zip((Y, Yh, Yr), (Y1 + Y2, Y1, Y2), ("Y", "Y_heavy", "Y_rem")):
-        e = relf(host(g[torch.from_numpy(rows).cuda()]), w)
-        assert e < TOL["bf16"], (nm, e)
+        assert_close(host(g), w, "bf16", f"C4 int4 T={T} {nm}")
 
 
 def test_c4_llama7b_shape_w3h8(ff):
@@ -254,13 +258,12 @@ def test_c4_llama7b_shape_w3h8(ff):
         got = guarded_forward(ff, desc, split, dev(Xb, "bf16"), want_parts=True)
         torch.cuda.synchronize()
         for g, w, nm in zip(got, want(Xb), ("Y", "Y_heavy", "Y_rem")):
-            assert relf(host(g), w) < TOL["bf16"], (B, nm, relf(host(g), w))
+            assert_close(host(g), w, "bf16", f"C4 w3h8 B={B} {nm}")
     T = 4096
     X = wl.make_tokens(cfg, T)
     Y = guarded_forward(ff, desc, split, dev(X, "bf16"))
     torch.cuda.synchronize()
-    rows = sampled_rows(T, 24)
-    assert relf(host(Y[torch.from_numpy(rows).cuda()]), want(X[rows])[0]) < TOL["bf16"]
+    assert_close(host(Y), want(X)[0], "bf16", f"C4 w3h8 T={T}, all rows")
 
 
 def test_c5_opt13b_shape_layers_teacher_forced(ff):

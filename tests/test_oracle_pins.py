@@ -476,6 +476,52 @@ def test_stack_layers_propagate_residual():
     assert np.allclose(x2, x1, rtol=1e-12)
 
 
+# ----------------------------------------------------------------- biases and the residual connection
+
+def test_biased_layer_matches_pure_python_loops_and_follows_its_neurons():
+    rng = np.random.default_rng(5)
+    T, d, f = 4, 6, 10
+    X, W1, W2 = rng.standard_normal((T, d)), rng.standard_normal((d, f)), rng.standard_normal((f, d))
+    b1, b2, res = rng.standard_normal(f), rng.standard_normal(d), rng.standard_normal((T, d))
+    want = [[b2[c] + sum(py_gelu(sum(X[t][i] * W1[i][j] for i in range(d)) + b1[j]) * W2[j][c] for j in range(f))
+             for c in range(d)] for t in range(T)]
+    dense = orc.dense_ffn_biased(X, W1, W2, b1, b2)
+    assert np.allclose(dense, want, rtol=1e-12, atol=1e-12)
+    # no bias: Sec. 2's first equation
+    assert np.array_equal(orc.dense_ffn_biased(X, W1, W2), orc.dense_ffn(X, W1, W2))
+    # heavy = everything, in any order, and a dense remainder: the biased dense layer; the parts
+    # carry neither b2 nor the residual and add up
+    for idx, kind in ((np.arange(f)[::-1].copy(), "none"), (np.array([7, 2, 3]), "dense")):
+        Y, Y1, Y2 = orc.forward_split_biased(X, W1, W2, idx, kind, None, b1, b2, res)
+        assert np.allclose(Y, res + dense, rtol=1e-12, atol=1e-12)
+        assert np.allclose(Y1 + Y2 + b2[None, :] + res, Y, rtol=1e-12, atol=1e-12)
+    # a neuron's bias moves with the neuron: permuting columns of W1, rows of W2 and b1 together
+    # changes nothing; permuting the weights alone does
+    p = rng.permutation(f)
+    assert np.allclose(orc.dense_ffn_biased(X, W1[:, p], W2[p, :], b1[p], b2), dense, rtol=1e-12)
+    assert not np.allclose(orc.dense_ffn_biased(X, W1[:, p], W2[p, :], b1, b2), dense, rtol=1e-3)
+    # low-rank remainder: the remainder's biases (ascending order of the rest) enter the compressed
+    # pre-activation; entry by entry with hand-made factors
+    idx = np.array([8, 1])
+    rest = np.array([0, 2, 3, 4, 5, 6, 7, 9])
+    r = 3
+    fac = {"P1": rng.standard_normal((d, r)), "Q1": rng.standard_normal((r, 8)),
+           "P2": rng.standard_normal((8, r)), "Q2": rng.standard_normal((r, d))}
+    Y, Y1, Y2 = orc.forward_split_biased(X, W1, W2, idx, "lowrank", fac, b1, b2, None)
+    for t in range(T):
+        h = [py_gelu(sum(sum(X[t][i] * fac["P1"][i][a] for i in range(d)) * fac["Q1"][a][n] for a in range(r))
+                     + b1[rest[n]]) for n in range(8)]
+        for c in range(d):
+            y2 = sum(sum(h[n] * fac["P2"][n][a] for n in range(8)) * fac["Q2"][a][c] for a in range(r))
+            y1 = sum(py_gelu(sum(X[t][i] * W1[i][j] for i in range(d)) + b1[j]) * W2[j][c] for j in idx)
+            assert Y2[t, c] == pytest.approx(y2, rel=1e-10, abs=1e-12)
+            assert Y[t, c] == pytest.approx(y1 + y2 + b2[c], rel=1e-10, abs=1e-12)
+    # zero biases, no residual: the unbiased split
+    Y0 = orc.forward_split_biased(X, W1, W2, idx, "lowrank", fac)
+    Yu = orc.forward_split(X, W1, W2, None, idx, "gelu", "lowrank", fac)
+    assert all(np.allclose(a, b, rtol=1e-13, atol=1e-13) for a, b in zip(Y0, Yu))
+
+
 # ----------------------------------------------------------------- the paper's printed figure
 
 def test_parameter_reduction_matches_printed_43_1_percent():

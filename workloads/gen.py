@@ -23,24 +23,42 @@ def _rng(seed: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=seed))
 
 
-def bf16_round(a) -> np.ndarray:
-    """fp32 -> nearest bf16 (ties to even) -> fp32.  NaN/Inf pass through."""
-    a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32)
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    r = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
-    fin = np.isfinite(a)
-    out = np.where(fin, r, u).astype(np.uint32)
-    return out.view(np.float32).reshape(a.shape)
+def bf16_round(a, inplace: bool = False) -> np.ndarray:
+    """fp32 -> nearest bf16 (ties to even) -> fp32.  NaN/Inf pass through.
+    Works through the array in blocks with small scratch buffers (the matrices of the large
+    layers hold 10^8 entries, and fresh pages are the expensive part); inplace=True overwrites
+    a contiguous fp32 array instead of returning a copy."""
+    src = np.ascontiguousarray(a, dtype=np.float32)
+    dst = src if (inplace and src is a) else np.empty_like(src)
+    u = src.reshape(-1).view(np.uint32)
+    o = dst.reshape(-1).view(np.uint32)
+    blk = 1 << 20
+    r = np.empty(blk, np.uint32)
+    e = np.empty(blk, np.uint32)
+    for lo in range(0, u.size, blk):
+        ub = u[lo:lo + blk]
+        n = ub.size
+        rb, eb = r[:n], e[:n]
+        np.right_shift(ub, np.uint32(16), out=rb)
+        rb &= np.uint32(1)
+        rb += np.uint32(0x7FFF)
+        rb += ub
+        rb &= np.uint32(0xFFFF0000)
+        np.bitwise_and(ub, np.uint32(0x7F800000), out=eb)
+        nonfinite = eb == np.uint32(0x7F800000)
+        if nonfinite.any():
+            rb[nonfinite] = ub[nonfinite]
+        o[lo:lo + n] = rb
+    return dst.reshape(src.shape)
 
 
 def fp16_round(a) -> np.ndarray:
     return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
 
 
-def storage_round(a, dtype: str) -> np.ndarray:
+def storage_round(a, dtype: str, inplace: bool = False) -> np.ndarray:
     if dtype == "bf16":
-        return bf16_round(a)
+        return bf16_round(a, inplace)
     if dtype == "f16":
         return fp16_round(a)
     return np.ascontiguousarray(a, dtype=np.float32)
@@ -63,12 +81,13 @@ def make_layer(cfg: FFNConfig, layer: int = 0) -> dict:
     names = ["W1", "W2"] + (["Wg"] if cfg.act == "swiglu" else [])
     for nm in names:
         shape = (f, d) if nm == "W2" else (d, f)
-        w = rng.standard_normal(shape, dtype=np.float32) * np.float32(cfg.weight_std)
+        w = rng.standard_normal(shape, dtype=np.float32)
+        w *= np.float32(cfg.weight_std)
         if nm == "W2":
             w[planted, :] *= np.float32(cfg.heavy_scale)
         else:
             w[:, planted] *= np.float32(cfg.heavy_scale)
-        out[nm] = storage_round(w, cfg.dtype)
+        out[nm] = storage_round(w, cfg.dtype, inplace=True)
     if "Wg" not in out:
         out["Wg"] = None
     return out
@@ -78,7 +97,7 @@ def make_tokens(cfg: FFNConfig, T: int, stream: int = S_EVAL, layer: int = 0) ->
     """T tokens x ~ N(0, 1) of width d_model, rounded to the storage dtype."""
     rng = _rng(seed_for(cfg, stream, layer) + 100000)
     x = rng.standard_normal((T, cfg.d_model), dtype=np.float32)
-    return storage_round(x, cfg.dtype)
+    return storage_round(x, cfg.dtype, inplace=True)
 
 
 def remainder_order(idx, d_ff: int) -> np.ndarray:
@@ -112,8 +131,10 @@ def truncated_factors(W: np.ndarray, r: int):
 def gaussian_factors(p: int, q: int, r: int, std: float, rng: np.random.Generator):
     """Stand-in factors of the right shape whose product has entries of std `std`."""
     a = np.sqrt(std / np.sqrt(r))
-    P = rng.standard_normal((p, r), dtype=np.float32) * np.float32(a)
-    Q = rng.standard_normal((r, q), dtype=np.float32) * np.float32(a)
+    P = rng.standard_normal((p, r), dtype=np.float32)
+    P *= np.float32(a)
+    Q = rng.standard_normal((r, q), dtype=np.float32)
+    Q *= np.float32(a)
     return P, Q
 
 
