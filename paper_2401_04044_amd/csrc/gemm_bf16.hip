@@ -24,6 +24,7 @@
 // with two output destinations, fp32 split-K partials, and the neuron-norm
 // column reduction of Sec. 4.1 (Eq. 3) for the calibration pass.
 #include "common.h"
+#include <atomic>
 #include <type_traits>
 
 namespace ffsplit {
@@ -659,11 +660,17 @@ static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
   constexpr size_t lds = ring > park ? ring : park;
   static_assert(lds <= 160 * 1024, "LDS budget of a CU");
   auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, KG, STAGES, ACT, DUAL, SCORE, A_TILED>;
-  static bool configured = false;
-  if (!configured) {
+  // The kernel needs more dynamic LDS than the default limit: the attribute is set once per
+  // device and instantiation.  The only state kept is this set-once bit mask (one bit per
+  // device ordinal); setting the attribute twice from racing first calls is harmless.
+  static std::atomic<uint64_t> configured{0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -1;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev >= 64 || !(configured.load(std::memory_order_acquire) & bit)) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return -1;
-    configured = true;
+    if (dev < 64) configured.fetch_or(bit, std::memory_order_release);
   }
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * KG * 64), lds, st, a);
