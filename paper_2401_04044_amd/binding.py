@@ -118,7 +118,7 @@ def select_heavy(scores, k, want_perm=False, workspace=None):
     idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)[:k]
     perm = torch.empty(d_ff, dtype=torch.int32, device=dev) if want_perm else None
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
-    ws = _ws(12 * d_ff + 256, workspace, dev)
+    ws = _ws(int(lib.ffsplit_workspace_bytes(ctypes.byref(make_desc(8, d_ff)), WS_SELECT, 0)), workspace, dev)
     rc = lib.ffsplit_select_heavy(_ptr(scores), d_ff, k, _ptr(idx) if k > 0 else None, _ptr(perm), _ptr(flag),
                                   _ptr(ws), ws.numel(), _stream())
     _check(rc, "ffsplit_select_heavy")
