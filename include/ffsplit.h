@@ -69,7 +69,8 @@ enum { FFSPLIT_OK = 0,
        FFSPLIT_E_WORKSPACE = -5,   /* workspace missing or too small                      */
        FFSPLIT_E_UNSUPPORTED = -6, /* valid but not implemented combination               */
        FFSPLIT_E_NONFINITE = -7,   /* reported through select_heavy's device flag only    */
-       FFSPLIT_E_HIP = -8          /* a HIP runtime call failed                           */ };
+       FFSPLIT_E_HIP = -8,         /* a HIP runtime call failed                           */
+       FFSPLIT_E_TOO_LARGE = -9    /* beyond the fixed scratch of a *_static entry point  */ };
 
 /* Plain data, passed by pointer, never retained. */
 typedef struct {
@@ -125,6 +126,25 @@ int ffsplit_score_neurons(const ffsplit_desc_t* desc, const void* X, int64_t T,
 int ffsplit_select_heavy(const float* scores, int32_t d_ff, int32_t k,
                          int32_t* idx, int32_t* perm, int32_t* nan_flag,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ffsplit_select_heavy for callers that cannot allocate or size a workspace:
+ * code under HIP graph capture, tight serving loops that re-select per request,
+ * harnesses that forbid hipMalloc.  Same results, same argument meaning; the
+ * scratch is a fixed array inside the library (FFSPLIT_SELECT_STATIC_MAX_DFF * 12
+ * + 256 bytes of device memory per GPU, held until the process ends), so
+ *   - d_ff > FFSPLIT_SELECT_STATIC_MAX_DFF returns FFSPLIT_E_TOO_LARGE (nothing
+ *     is launched);
+ *   - the call allocates nothing and frees nothing (the first call on a device
+ *     looks the array's address up once, with that device current);
+ *   - every call on one GPU uses the same array: calls that overlap in time on
+ *     one GPU (two streams, two threads) race.  Calls on one stream are safe.
+ * Nothing in the array has to be cleared between calls.
+ */
+#define FFSPLIT_SELECT_STATIC_MAX_DFF 65536
+int ffsplit_select_heavy_static(const float* scores, int32_t d_ff, int32_t k,
+                                int32_t* idx, int32_t* perm, int32_t* nan_flag,
+                                void* stream);
 
 /*
  * Split construction (Eq. 2; Fig. 3: U1 = U[:,h2], V1 = V[h2,:], U2, V2 the

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE,
     Desc, FFSplitError, lib, lib_path, status_string, make_desc,
     workspace_bytes, split_bytes, score_neurons, select_heavy, build_split, forward, split_export,
-    factorize_remainder,
+    factorize_remainder, select_heavy_static, SELECT_STATIC_MAX_DFF,
 )

@@ -47,6 +47,8 @@ def _load():
     L.ffsplit_score_neurons.argtypes = [dp, vp, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp, i32, vp, sz, vp]
     L.ffsplit_select_heavy.restype = ctypes.c_int
     L.ffsplit_select_heavy.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.ffsplit_select_heavy_static.restype = ctypes.c_int
+    L.ffsplit_select_heavy_static.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     L.ffsplit_build_split.restype = ctypes.c_int
     L.ffsplit_build_split.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
     L.ffsplit_forward.restype = ctypes.c_int
@@ -123,6 +125,16 @@ def select_heavy(scores, k, want_perm=False, workspace=None):
                                   _ptr(ws), ws.numel(), _stream())
     _check(rc, "ffsplit_select_heavy")
     return idx, perm, flag
+
+
+SELECT_STATIC_MAX_DFF = 65536
+
+
+def select_heavy_static(scores, k, idx, perm=None, flag=None):
+    """ffsplit_select_heavy_static: every buffer is the caller's, nothing is allocated here."""
+    rc = lib.ffsplit_select_heavy_static(_ptr(scores), scores.numel(), k, _ptr(idx) if k > 0 else None, _ptr(perm),
+                                         _ptr(flag), _stream())
+    _check(rc, "ffsplit_select_heavy_static")
 
 
 def build_split(desc, W1, Wg, W2, idx, factors=None, split=None, workspace=None):

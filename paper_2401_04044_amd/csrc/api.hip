@@ -178,6 +178,7 @@ const char* ffsplit_status_string(int s) {
     case FFSPLIT_E_UNSUPPORTED: return "combination not supported";
     case FFSPLIT_E_NONFINITE: return "NaN among the scores";
     case FFSPLIT_E_HIP: return "HIP runtime error";
+    case FFSPLIT_E_TOO_LARGE: return "size beyond the fixed scratch of the entry point that allocates nothing";
     default: return "unknown status";
   }
 }
@@ -275,6 +276,17 @@ int ffsplit_select_heavy(const float* scores, int32_t d_ff, int32_t k, int32_t* 
   if (!workspace || workspace_bytes < select_workspace_bytes(d_ff)) return FFSPLIT_E_WORKSPACE;
   if (misaligned(scores) || misaligned(workspace)) return FFSPLIT_E_ALIGN;
   FFS_TRY(launch_select(scores, d_ff, k, idx, perm, nan_flag, workspace, (hipStream_t)stream));
+  return FFSPLIT_OK;
+}
+
+int ffsplit_select_heavy_static(const float* scores, int32_t d_ff, int32_t k, int32_t* idx, int32_t* perm,
+                                int32_t* nan_flag, void* stream) {
+  if (d_ff <= 0) return FFSPLIT_E_BADDESC;
+  if (k < 0 || k > d_ff) return FFSPLIT_E_BADSHAPE;
+  if (d_ff > select_static_max_dff()) return FFSPLIT_E_TOO_LARGE;
+  if (!scores || (k > 0 && !idx)) return FFSPLIT_E_NULLPTR;
+  if (misaligned(scores)) return FFSPLIT_E_ALIGN;
+  FFS_TRY(launch_select_static(scores, d_ff, k, idx, perm, nan_flag, (hipStream_t)stream));
   return FFSPLIT_OK;
 }
 

@@ -36,5 +36,9 @@ int launch_finalize_scores(const void* W2, int bf16, int d_model, int d_ff, cons
 size_t select_workspace_bytes(int d_ff);
 int launch_select(const float* scores, int d_ff, int k, int32_t* idx, int32_t* perm, int32_t* nan_flag,
                   void* ws, hipStream_t st);
+// the same on the library's own static device scratch (d_ff <= select_static_max_dff())
+int select_static_max_dff();
+int launch_select_static(const float* scores, int d_ff, int k, int32_t* idx, int32_t* perm, int32_t* nan_flag,
+                         hipStream_t st);
 
 }  // namespace ffsplit

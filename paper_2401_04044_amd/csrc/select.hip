@@ -5,8 +5,16 @@
 // compacted in index order (equal keys: lowest indices first) and finally ranked
 // by counting, which yields the order (score descending, index ascending).
 #include "prep.h"
+#include <atomic>
 
 namespace ffsplit {
+
+// Scratch of the entry point that allocates nothing (ffsplit_select_heavy_static): one copy per
+// GPU the library runs on, held until the process ends.  In host code this name is only a
+// stand-in for the symbol; the device address comes from hipGetSymbolAddress (below).
+constexpr int SELECT_STATIC_MAX_DFF = 65536;
+constexpr size_t SELECT_STATIC_BYTES = (size_t)12 * SELECT_STATIC_MAX_DFF + 256;
+static __device__ __align__(256) unsigned char scratch[SELECT_STATIC_BYTES];
 
 __device__ __forceinline__ uint32_t score_key(float s, int* saw_nan) {
   uint32_t b = __float_as_uint(s);
@@ -167,6 +175,32 @@ int launch_select(const float* scores, int d_ff, int k, int32_t* idx, int32_t* p
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;
+}
+
+int select_static_max_dff() { return SELECT_STATIC_MAX_DFF; }
+
+// Device address of this GPU's copy of `scratch`, looked up once per device (with that device
+// current) and kept; nullptr on failure.  Racing first calls both look it up and store the same
+// value.
+static void* select_static_scratch() {
+  static std::atomic<void*> ptr[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) return nullptr;
+  void* p = dev < 64 ? ptr[dev].load(std::memory_order_acquire) : nullptr;
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    if (dev < 64) ptr[dev].store(p, std::memory_order_release);
+  }
+  return p;
+}
+
+int launch_select_static(const float* scores, int d_ff, int k, int32_t* idx, int32_t* perm, int32_t* nan_flag,
+                         hipStream_t st) {
+  void* ws = select_static_scratch();
+  if (!ws) return -1;
+  // nothing in the scratch has to start at zero: every key, candidate key and candidate index
+  // that a launch reads was written earlier in the same call
+  return launch_select(scores, d_ff, k, idx, perm, nan_flag, ws, st);
 }
 
 }  // namespace ffsplit

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings_and_sizes():
     import paper_2401_04044_amd as ff
     assert ff.status_string(0) == "ok"
-    for c in range(-8, 0):
+    for c in range(-9, 0):
         assert ff.status_string(c) != "unknown status"
     d = ff.make_desc(2048, 8192, "gelu", "bf16", 246, "lowrank", 512)
     sb = ff.split_bytes(d)
@@ -68,6 +68,11 @@ def test_argument_errors_are_found_on_the_host():
         assert L.ffsplit_forward(ref(bad), fake, fake, 4, fake, None, None, fake, 1 << 30, None) == -3
     assert L.ffsplit_forward(ref(good), fake, fake, -1, fake, None, None, fake, 1 << 30, None) == -3
     assert L.ffsplit_select_heavy(fake, 100, 101, fake, None, None, fake, 1 << 20, None) == -3
+    # the entry point without a workspace: beyond its fixed scratch, and the usual argument checks
+    assert L.ffsplit_select_heavy_static(fake, 65537, 5, fake, None, None, None) == -9
+    assert L.ffsplit_select_heavy_static(fake, 100, 101, fake, None, None, None) == -3
+    assert L.ffsplit_select_heavy_static(None, 100, 10, fake, None, None, None) == -1
+    assert L.ffsplit_select_heavy_static(odd, 100, 10, fake, None, None, None) == -4
     # int4 needs bf16
     bad = ff.make_desc(256, 1024, "swiglu", "f32", 16, "int4", 0, 128)
     assert L.ffsplit_forward(ref(bad), fake, fake, 4, fake, None, None, fake, 1 << 30, None) == -6
