@@ -57,8 +57,14 @@ enum { FFSPLIT_REM_NONE = 0,      /* FFN_2 dropped                              
 enum { FFSPLIT_SCORE_SUMSQ = 0,   /* Eq. 3: ||sigma(X U[:,j])||_F^2 * ||V[j,:]||_F^2      */
        FFSPLIT_SCORE_MEAN_L2 = 1, /* mean_t ||sigma(x_t U[:,j]) V[j,:]||_2                */
        FFSPLIT_SCORE_ACT_ONLY = 2 /* ||sigma(X U[:,j])||_F^2 (Sec. 2's heavy-hitter norm) */ };
+/* Flag, or-ed into score_kind: this batch continues a calibration run on the same desc, the
+ * same W1 / Wg and the same workspace as the previous ffsplit_score_neurons call, whose
+ * re-tiled copy of the up projection (the first bytes of the workspace, independent of T as
+ * long as the workspace was sized for the largest batch) is reused instead of being rebuilt.
+ * The caller must not have used the workspace for anything else in between.            */
+#define FFSPLIT_SCORE_REUSE_TILED 0x100
 enum { FFSPLIT_WS_SCORE = 0, FFSPLIT_WS_SELECT = 1, FFSPLIT_WS_BUILD = 2, FFSPLIT_WS_FORWARD = 3,
-       FFSPLIT_WS_FACTORIZE = 4 };
+       FFSPLIT_WS_FACTORIZE = 4, FFSPLIT_WS_STACK = 5 };
 
 enum { FFSPLIT_OK = 0,
        FFSPLIT_E_NULLPTR = -1,     /* a required pointer is NULL                          */
@@ -219,6 +225,74 @@ int ffsplit_factorize_remainder(const ffsplit_desc_t* desc, const void* W1, cons
 int ffsplit_forward(const ffsplit_desc_t* desc, const void* split, const void* X, int64_t T,
                     void* Y, void* Y_heavy, void* Y_rem,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The layer as the models of Sec. 5.1 / 5.2 wrap it: biases and the residual
+ * connection around the split feed-forward layer, fused into the products'
+ * store steps (Sec. 2's first equation omits the biases that BERT and OPT have;
+ * Sec. 4.1 applies the split "at each layer" of such a model).
+ *   Y = [residual +] FFN_1(X) + FFN_2~(X) [+ b2],
+ *   FFN_1 = gelu(X W1[:,h2] + b1[h2]) W2[h2,:], and the remainder's biases enter
+ *   its compressed pre-activation: gelu((X P1) Q1 + b1[rest]) P2 Q2.
+ * A neuron's bias belongs to the neuron and moves with it in Eq. 2's partition;
+ * b2 is added once.  Every field may be NULL / 0:
+ *   b1_packed  fp32 [ffsplit_neuron_bias_floats(desc)], from ffsplit_pack_neuron_bias.
+ *              GELU with NONE / DENSE / LOWRANK only (else FFSPLIT_E_UNSUPPORTED).
+ *   b2         fp32 [d_model].
+ *   residual   fp32 [T, d_model]; may be the same buffer as Y when y_f32 is set
+ *              (every element is read, then written, by one thread).
+ *   y_f32      Y is float [T, d_model] instead of desc->dtype (the fp32 residual
+ *              stream of a layer stack).  Y_heavy / Y_rem stay in desc->dtype and
+ *              carry neither b2 nor the residual.
+ * A layer with no neuron at all (k = 0 and no remainder) cannot carry an
+ * epilogue: FFSPLIT_E_UNSUPPORTED.
+ */
+typedef struct {
+  const float* b1_packed;
+  const float* b2;
+  const float* residual;
+  int32_t y_f32;
+} ffsplit_epilogue_t;
+
+int ffsplit_forward_ex(const ffsplit_desc_t* desc, const void* split, const void* X, int64_t T,
+                       void* Y, void* Y_heavy, void* Y_rem, const ffsplit_epilogue_t* epilogue,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Floats of a packed neuron-bias vector: round_up(k, 64) + round_up(d_ff - k, 64). */
+size_t ffsplit_neuron_bias_floats(const ffsplit_desc_t* desc);
+
+/*
+ * b1 [d_ff] (desc->dtype, original neuron order) -> b1_packed in the packed
+ * split's neuron order: b1[idx[0..k)], zeros up to round_up(k, 64), then b1 of
+ * the other neurons ascending, zeros up to the end.  idx as given to
+ * ffsplit_build_split.  workspace: ffsplit_workspace_bytes(desc, FFSPLIT_WS_BUILD, 0).
+ */
+int ffsplit_pack_neuron_bias(const ffsplit_desc_t* desc, const void* b1, const int32_t* idx,
+                             float* b1_packed, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-token RMS normalisation n(x) = x / sqrt(mean(x^2) + eps), no learned
+ * scale: the pre-norm of the layer stack below.  x fp32 [T, d_model];
+ * out [T, d_model] in `dtype` (FFSPLIT_F32 / FFSPLIT_BF16).  d_model % 8 == 0.
+ */
+int ffsplit_token_rmsnorm(const float* x, int64_t T, int32_t d_model, float eps, int32_t dtype,
+                          void* out, void* stream);
+
+/*
+ * A stack of n_layers split feed-forward layers of one shape on an fp32 residual
+ * stream (Sec. 4.1: the split is applied at each layer; the 40-layer workload):
+ *   for l in 0..n_layers:  x <- x + FFN_split_l(n(x)) [+ b2_l],
+ * n = ffsplit_token_rmsnorm in desc->dtype, the addition fused into the last
+ * product of each layer (ffsplit_forward_ex with residual = Y = x, y_f32 = 1).
+ * splits: HOST array of n_layers device pointers (packed splits of `desc`);
+ * b1_packed, b2: NULL or HOST arrays of n_layers device pointers (entries may
+ * be NULL).  x [T, d_model] fp32, in place.
+ * workspace: ffsplit_workspace_bytes(desc, FFSPLIT_WS_STACK, T).
+ */
+int ffsplit_stack_forward(const ffsplit_desc_t* desc, int32_t n_layers, const void* const* splits,
+                          const float* const* b1_packed, const float* const* b2,
+                          float* x, int64_t T, float eps,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Test hook: unpack the quantised weights of a built split (INT4, W3H8) into

@@ -7,9 +7,10 @@ There is no CPU fallback: a missing library raises at import of `binding`.
 """
 from .binding import (  # noqa: F401
     ACT_GELU, ACT_SWIGLU, F32, BF16, REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4, REM_W3H8,
-    SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY,
-    WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE,
+    SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY, SCORE_REUSE_TILED,
+    WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE, WS_STACK,
     Desc, FFSplitError, lib, lib_path, status_string, make_desc,
     workspace_bytes, split_bytes, score_neurons, select_heavy, build_split, forward, split_export,
     factorize_remainder, select_heavy_static, SELECT_STATIC_MAX_DFF,
+    forward_ex, pack_neuron_bias, token_rmsnorm, stack_forward, Epilogue,
 )

@@ -8,7 +8,8 @@ ACT_GELU, ACT_SWIGLU = 0, 1
 F32, BF16 = 0, 1
 REM_NONE, REM_DENSE, REM_LOWRANK, REM_INT4, REM_W3H8 = 0, 1, 2, 3, 4
 SCORE_SUMSQ, SCORE_MEAN_L2, SCORE_ACT_ONLY = 0, 1, 2
-WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE = 0, 1, 2, 3, 4
+SCORE_REUSE_TILED = 0x100
+WS_SCORE, WS_SELECT, WS_BUILD, WS_FORWARD, WS_FACTORIZE, WS_STACK = 0, 1, 2, 3, 4, 5
 E_NONFINITE = -7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -22,6 +23,11 @@ class FFSplitError(RuntimeError):
     def __init__(self, code, where):
         self.code = code
         super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+class Epilogue(ctypes.Structure):
+    _fields_ = [("b1_packed", ctypes.c_void_p), ("b2", ctypes.c_void_p), ("residual", ctypes.c_void_p),
+                ("y_f32", ctypes.c_int32)]
 
 
 class Desc(ctypes.Structure):
@@ -53,6 +59,17 @@ def _load():
     L.ffsplit_build_split.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
     L.ffsplit_forward.restype = ctypes.c_int
     L.ffsplit_forward.argtypes = [dp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.ffsplit_forward_ex.restype = ctypes.c_int
+    L.ffsplit_forward_ex.argtypes = [dp, vp, vp, i64, vp, vp, vp, ctypes.POINTER(Epilogue), vp, sz, vp]
+    L.ffsplit_neuron_bias_floats.restype = sz
+    L.ffsplit_neuron_bias_floats.argtypes = [dp]
+    L.ffsplit_pack_neuron_bias.restype = ctypes.c_int
+    L.ffsplit_pack_neuron_bias.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    L.ffsplit_token_rmsnorm.restype = ctypes.c_int
+    L.ffsplit_token_rmsnorm.argtypes = [vp, i64, i32, ctypes.c_float, i32, vp, vp]
+    L.ffsplit_stack_forward.restype = ctypes.c_int
+    L.ffsplit_stack_forward.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i64,
+                                        ctypes.c_float, vp, sz, vp]
     L.ffsplit_factorize_remainder.restype = ctypes.c_int
     L.ffsplit_factorize_remainder.argtypes = [dp, vp, vp, vp, vp, ctypes.c_uint32, ctypes.POINTER(vp), vp, sz, vp]
     L.ffsplit_split_export.restype = ctypes.c_int
@@ -191,6 +208,64 @@ def forward(desc, split, X, Y=None, want_parts=False, workspace=None):
                              ws.numel(), _stream())
     _check(rc, "ffsplit_forward")
     return (Y, Yh, Yr) if want_parts else Y
+
+
+def forward_ex(desc, split, X, Y=None, b1_packed=None, b2=None, residual=None, y_f32=False, want_parts=False,
+               workspace=None):
+    """ffsplit_forward_ex: Y = [residual +] FFN_split(X) [+ b2], neuron biases in packed order.
+    Returns Y, or (Y, Y_heavy, Y_rem) with want_parts."""
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, desc.d_model), dtype=torch.float32 if y_f32 else X.dtype, device=X.device)
+    Yh = torch.empty((T, desc.d_model), dtype=X.dtype, device=X.device) if want_parts else None
+    Yr = torch.empty((T, desc.d_model), dtype=X.dtype, device=X.device) if want_parts else None
+    ws = _ws(workspace_bytes(desc, WS_FORWARD, T), workspace, X.device)
+    e = Epilogue(None if b1_packed is None else b1_packed.data_ptr(), None if b2 is None else b2.data_ptr(),
+                 None if residual is None else residual.data_ptr(), 1 if y_f32 else 0)
+    rc = lib.ffsplit_forward_ex(ctypes.byref(desc), _ptr(split), _ptr(X), T, _ptr(Y), _ptr(Yh), _ptr(Yr),
+                                ctypes.byref(e), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_forward_ex")
+    return (Y, Yh, Yr) if want_parts else Y
+
+
+def pack_neuron_bias(desc, b1, idx, workspace=None):
+    """b1 [d_ff] in the layer's dtype -> fp32 vector in the packed split's neuron order."""
+    n = int(lib.ffsplit_neuron_bias_floats(ctypes.byref(desc)))
+    out = torch.empty(max(n, 1), dtype=torch.float32, device=b1.device)
+    ws = _ws(workspace_bytes(desc, WS_BUILD, 0), workspace, b1.device)
+    rc = lib.ffsplit_pack_neuron_bias(ctypes.byref(desc), _ptr(b1), _ptr(idx) if idx is not None and idx.numel() > 0
+                                      else None, _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_pack_neuron_bias")
+    return out
+
+
+def token_rmsnorm(x, dtype=BF16, eps=1e-6, out=None):
+    """n(x) = x / sqrt(mean(x^2) + eps) per token; x fp32 [T, d]."""
+    T, d = x.shape
+    if out is None:
+        out = torch.empty((T, d), dtype=torch.bfloat16 if dtype == BF16 else torch.float32, device=x.device)
+    rc = lib.ffsplit_token_rmsnorm(_ptr(x), T, d, ctypes.c_float(eps), dtype, _ptr(out), _stream())
+    _check(rc, "ffsplit_token_rmsnorm")
+    return out
+
+
+def stack_forward(desc, splits, x, b1_packed=None, b2=None, eps=1e-6, workspace=None):
+    """x <- x + FFN_split_l(n(x)) [+ b2_l] for every layer, in place on the fp32 stream x [T, d]."""
+    n, T = len(splits), x.shape[0]
+
+    def arr(ts):
+        if ts is None:
+            return None
+        a = (ctypes.c_void_p * n)()
+        for i, t in enumerate(ts):
+            a[i] = None if t is None else t.data_ptr()
+        return a
+
+    ws = _ws(workspace_bytes(desc, WS_STACK, T), workspace, x.device)
+    rc = lib.ffsplit_stack_forward(ctypes.byref(desc), n, arr(splits), arr(b1_packed), arr(b2), _ptr(x), T,
+                                   ctypes.c_float(eps), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "ffsplit_stack_forward")
+    return x
 
 
 def split_export(desc, split, what):

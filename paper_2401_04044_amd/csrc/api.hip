@@ -48,7 +48,7 @@ inline int act_of(const ffsplit_desc_t* d) { return d->act == FFSPLIT_ACT_SWIGLU
 // split, ws: scratch laid out by w).  Also the large-batch path of the int4 remainder, which
 // first expands its weights to a DENSE image.
 static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& w, const char* sp, const void* X, int M,
-                         void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st) {
+                         void* Y, void* Y_heavy, void* Y_rem, const Epilogue& ep, char* ws, hipStream_t st) {
   const int bf16 = d->dtype == FFSPLIT_BF16;
   const int esz = bf16 ? 2 : 4;
   const int act = act_of(d);
@@ -79,6 +79,7 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
         GemmArgs gp = g;
         gp.partial = 1; gp.C0 = part; gp.ldc0 = ldp; gp.split_col = ldp; gp.act_cols = 0;
         gp.c0_tiled = 0; gp.c1_tiled = 0;
+        gp.bias = nullptr; gp.bias_cols = 0; gp.resid = nullptr; gp.out_f32 = 0;   // applied with the sum
         if (launch_gemm_bf16(gp, ACT_NONE, false, GEMM_128x128, sp, st) != 0) return -1;
         return launch_splitk_epilogue(part, sp, ldp, g, a, st);
       }
@@ -105,6 +106,7 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.C0 = cat; g.ldc0 = L.k4; g.c0_tiled = L.tiled;
     g.C1 = tbuf; g.ldc1 = (int64_t)L.n_up * L.rp; g.c1_tiled = L.tiled;
     g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
+    g.bias = ep.b1; g.bias_cols = ep.b1 ? acted : 0;   // the activated neurons' biases (packed order)
     // (few tiles: eight wavefronts on 64-deep slabs, whose row-major gather takes whole cache lines)
     const int wide = fill256(M, L.n1) >= 50 ? GEMM_256x256 : (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_KSPLIT);
     FFS_TRY(run(g, act, big_m ? wide : GEMM_128x128, 1));
@@ -118,6 +120,7 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.M = M; g.N = L.n_up * L.mp; g.K = L.rp;
     g.act_cols = g.N; g.split_col = L.mp;
     g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
+    g.bias = ep.b1 ? ep.b1 + L.kp : nullptr; g.bias_cols = ep.b1 ? L.mp : 0;   // the remainder neurons' biases
     // (a short reduction leaves a 256x256 tile's epilogue uncovered: one workgroup per CU)
     const int g2s = (!glu && g.K >= 1024 && fill256(M, g.N) >= 90) ? GEMM_256x256 : GEMM_256x128;
     FFS_TRY(run(g, act, big_m ? g2s : GEMM_128x128, 1));
@@ -140,25 +143,31 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     }
   }
   // G4: [h1 | t2] * [W2h ; Q2] -> Y   (one fp32 accumulation, one rounding: Eq. 2's sum)
-  auto down = [&](void* out, int koff, int klen) -> int {
+  auto down = [&](void* out, int koff, int klen, bool with_ep) -> int {
     GemmArgs g = {};
     g.A = cat + koff_bytes(koff); g.lda = L.k4; g.a_tiled = L.tiled;
     g.Bt = sp + L.off_b4 + koff_bytes(koff); g.ldb = L.k4;
     g.M = M; g.N = dm; g.K = klen;
     g.split_col = dm; g.C0 = out; g.ldc0 = dm; g.n_store = dm;
+    if (with_ep) {   // output bias, residual stream, fp32 destination: Y only
+      g.bias = ep.b2; g.bias_cols = ep.b2 ? dm : 0;
+      g.resid = ep.resid; g.ldr = dm; g.out_f32 = bf16 ? ep.out_f32 : 0;
+    }
     return run(g, ACT_NONE, (big_m && fill256(M, dm) >= 90) ? GEMM_256x256 : GEMM_128x128, 1);
   };
   if (L.k4 > 0) {
-    FFS_TRY(down(Y, 0, L.k4));
+    FFS_TRY(down(Y, 0, L.k4, true));
+  } else if (ep.b2 || ep.resid || (bf16 && ep.out_f32)) {
+    return FFSPLIT_E_UNSUPPORTED;   // an empty layer with an epilogue: nothing to fuse it into
   } else {
     FFS_TRY(launch_fill_zero(Y, (size_t)M * dm * esz, st));
   }
   if (Y_heavy) {
-    if (L.kp > 0) FFS_TRY(down(Y_heavy, 0, L.kp));
+    if (L.kp > 0) FFS_TRY(down(Y_heavy, 0, L.kp, false));
     else FFS_TRY(launch_fill_zero(Y_heavy, (size_t)M * dm * esz, st));
   }
   if (Y_rem) {
-    if (L.k4 > L.kp) FFS_TRY(down(Y_rem, L.kp, L.k4 - L.kp));
+    if (L.k4 > L.kp) FFS_TRY(down(Y_rem, L.kp, L.k4 - L.kp, false));
     else FFS_TRY(launch_fill_zero(Y_rem, (size_t)M * dm * esz, st));
   }
   (void)k;
@@ -201,6 +210,10 @@ size_t ffsplit_workspace_bytes(const ffsplit_desc_t* d, int32_t call_id, int64_t
     if (d->rem_kind != FFSPLIT_REM_LOWRANK) return 0;
     return build_ws_bytes(*d) + factorize_ws_bytes(*d);
   }
+  if (call_id == FFSPLIT_WS_STACK) {
+    const size_t fwd = ffsplit_workspace_bytes(d, FFSPLIT_WS_FORWARD, T);
+    return fwd ? align256((size_t)T * d->d_model * esz) + fwd : 0;
+  }
   if (call_id == FFSPLIT_WS_FORWARD) {
     const Layout L = make_layout(*d);
     const FwdWs w = make_fwd_ws(*d, L, T);
@@ -216,6 +229,10 @@ int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, con
   int rc = check_desc(d, false);
   if (rc) return rc;
   if (T < 0 || T > 0x7fffffff) return FFSPLIT_E_BADSHAPE;
+  // The re-tiled (neuron-major) copy of the up projection lives at the start of the workspace;
+  // a later batch of the same calibration run may reuse it instead of transposing again.
+  const bool reuse_tiled = (score_kind & FFSPLIT_SCORE_REUSE_TILED) != 0;
+  score_kind &= ~FFSPLIT_SCORE_REUSE_TILED;
   if (score_kind < 0 || score_kind > 2) return FFSPLIT_E_BADDESC;
   const bool glu = d->act == FFSPLIT_ACT_SWIGLU;
   if (!acc || !T_total || !W1 || (glu && !Wg) || (T > 0 && !X)) return FFSPLIT_E_NULLPTR;
@@ -234,7 +251,7 @@ int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, con
     float* p2 = (float*)(ws + w.off_p2);
     float* p1 = (float*)(ws + w.off_p1);
     // transposed (neuron-major) copy of the up projection(s); rows beyond d_ff are zero
-    FFS_TRY(launch_fill_zero(Wt, w.wt_bytes, st));
+    if (!reuse_tiled) FFS_TRY(launch_fill_zero(Wt, w.wt_bytes, st));
     PermArgs pa = {};
     pa.lds = d->d_ff;
     pa.dst = Wt;
@@ -242,7 +259,9 @@ int ffsplit_score_neurons(const ffsplit_desc_t* d, const void* X, int64_t T, con
     pa.dst_tiled = bf16;
     pa.n_count = d->d_ff;
     pa.c_count = d->d_model;
-    if (glu) {
+    if (reuse_tiled) {
+      // nothing to do: the copy is in place
+    } else if (glu) {
       pa.src = Wg; pa.glu_mode = 1;
       FFS_TRY(launch_permute_transpose(pa, esz, st));
       pa.src = W1; pa.glu_mode = 2;
@@ -435,8 +454,9 @@ int ffsplit_factorize_remainder(const ffsplit_desc_t* d, const void* W1, const v
   return FFSPLIT_OK;
 }
 
-int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, int64_t T, void* Y, void* Y_heavy,
-                    void* Y_rem, void* workspace, size_t workspace_bytes, void* stream) {
+static int forward_impl(const ffsplit_desc_t* d, const void* split, const void* X, int64_t T, void* Y, void* Y_heavy,
+                        void* Y_rem, const ffsplit_epilogue_t* epi, void* workspace, size_t workspace_bytes,
+                        void* stream) {
   int rc = check_desc(d, true);
   if (rc) return rc;
   if (T < 0 || T > 0x7fffffff) return FFSPLIT_E_BADSHAPE;
@@ -444,6 +464,15 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   if (!split || !X || !Y) return FFSPLIT_E_NULLPTR;
   if (misaligned(X) || misaligned(Y) || misaligned(Y_heavy) || misaligned(Y_rem) || ((uintptr_t)split & 255u))
     return FFSPLIT_E_ALIGN;
+  Epilogue ep = {};
+  if (epi) {
+    if (misaligned(epi->b1_packed) || misaligned(epi->b2) || misaligned(epi->residual)) return FFSPLIT_E_ALIGN;
+    ep.b1 = epi->b1_packed; ep.b2 = epi->b2; ep.resid = epi->residual; ep.out_f32 = epi->y_f32 != 0;
+    // a neuron's bias enters before the activation: built for the GeLU layers with bf16 / fp32
+    // weights (the gated layers of the Llama family carry no biases)
+    if (ep.b1 && (d->act != FFSPLIT_ACT_GELU || d->rem_kind == FFSPLIT_REM_INT4 || d->rem_kind == FFSPLIT_REM_W3H8))
+      return FFSPLIT_E_UNSUPPORTED;
+  }
   const Layout L = make_layout(*d);
   const FwdWs w = make_fwd_ws(*d, L, T);
   if (!workspace || workspace_bytes < w.total_bytes) return FFSPLIT_E_WORKSPACE;
@@ -452,13 +481,19 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
   const char* sp = (const char*)split;
   char* ws = (char*)workspace;
   const int M = (int)T;
+  const size_t ysz = ep.out_f32 ? 4 : 2;   // (quantised kinds are bf16)
   if (d->rem_kind == FFSPLIT_REM_W3H8) {
     if (M <= W3H8_DECODE_MAX_T) {
       // passes of at most 32 tokens, each streaming the packed codes once
       for (int t0 = 0; t0 < M; t0 += 32) {
         const size_t o = (size_t)t0 * d->d_model * 2;
-        FFS_TRY(w3h8_forward_small(*d, L, w, sp, (const char*)X + o, M - t0 < 32 ? M - t0 : 32, (char*)Y + o,
-                                   Y_heavy ? (char*)Y_heavy + o : nullptr, Y_rem ? (char*)Y_rem + o : nullptr, ws, st));
+        Epilogue e2 = ep;
+        if (e2.resid) e2.resid += (size_t)t0 * d->d_model;
+        const int r3 = w3h8_forward_small(*d, L, w, sp, (const char*)X + o, M - t0 < 32 ? M - t0 : 32,
+                                          (char*)Y + (size_t)t0 * d->d_model * ysz,
+                                          Y_heavy ? (char*)Y_heavy + o : nullptr, Y_rem ? (char*)Y_rem + o : nullptr, e2,
+                                          ws, st);
+        if (r3) return r3 == -2 ? FFSPLIT_E_UNSUPPORTED : FFSPLIT_E_HIP;
       }
       return FFSPLIT_OK;
     }
@@ -467,7 +502,7 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
     const Layout LD = make_layout(dd);
     const FwdWs wd = make_fwd_ws(dd, LD, T);
     FFS_TRY(launch_w3h8_expand(*d, L, LD, sp, ws + w.off_img, st));
-    return forward_chain(&dd, LD, wd, ws + w.off_img, X, M, Y, Y_heavy, Y_rem, ws + w.off_dense, st);
+    return forward_chain(&dd, LD, wd, ws + w.off_img, X, M, Y, Y_heavy, Y_rem, ep, ws + w.off_dense, st);
   }
   if (d->rem_kind == FFSPLIT_REM_INT4) {
     if (w.i4_prefill) {
@@ -477,12 +512,86 @@ int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, i
       const Layout LD = make_layout(dd);
       const FwdWs wd = make_fwd_ws(dd, LD, T);
       FFS_TRY(launch_int4_expand(*d, L, LD, sp, ws + w.off_img, st));
-      return forward_chain(&dd, LD, wd, ws + w.off_img, X, M, Y, Y_heavy, Y_rem, ws + w.off_dense, st);
+      return forward_chain(&dd, LD, wd, ws + w.off_img, X, M, Y, Y_heavy, Y_rem, ep, ws + w.off_dense, st);
     }
-    const int r4 = int4_forward(*d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st);
+    const int r4 = int4_forward(*d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ep, ws, st);
     return r4 == 0 ? FFSPLIT_OK : (r4 == -2 ? FFSPLIT_E_UNSUPPORTED : FFSPLIT_E_HIP);
   }
-  return forward_chain(d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ws, st);
+  return forward_chain(d, L, w, sp, X, M, Y, Y_heavy, Y_rem, ep, ws, st);
+}
+
+int ffsplit_forward(const ffsplit_desc_t* d, const void* split, const void* X, int64_t T, void* Y, void* Y_heavy,
+                    void* Y_rem, void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(d, split, X, T, Y, Y_heavy, Y_rem, nullptr, workspace, workspace_bytes, stream);
+}
+
+int ffsplit_forward_ex(const ffsplit_desc_t* d, const void* split, const void* X, int64_t T, void* Y, void* Y_heavy,
+                       void* Y_rem, const ffsplit_epilogue_t* epilogue, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  return forward_impl(d, split, X, T, Y, Y_heavy, Y_rem, epilogue, workspace, workspace_bytes, stream);
+}
+
+size_t ffsplit_neuron_bias_floats(const ffsplit_desc_t* d) {
+  if (check_desc(d, true) != FFSPLIT_OK) return 0;
+  return (size_t)round_up(d->k, 64) + (size_t)round_up(d->d_ff - d->k, 64);
+}
+
+int ffsplit_pack_neuron_bias(const ffsplit_desc_t* d, const void* b1, const int32_t* idx, float* b1_packed,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_desc(d, true);
+  if (rc) return rc;
+  if (!b1 || !b1_packed || (d->k > 0 && !idx)) return FFSPLIT_E_NULLPTR;
+  if (misaligned(b1) || misaligned(b1_packed)) return FFSPLIT_E_ALIGN;
+  if (!workspace || workspace_bytes < build_ws_bytes(*d)) return FFSPLIT_E_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* rest = (int32_t*)workspace;
+  FFS_TRY(launch_rest_order(idx, d->k, d->d_ff, rest, (int32_t*)workspace + d->d_ff, st));
+  FFS_TRY(launch_pack_neuron_bias(b1, d->dtype == FFSPLIT_BF16, idx, rest, d->k, round_up(d->k, 64), d->d_ff - d->k,
+                                  round_up(d->d_ff - d->k, 64), b1_packed, st));
+  return FFSPLIT_OK;
+}
+
+int ffsplit_token_rmsnorm(const float* x, int64_t T, int32_t d_model, float eps, int32_t dtype, void* out,
+                          void* stream) {
+  if (d_model <= 0 || d_model % 8 != 0 || T < 0 || T > 0x7fffffff) return FFSPLIT_E_BADSHAPE;
+  if (dtype != FFSPLIT_F32 && dtype != FFSPLIT_BF16) return FFSPLIT_E_BADDESC;
+  if (T == 0) return FFSPLIT_OK;
+  if (!x || !out) return FFSPLIT_E_NULLPTR;
+  if (misaligned(x) || misaligned(out)) return FFSPLIT_E_ALIGN;
+  FFS_TRY(launch_token_rmsnorm(x, T, d_model, eps, dtype == FFSPLIT_BF16, out, (hipStream_t)stream));
+  return FFSPLIT_OK;
+}
+
+int ffsplit_stack_forward(const ffsplit_desc_t* d, int32_t n_layers, const void* const* splits,
+                          const float* const* b1_packed, const float* const* b2, float* x, int64_t T, float eps,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_desc(d, true);
+  if (rc) return rc;
+  if (n_layers < 0 || T < 0 || T > 0x7fffffff) return FFSPLIT_E_BADSHAPE;
+  if (n_layers == 0 || T == 0) return FFSPLIT_OK;
+  if (!splits || !x) return FFSPLIT_E_NULLPTR;
+  for (int l = 0; l < n_layers; ++l)
+    if (!splits[l]) return FFSPLIT_E_NULLPTR;
+  if (misaligned(x)) return FFSPLIT_E_ALIGN;
+  const size_t esz = d->dtype == FFSPLIT_BF16 ? 2 : 4;
+  const size_t xn_bytes = align256((size_t)T * d->d_model * esz);
+  const size_t fwd = ffsplit_workspace_bytes(d, FFSPLIT_WS_FORWARD, T);
+  if (!workspace || workspace_bytes < xn_bytes + fwd) return FFSPLIT_E_WORKSPACE;
+  if ((uintptr_t)workspace & 255u) return FFSPLIT_E_ALIGN;
+  char* xn = (char*)workspace;
+  for (int l = 0; l < n_layers; ++l) {
+    // x <- x + FFN_l(n(x)): the normalised tokens in the storage type, the sum back into the fp32 stream
+    rc = ffsplit_token_rmsnorm(x, T, d->d_model, eps, d->dtype, xn, stream);
+    if (rc) return rc;
+    ffsplit_epilogue_t e = {};
+    e.b1_packed = b1_packed ? b1_packed[l] : nullptr;
+    e.b2 = b2 ? b2[l] : nullptr;
+    e.residual = x;
+    e.y_f32 = 1;
+    rc = forward_impl(d, splits[l], xn, T, x, nullptr, nullptr, &e, xn + xn_bytes, workspace_bytes - xn_bytes, stream);
+    if (rc) return rc;
+  }
+  return FFSPLIT_OK;
 }
 
 int ffsplit_split_export(const ffsplit_desc_t* d, const void* split, int32_t what, int8_t* q_out, uint16_t* s_out,

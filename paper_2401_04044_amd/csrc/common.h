@@ -80,10 +80,30 @@ struct GemmArgs {
   int m_pad;       // rows of a tiled destination (multiple of 32)
   int n_store;     // valid columns of a row-major destination
   int partial;     // bf16 kernels: write fp32 split-K partials [split][M][ldc0] to C0 instead
+  // Optional additions of the store epilogue (never with partial):
+  //   bias [bias_cols] fp32, added to GEMM columns [0, bias_cols) before the activation (a
+  //   neuron's bias; not with ACT_GLU), or to every output column of an un-activated product;
+  //   resid [M, ldr] fp32, added to the value routed to C0 (row-major destinations only);
+  //   out_f32: C0 holds fp32 [M, ldc0] instead of the storage type.
+  const float* bias;
+  int bias_cols;
+  const float* resid;
+  int64_t ldr;
+  int out_f32;
   // score mode: per-row-tile partial column sums of h^2 and |h|
   float* part_s2;  // [tiles_m, n_out]
   float* part_s1;
   int n_out;
+};
+
+// What a forward call adds around the two halves of Eq. 2 (all optional): the neurons' biases in
+// packed order [heavy kp | remainder mp] (fp32), the output bias [d_model] (fp32), the residual
+// stream [T, d_model] (fp32) and an fp32 destination for Y.
+struct Epilogue {
+  const float* b1;
+  const float* b2;
+  const float* resid;
+  int out_f32;
 };
 
 // n_split > 1: only with a.partial and no activation: fp32 partials [split][M][ldc0] into C0

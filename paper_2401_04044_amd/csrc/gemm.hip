@@ -107,9 +107,12 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs p) {
         const int row = m0 + ty + 16 * i;
         if (row >= p.M) continue;
         float v;
+        // (a neuron's bias before the activation; the output bias of an un-activated product)
+        const float bz = (ACT != ACT_GLU && p.bias != nullptr && cb < p.bias_cols) ? p.bias[cb] : 0.f;
         if (ACT == ACT_GLU) v = glu_here ? silu_f(acc[i][j]) * acc[i][(j + 2) & 3] : acc[i][j];
-        else if (ACT == ACT_GELU) v = cb < p.act_cols ? gelu_f(acc[i][j]) : acc[i][j];
-        else v = acc[i][j];
+        else if (ACT == ACT_GELU) v = cb < p.act_cols ? gelu_f(acc[i][j] + bz) : acc[i][j] + bz;
+        else v = acc[i][j] + bz;
+        if (p.resid != nullptr && !p.partial && oc < p.split_col) v += p.resid[(int64_t)row * p.ldr + oc];
         base[(int64_t)row * ld] = v;
       }
     }

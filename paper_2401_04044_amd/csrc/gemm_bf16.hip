@@ -105,8 +105,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
       char* base;
       int64_t ld;
       int occ, tiled;
-      if (oc < p.split_col) { base = (char*)p.C0; ld = p.ldc0; occ = oc; tiled = p.c0_tiled; }
+      const bool to_c0 = oc < p.split_col;
+      if (to_c0) { base = (char*)p.C0; ld = p.ldc0; occ = oc; tiled = p.c0_tiled; }
       else { base = (char*)p.C1; ld = p.ldc1; occ = oc - p.split_col; tiled = p.c1_tiled; }
+      // a neuron's bias (GEMM column cb + 8 g + 4 half + e), added before the activation
+      float bz[4][4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c = cb + 8 * g + 4 * half;
+        float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ACT != ACT_GLU && p.bias != nullptr && c + 3 < p.bias_cols) b4 = *(const float4*)(p.bias + c);
+        bz[g][0] = b4.x; bz[g][1] = b4.y; bz[g][2] = b4.z; bz[g][3] = b4.w;
+      }
+      const bool f32o = p.out_f32 && to_c0 && !tiled;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int rblk = (m0 + wm * WM) / 32 + i;
@@ -122,6 +133,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
           }
           continue;
         }
+        // the residual stream (fp32, row-major, same columns as the destination)
+        const float* rrow = (p.resid != nullptr && to_c0 && !tiled && row < p.M)
+                                ? p.resid + (int64_t)row * p.ldr + occ + 4 * half : nullptr;
         uint32_t pk[4][2];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -131,13 +145,24 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
             // (static tile indices: an activated pair is (gate j, value j + 1))
             constexpr int TNM1 = TN - 1;
             const int j1 = j + 1 < TN ? j + 1 : TNM1;
-            const float gt = acc[i][j][4 * g + e];
+            const float gt = acc[i][j][4 * g + e] + bz[g][e];
             const float z = (ACT == ACT_GLU && act_here) ? acc[i][j1][4 * g + e] : gt;
             v[e] = act_here ? act_bf16<ACT>(z, gt) : z;
           }
-          pk[g][0] = pack_bf16x2(v[0], v[1]);
-          pk[g][1] = pack_bf16x2(v[2], v[3]);
+          const bool col_ok = occ + 8 * g + 4 * half < p.n_store;
+          if (rrow != nullptr && col_ok) {
+            const float4 r4 = *(const float4*)(rrow + 8 * g);
+            v[0] += r4.x; v[1] += r4.y; v[2] += r4.z; v[3] += r4.w;
+          }
+          if (f32o) {
+            if (row < p.M && col_ok)
+              *(float4*)((float*)base + (int64_t)row * ld + occ + 8 * g + 4 * half) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            pk[g][0] = pack_bf16x2(v[0], v[1]);
+            pk[g][1] = pack_bf16x2(v[2], v[3]);
+          }
         }
+        if (f32o) continue;
         // groups (0,1) and (2,3) each cover 16 consecutive columns: after the swap the lower
         // lanes hold columns 0..7 and the upper lanes columns 8..15 of those 16
 #pragma unroll
@@ -590,6 +615,11 @@ struct SplitEpiArgs {
   void* C1;
   int64_t ldc0, ldc1;
   int c0_tiled, c1_tiled, n_store;
+  const float* bias;   // as in GemmArgs
+  int bias_cols;
+  const float* resid;
+  int64_t ldr;
+  int out_f32;
 };
 
 __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const SplitEpiArgs p) {
@@ -612,6 +642,10 @@ __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const SplitEpiArgs
         u[0] += e.x; u[1] += e.y; u[2] += e.z; u[3] += e.w; u[4] += f.x; u[5] += f.y; u[6] += f.z; u[7] += f.w;
       }
     }
+    if (!glu && p.bias != nullptr && c + 7 < p.bias_cols) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += p.bias[c + e];
+    }
     if (pair) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = silu_fast(v[e]) * u[e];
@@ -623,8 +657,22 @@ __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const SplitEpiArgs
   char* base;
   int64_t ld;
   int col, tiled;
-  if (oc < p.split_col) { base = (char*)p.C0; ld = p.ldc0; col = oc; tiled = p.c0_tiled; }
+  const bool to_c0 = oc < p.split_col;
+  if (to_c0) { base = (char*)p.C0; ld = p.ldc0; col = oc; tiled = p.c0_tiled; }
   else { base = (char*)p.C1; ld = p.ldc1; col = oc - p.split_col; tiled = p.c1_tiled; }
+  if (to_c0 && !tiled && row < p.M && col < p.n_store) {
+    if (p.resid != nullptr) {
+      const float* r = p.resid + (int64_t)row * p.ldr + col;
+      const float4 a = *(const float4*)r, b = *(const float4*)(r + 4);
+      v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w; v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+    }
+    if (p.out_f32) {
+      float* dst = (float*)base + (int64_t)row * ld + col;
+      *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+      *(float4*)(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      return;
+    }
+  }
   const uint4 val = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
                                pack_bf16x2(v[6], v[7]));
   if (tiled) {
@@ -643,6 +691,7 @@ int launch_splitk_epilogue(const float* part, int n_split, int ldp, const GemmAr
   a.act = act; a.act_cols = g.act_cols; a.split_col = g.split_col;
   a.C0 = g.C0; a.C1 = g.C1; a.ldc0 = g.ldc0; a.ldc1 = g.ldc1;
   a.c0_tiled = g.c0_tiled; a.c1_tiled = g.c1_tiled; a.n_store = g.n_store;
+  a.bias = g.bias; a.bias_cols = g.bias_cols; a.resid = g.resid; a.ldr = g.ldr; a.out_f32 = g.out_f32;
   if ((a.n_out & 7) || (g.split_col & 7) || (g.act_cols & 63)) return -1;
   const int64_t n = (int64_t)a.rows * (a.n_out / 8);
   if (n <= 0) return 0;

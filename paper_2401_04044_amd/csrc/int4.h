@@ -17,6 +17,6 @@ int launch_int4_export(const ffsplit_desc_t& d, const Layout& L, const char* spl
 int launch_int4_expand(const ffsplit_desc_t& d, const Layout& L, const Layout& LD, const char* split, char* image,
                        hipStream_t st);
 int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X, int M,
-                 void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st);
+                 void* Y, void* Y_heavy, void* Y_rem, const Epilogue& ep, char* ws, hipStream_t st);
 
 }  // namespace ffsplit

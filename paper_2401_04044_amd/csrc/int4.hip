@@ -574,6 +574,9 @@ struct Phase2Args {
   bf16_t* Y;
   bf16_t* Yh;
   bf16_t* Yr;
+  const float* b2;         // [d] output bias or null
+  const float* resid;      // [T, d] residual stream or null
+  int out_f32;             // Y holds fp32
 };
 
 constexpr int P2_MAXJ = 12;  // int4 neuron blocks per workgroup and pass
@@ -750,7 +753,11 @@ __global__ void __launch_bounds__(512) int4_phase2_kernel(const Phase2Args p) {
 #pragma unroll
     for (int s = 0; s < 16; ++s) { a0 += va[s].x; a1 += va[s].y; b0 += vb[s].x; b1 += vb[s].y; }
     const int64_t oi = (int64_t)tok * p.d + cg * 128 + c;
-    *(uint32_t*)(p.Y + oi) = pack_bf16x2(a0 + b0, a1 + b1);
+    float y0 = a0 + b0, y1 = a1 + b1;
+    if (p.b2) { y0 += p.b2[cg * 128 + c]; y1 += p.b2[cg * 128 + c + 1]; }
+    if (p.resid) { y0 += p.resid[oi]; y1 += p.resid[oi + 1]; }
+    if (p.out_f32) *(float2*)((float*)p.Y + oi) = make_float2(y0, y1);
+    else *(uint32_t*)(p.Y + oi) = pack_bf16x2(y0, y1);
     if (p.Yh) *(uint32_t*)(p.Yh + oi) = pack_bf16x2(a0, a1);
     if (p.Yr) *(uint32_t*)(p.Yr + oi) = pack_bf16x2(b0, b1);
   }
@@ -1008,7 +1015,7 @@ static int launch_phase1(const Phase1Args& a, int grid, hipStream_t st) {
 }
 
 int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X, int M,
-                 void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st) {
+                 void* Y, void* Y_heavy, void* Y_rem, const Epilogue& ep, char* ws, hipStream_t st) {
   const int m = d.d_ff - d.k, dm = d.d_model, G = L.groups;
   const int hl = L.kp128 + L.jp128;
   const int S = w.n_split;
@@ -1054,7 +1061,8 @@ int int4_forward(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const
     b.jp128 = L.jp128;
     b.part = (float*)(ws + w.off_part);
     b.counters = (unsigned*)(ws + w.off_cnt);
-    b.Y = (bf16_t*)Y + (int64_t)t0 * dm;
+    b.Y = ep.out_f32 ? (bf16_t*)((float*)Y + (int64_t)t0 * dm) : (bf16_t*)Y + (int64_t)t0 * dm;
+    b.b2 = ep.b2; b.resid = ep.resid ? ep.resid + (int64_t)t0 * dm : nullptr; b.out_f32 = ep.out_f32;
     b.Yh = Y_heavy ? (bf16_t*)Y_heavy + (int64_t)t0 * dm : nullptr;
     b.Yr = Y_rem ? (bf16_t*)Y_rem + (int64_t)t0 * dm : nullptr;
     hipLaunchKernelGGL(int4_phase2_kernel, dim3(G, S), dim3(512), 0, st, b);

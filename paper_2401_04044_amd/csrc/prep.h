@@ -32,6 +32,12 @@ int launch_reduce_partials(const float* p2, const float* p1, int tiles, int n_ou
 int launch_finalize_scores(const void* W2, int bf16, int d_model, int d_ff, const float* acc, float t_total,
                            int kind, float* scores, hipStream_t st);
 
+// per-token RMS normalisation of an fp32 stream into bf16 or fp32 (the pre-norm of a layer stack)
+int launch_token_rmsnorm(const float* x, int64_t T, int d, float eps, int bf16, void* out, hipStream_t st);
+// a layer's neuron biases in the packed split's neuron order, fp32, zero on the padding
+int launch_pack_neuron_bias(const void* b1, int bf16, const int32_t* idx, const int32_t* rest, int k, int kp, int m,
+                            int mp, float* out, hipStream_t st);
+
 // select.hip
 size_t select_workspace_bytes(int d_ff);
 int launch_select(const float* scores, int d_ff, int k, int32_t* idx, int32_t* perm, int32_t* nan_flag,

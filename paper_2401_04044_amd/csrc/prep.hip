@@ -138,4 +138,70 @@ int launch_finalize_scores(const void* W2, int bf16, int d_model, int d_ff, cons
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// ------------------------------------------------------------------ stack harness kernels
+
+// out[t, :] = x[t, :] / sqrt(mean(x[t, :]^2) + eps), one workgroup per token, fp32 sums added in
+// a fixed order (lane-strided partials, wavefront butterfly, then the four wavefronts in order).
+template <bool BF16>
+__global__ void __launch_bounds__(256) token_rmsnorm_kernel(const float* x, int d, float eps, void* out) {
+  __shared__ float wsum[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* row = x + (int64_t)blockIdx.x * d;
+  float s = 0.f;
+  for (int c = tid * 4; c < d; c += 1024) {
+    const float4 v = *(const float4*)(row + c);
+    s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+  if (lane == 0) wsum[wave] = s;
+  __syncthreads();
+  const float tot = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int c = tid * 4; c < d; c += 1024) {
+    const float4 v = *(const float4*)(row + c);
+    if (BF16) {
+      *(uint2*)((bf16_t*)out + (int64_t)blockIdx.x * d + c) =
+          make_uint2(pack_bf16x2(v.x * inv, v.y * inv), pack_bf16x2(v.z * inv, v.w * inv));
+    } else {
+      *(float4*)((float*)out + (int64_t)blockIdx.x * d + c) = make_float4(v.x * inv, v.y * inv, v.z * inv, v.w * inv);
+    }
+  }
+}
+
+int launch_token_rmsnorm(const float* x, int64_t T, int d, float eps, int bf16, void* out, hipStream_t st) {
+  if (T <= 0) return 0;
+  if (bf16) hipLaunchKernelGGL(token_rmsnorm_kernel<true>, dim3((unsigned)T), dim3(256), 0, st, x, d, eps, out);
+  else hipLaunchKernelGGL(token_rmsnorm_kernel<false>, dim3((unsigned)T), dim3(256), 0, st, x, d, eps, out);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// packed[i] = b1[idx[i]] for i < k, 0 up to kp; packed[kp + i] = b1[rest[i]] for i < m, 0 up to kp + mp
+template <typename T>
+__global__ void pack_neuron_bias_kernel(const T* b1, const int32_t* idx, const int32_t* rest, int k, int kp, int m,
+                                        int mp, float* out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= kp + mp) return;
+  int src = -1;
+  if (i < k) src = idx[i];
+  else if (i >= kp && i - kp < m) src = rest[i - kp];
+  float v = 0.f;
+  if (src >= 0) {
+    if (sizeof(T) == 2) v = bf16_to_f32((bf16_t)b1[src]);
+    else v = __uint_as_float((uint32_t)b1[src]);
+  }
+  out[i] = v;
+}
+
+int launch_pack_neuron_bias(const void* b1, int bf16, const int32_t* idx, const int32_t* rest, int k, int kp, int m,
+                            int mp, float* out, hipStream_t st) {
+  const int n = kp + mp;
+  if (n <= 0) return 0;
+  if (bf16) hipLaunchKernelGGL(pack_neuron_bias_kernel<uint16_t>, dim3((n + 255) / 256), dim3(256), 0, st,
+                               (const uint16_t*)b1, idx, rest, k, kp, m, mp, out);
+  else hipLaunchKernelGGL(pack_neuron_bias_kernel<uint32_t>, dim3((n + 255) / 256), dim3(256), 0, st,
+                          (const uint32_t*)b1, idx, rest, k, kp, m, mp, out);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 }  // namespace ffsplit

@@ -18,6 +18,6 @@ int launch_w3h8_expand(const ffsplit_desc_t& d, const Layout& L, const Layout& L
 // forward for at most 32 tokens (one pass): the packed codes are streamed once per product
 // (weight-streaming kernels of skinny.hip), scratch laid out by make_fwd_ws
 int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X,
-                       int M, void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st);
+                       int M, void* Y, void* Y_heavy, void* Y_rem, const Epilogue& ep, char* ws, hipStream_t st);
 
 }  // namespace ffsplit

@@ -311,7 +311,7 @@ int launch_w3h8_expand(const ffsplit_desc_t& d, const Layout& L, const Layout& L
 }
 
 int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w, const char* split, const void* X,
-                       int M, void* Y, void* Y_heavy, void* Y_rem, char* ws, hipStream_t st) {
+                       int M, void* Y, void* Y_heavy, void* Y_rem, const Epilogue& ep, char* ws, hipStream_t st) {
   const int dm = d.d_model;
   const int act = d.act == FFSPLIT_ACT_SWIGLU ? ACT_GLU : ACT_GELU;
   char* cat = ws + w.off_cat;                  // [32, k4] tiled fp16: activated heavy | remainder neurons
@@ -353,7 +353,11 @@ int w3h8_forward_small(const ffsplit_desc_t& d, const Layout& L, const FwdWs& w,
     g.C0 = out;
     return launch_skinny_reduce(g, ACT_NONE, p0, n, 0, st);
   };
+  // (output bias, residual stream and an fp32 destination apply to Y only)
+  g.bias = ep.b2; g.bias_cols = ep.b2 ? dm : 0; g.resid = ep.resid; g.ldr = dm; g.out_f32 = ep.out_f32;
+  if (S[0] + S[1] == 0 && (ep.b2 || ep.resid || ep.out_f32)) return -2;
   if (emit(Y, part, S[0] + S[1])) return -1;
+  g.bias = nullptr; g.bias_cols = 0; g.resid = nullptr; g.out_f32 = 0;
   if (emit(Y_heavy, part, S[0])) return -1;
   if (emit(Y_rem, part + seg, S[1])) return -1;
   return 0;

@@ -387,6 +387,11 @@ struct SkinnyReduceArgs {
   int f16_out;   // destinations hold fp16 (saturating) instead of bf16
   int rb_split, n_split_b;   // row blocks from rb_split on have n_split_b ranges
   int n_tb, nt;              // 32-token blocks to write / token blocks per row block in part
+  const float* bias;         // as in GemmArgs
+  int bias_cols;
+  const float* resid;
+  int64_t ldr;
+  int out_f32;
 };
 
 __device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi) {
@@ -404,6 +409,14 @@ __device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int t
   const bool glu = p.act == ACT_GLU;
   int oc = cb;
   if (glu) oc = act_here ? cb / 2 : cb - p.act_cols / 2;
+  {
+    // a neuron's bias (GEMM column cb + 8 g + 4 (lane >> 5) + e), before the activation
+    const int c = cb + 8 * g + 4 * (lane >> 5);
+    if (!glu && p.bias != nullptr && c + 3 < p.bias_cols) {
+      const float4 b4 = *(const float4*)(p.bias + c);
+      v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+    }
+  }
   if (act_here) {
     if (glu) {
 #pragma unroll
@@ -418,8 +431,19 @@ __device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int t
   char* base;
   int64_t ld;
   int col, tiled;
-  if (col0 < p.split_col) { base = (char*)p.C0; ld = p.ldc0; col = col0; tiled = p.c0_tiled; }
+  const bool to_c0 = col0 < p.split_col;
+  if (to_c0) { base = (char*)p.C0; ld = p.ldc0; col = col0; tiled = p.c0_tiled; }
   else { base = (char*)p.C1; ld = p.ldc1; col = col0 - p.split_col; tiled = p.c1_tiled; }
+  if (to_c0 && !tiled && row < p.M && col < p.n_store) {
+    if (p.resid != nullptr) {
+      const float4 r4 = *(const float4*)(p.resid + (int64_t)row * p.ldr + col);
+      v[0] += r4.x; v[1] += r4.y; v[2] += r4.z; v[3] += r4.w;
+    }
+    if (p.out_f32) {
+      *(float4*)((float*)base + (int64_t)row * ld + col) = make_float4(v[0], v[1], v[2], v[3]);
+      return;
+    }
+  }
   const uint2 val = p.f16_out ? make_uint2(pack_f16x2_sat(v[0], v[1]), pack_f16x2_sat(v[2], v[3]))
                               : make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
   if (tiled) {
@@ -591,6 +615,7 @@ static void fill_reduce_args(SkinnyReduceArgs& r, const GemmArgs& g, int act) {
   r.act = act; r.act_cols = g.act_cols; r.split_col = g.split_col;
   r.C0 = g.C0; r.C1 = g.C1; r.ldc0 = g.ldc0; r.ldc1 = g.ldc1;
   r.c0_tiled = g.c0_tiled; r.c1_tiled = g.c1_tiled; r.n_store = g.n_store;
+  r.bias = g.bias; r.bias_cols = g.bias_cols; r.resid = g.resid; r.ldr = g.ldr; r.out_f32 = g.out_f32;
 }
 
 template <bool AT, int RB, int NW, bool DUAL>
@@ -679,6 +704,7 @@ int launch_skinny_reduce2(const GemmArgs& g, int act, const float* part, int n_s
   r.act = act; r.act_cols = g.act_cols; r.split_col = g.split_col;
   r.C0 = g.C0; r.C1 = g.C1; r.ldc0 = g.ldc0; r.ldc1 = g.ldc1;
   r.c0_tiled = g.c0_tiled; r.c1_tiled = g.c1_tiled; r.n_store = g.n_store;
+  r.bias = g.bias; r.bias_cols = g.bias_cols; r.resid = g.resid; r.ldr = g.ldr; r.out_f32 = g.out_f32;
   hipLaunchKernelGGL(skinny_reduce_kernel, dim3(r.n_rb), dim3(256), 0, st, r);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }

@@ -97,14 +97,21 @@ def layer_to_dev(L, dtype):
     return {nm: dev(L[nm], dtype) for nm in ("W1", "W2", "Wg")}
 
 
-def gpu_scores(ff, desc, Ld, Xd_batches, kind=0):
+def gpu_scores(ff, desc, Ld, Xd_batches, kind=0, reuse_tiled=False):
+    """reuse_tiled: one workspace for the whole run, batches after the first reuse the re-tiled
+    copy of the up projection that the first one left in it."""
     d_ff = desc.d_ff
     acc = torch.zeros(2 * d_ff, dtype=torch.float32, device="cuda")
     scores = torch.empty(d_ff, dtype=torch.float32, device="cuda")
     tt = 0
+    ws = None
+    if reuse_tiled:
+        n = max(ff.workspace_bytes(desc, ff.WS_SCORE, x.shape[0]) for x in Xd_batches)
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda")
     for i, Xd in enumerate(Xd_batches):
         last = i == len(Xd_batches) - 1
-        tt = ff.score_neurons(desc, Xd, Ld["W1"], Ld["Wg"], Ld["W2"], acc, tt, scores if last else None, kind)
+        flag = ff.SCORE_REUSE_TILED if (reuse_tiled and i > 0) else 0
+        tt = ff.score_neurons(desc, Xd, Ld["W1"], Ld["Wg"], Ld["W2"], acc, tt, scores if last else None, kind | flag, ws)
     torch.cuda.synchronize()
     return scores, acc, tt
 

@@ -120,6 +120,21 @@ def test_score_is_deterministic(ff):
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("cfg", [reduced(C2, 256, 1000, rank=64), reduced(C3, 192, 700, rank=64)],
+                         ids=["gelu", "swiglu"])
+def test_score_batches_can_reuse_the_retiled_weights(ff, cfg):
+    """Batches after the first of a calibration run skip the transposition of the up projection
+    (flag FFSPLIT_SCORE_REUSE_TILED): the same bits as re-tiling on every call."""
+    L = wl.make_layer(cfg)
+    Ld = layer_to_dev(L, cfg.dtype)
+    X = wl.make_tokens(cfg, 700, wl.gen.S_CALIB)
+    xs = [dev(X[:300], cfg.dtype), dev(X[300:301], cfg.dtype), dev(X[301:], cfg.dtype)]
+    a, acc_a, ta = gpu_scores(ff, desc_for(ff, cfg, "none"), Ld, xs)
+    b, acc_b, tb = gpu_scores(ff, desc_for(ff, cfg, "none"), Ld, xs, reuse_tiled=True)
+    assert ta == tb == 700
+    assert torch.equal(a, b) and torch.equal(acc_a, acc_b)
+
+
 # ---------------------------------------------------------------- forward, low-rank / dense / none
 
 FWD_CASES = [
