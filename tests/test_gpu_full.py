@@ -13,7 +13,7 @@ from oracle import ffsplit_oracle as orc
 import workloads as wl
 from workloads.configs import C1, C2, C3, C4, C5
 from gpu_util import (guarded_forward, TOL, dev, host, relf, assert_close, assert_scores_close, desc_for, layer_to_dev,
-                      gpu_scores)
+                      gpu_scores, Guarded)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
@@ -266,51 +266,159 @@ def test_c4_llama7b_shape_w3h8(ff):
     assert_close(host(Y), want(X)[0], "bf16", f"C4 w3h8 T={T}, all rows")
 
 
-def test_c5_opt13b_shape_layers_teacher_forced(ff):
-    """Two layers of the 40-layer stack at full width, each fed the oracle's own
-    layer input (rounded to bf16): x <- x + FFN_split(n(x)), n = per-token RMS
-    normalisation.  Calibration runs on a 2048-token slice to keep the oracle's
-    share of this test short; prefill T = 4096 and decode B = 16 as specified."""
+# ---------------------------------------------------------------- the 40-layer stack
+# x <- x + FFN_l(n(x)), n = per-token RMS normalisation (the reading under which the stream of
+# these synthetic layers stays finite).  Covered here, at full width (d_model 5120, d_ff 20480,
+# k 819, rank 1280):
+#   * ALL 40 layers teacher-forced: each layer is fed the oracle's own layer input.  Per layer:
+#     the norm kernel, the scores of a 256-token calibration stream that the oracle moves
+#     through the DENSE layers (heavy hitters are identified on the unmodified model), the
+#     selected set, the split built from it, a 4096-token prefill whose first 64 rows are the
+#     oracle's forward stream (moved through the SPLIT layers), a decode batch of 16, and one
+#     step of the stack driver (norm + layer + residual, fp32 stream).
+#   * layer 0: the full 16 384-token calibration (in four batches) against the oracle's scores
+#     of every neuron.
+#   * layers 0, 1, 20, 39: every one of the 4096 prefill rows against the oracle.
+#   * the free-running 40-layer ffsplit_stack_forward call (T = 4096): its first 64 rows against
+#     the oracle's end of stack (reported, and held to a looser bar: errors compound).
+# The calibration stream past layer 0 has 256 tokens, not 16 384: the oracle's dense fp64 layers
+# cost 0.42 GFLOP per token and layer.
+
+C5_STATE = {}
+C5_NC, C5_NF = 256, 64
+C5_FULL_ROWS = (0, 1, 20, 39)
+
+
+def _c5_layer(ff, layer, st):
     cfg = C5
-    Tc = 2048
-    x_cal = wl.make_tokens(cfg, Tc, wl.gen.S_CALIB).astype(np.float64)
-    x_fwd = wl.make_tokens(cfg, 64).astype(np.float64)          # oracle-side residual stream (sampled tokens)
-    for layer in range(2):
-        L = wl.make_layer(cfg, layer)
-        Ld = layer_to_dev(L, cfg.dtype)
-        xn_cal = wl.bf16_round(orc.token_rms_normalise(x_cal))
-        desc0 = desc_for(ff, cfg, "none")
-        scores, acc, tt = gpu_scores(ff, desc0, Ld, [dev(xn_cal[:1024], "bf16"), dev(xn_cal[1024:], "bf16")])
-        idx, _, flag = ff.select_heavy(scores, cfg.k)
-        torch.cuda.synchronize()
-        idx_h = idx.cpu().numpy()
-        assert np.array_equal(idx_h, orc.select_heavy(scores.cpu().numpy(), cfg.k))
-        # Past the first layer the residual stream is no longer isotropic (every token carries
-        # the mean FFN output), a few planted neurons go quiet and the heavy set is what the
-        # scores say, not the planted set: compare with the oracle's own selection.
-        acc_o = orc.score_accumulate(orc.new_accumulator(cfg.d_ff), xn_cal, L["W1"], None, "gelu")
-        want_s = orc.neuron_scores(acc_o, L["W2"])
-        srt = np.sort(want_s)[::-1]
-        assert srt[cfg.k - 1] / srt[cfg.k] > 1 + 1e-4          # the cut is wider than the fp32 score error
-        assert relf(scores.cpu().numpy(), want_s) < TOL["bf16"]
-        assert np.array_equal(np.sort(idx_h), np.sort(orc.select_heavy(want_s, cfg.k)))
-        if layer == 0:
-            assert np.array_equal(np.sort(idx_h), L["planted"])
-        fac = wl.make_factors(cfg, L, idx_h, layer=layer)
-        desc = desc_for(ff, cfg)
-        split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, {k: dev(v, "bf16") for k, v in fac.items()})
-        # prefill: 4096 tokens, the first 64 of them are the oracle's sample
-        xn = wl.bf16_round(orc.token_rms_normalise(x_fwd))
-        Xfull = np.concatenate([xn, wl.make_tokens(cfg, cfg.prefill_T - 64, wl.gen.S_EVAL, layer=layer + 1)])
-        Y = guarded_forward(ff, desc, split, dev(Xfull, "bf16"))
-        Yd = guarded_forward(ff, desc, split, dev(xn[:16], "bf16"))       # decode batch of 16
-        torch.cuda.synchronize()
-        want = orc.forward_split(xn, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
-        assert relf(host(Y[:64]), want) < TOL["bf16"]
-        assert relf(host(Yd), want[:16]) < TOL["bf16"]
-        # both residual streams move on through the oracle (teacher forcing)
-        x_fwd = x_fwd + want
-        x_cal = x_cal[:256] + orc.dense_ffn(xn_cal[:256], L["W1"], L["W2"], None, "gelu")
-        x_cal = np.concatenate([x_cal] * (Tc // 256))
-        del Ld, split
-        torch.cuda.empty_cache()
+    L = wl.make_layer(cfg, layer)
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc0 = desc_for(ff, cfg, "none")
+    # ---- the norm kernel on both oracle streams
+    xn_cal_o = orc.token_rms_normalise(st["x_cal"])
+    xn_fwd_o = orc.token_rms_normalise(st["x_fwd"])
+    got_n = ff.token_rmsnorm(torch.from_numpy(st["x_cal"].astype(np.float32)).cuda(), ff.BF16)
+    assert relf(host(got_n), xn_cal_o) < 3e-3, layer
+    xn_cal = wl.bf16_round(xn_cal_o)            # the stored tokens both sides multiply
+    xn_fwd = wl.bf16_round(xn_fwd_o)
+    # ---- calibration on the dense layer: scores, selection
+    scores, acc, tt = gpu_scores(ff, desc0, Ld, [dev(xn_cal[:100], "bf16"), dev(xn_cal[100:], "bf16")], reuse_tiled=True)
+    idx, _, flag = ff.select_heavy(scores, cfg.k)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    assert int(flag.item()) == 0
+    assert np.array_equal(idx_h, orc.select_heavy(scores.cpu().numpy(), cfg.k)), layer      # ranking kernel
+    acc_o = orc.score_accumulate(orc.new_accumulator(cfg.d_ff), xn_cal, L["W1"], None, "gelu")
+    want_s = orc.neuron_scores(acc_o, L["W2"])
+    srt = np.sort(want_s)[::-1]
+    margin = srt[cfg.k - 1] / srt[cfg.k]
+    assert_scores_close(scores.cpu().numpy(), want_s, "bf16", f"C5 layer {layer}")
+    # Past the first layer the stream is no longer isotropic (every token carries the mean
+    # layer output), a few planted neurons go quiet and the heavy set is what the scores say:
+    # the oracle's own selection, provided its cut is wider than the score error.
+    # Where that cut is narrower than the score tolerance several sets are correct: compare what
+    # is unique (every neuron clearly above the cut is selected, none clearly below it is) and
+    # require exact equality wherever the cut is wide.
+    cut, tol = srt[cfg.k - 1], 2 * 2e-2
+    chosen = np.zeros(cfg.d_ff, bool)
+    chosen[idx_h] = True
+    assert chosen[want_s > cut * (1 + tol)].all(), layer
+    assert not chosen[want_s < cut * (1 - tol)].any(), layer
+    if margin > 1 + tol:
+        assert np.array_equal(np.sort(idx_h), np.sort(orc.select_heavy(want_s, cfg.k))), layer
+    else:
+        diff = len(np.setxor1d(idx_h, orc.select_heavy(want_s, cfg.k)))
+        st["narrow_cuts"].append((layer, round(float(margin), 5), diff))
+    if layer == 0:
+        assert np.array_equal(np.sort(idx_h), L["planted"])
+        # the full calibration length: 16 384 tokens in four batches, every neuron's score
+        Xc = wl.make_tokens(cfg, cfg.calib_T, wl.gen.S_CALIB)
+        xs = [dev(Xc[i:i + 4096], "bf16") for i in range(0, cfg.calib_T, 4096)]
+        s_full, _, tt = gpu_scores(ff, desc0, Ld, xs, reuse_tiled=True)
+        assert tt == cfg.calib_T
+        del xs
+        acc_f = orc.new_accumulator(cfg.d_ff)
+        for i in range(0, cfg.calib_T, 2048):
+            orc.score_accumulate(acc_f, Xc[i:i + 2048], L["W1"], None, "gelu")
+        want_f = orc.neuron_scores(acc_f, L["W2"])
+        assert_scores_close(s_full.cpu().numpy(), want_f, "bf16", "C5 layer 0, 16384 tokens")
+        i_full, _, _ = ff.select_heavy(s_full, cfg.k)
+        assert np.array_equal(np.sort(i_full.cpu().numpy()), np.sort(orc.select_heavy(want_f, cfg.k)))
+        assert np.array_equal(np.sort(i_full.cpu().numpy()), L["planted"])
+        del Xc
+    # ---- the split of this layer and its forward
+    fac = wl.make_factors(cfg, L, idx_h, layer=layer)
+    desc = desc_for(ff, cfg)
+    split = ff.build_split(desc, Ld["W1"], None, Ld["W2"], idx, {k: dev(v, "bf16") for k, v in fac.items()})
+    sw = {"W1h": L["W1"][:, idx_h].astype(np.float64), "W2h": L["W2"][idx_h, :].astype(np.float64), "Wgh": None}
+
+    def want_for(Xh):
+        return orc.forward_heavy(Xh, sw, "gelu") + orc.forward_remainder_lowrank(Xh, fac, "gelu")
+
+    filler = wl.make_tokens(cfg, cfg.prefill_T - C5_NF, wl.gen.S_EVAL, layer=layer + 1)
+    Xfull = np.concatenate([xn_fwd, filler])
+    Y = guarded_forward(ff, desc, split, dev(Xfull, "bf16"))
+    Yd = guarded_forward(ff, desc, split, dev(xn_fwd[:16], "bf16"))               # decode batch of 16
+    torch.cuda.synchronize()
+    want = want_for(xn_fwd)
+    assert_close(host(Y[:C5_NF]), want, "bf16", f"C5 layer {layer} prefill, oracle stream rows")
+    assert_close(host(Yd), want[:16], "bf16", f"C5 layer {layer} decode B=16")
+    if layer in C5_FULL_ROWS:
+        assert_close(host(Y), np.concatenate([want, want_for(filler)]), "bf16", f"C5 layer {layer} prefill, all rows")
+    # one step of the stack driver on the oracle's stream: norm + layer + residual, fp32
+    x_in = torch.from_numpy(st["x_fwd"].astype(np.float32)).cuda()
+    x_out = ff.stack_forward(desc, [split], x_in.clone())
+    torch.cuda.synchronize()
+    assert_close(host(x_out), st["x_fwd"] + want, "bf16", f"C5 layer {layer} stack step")
+    assert_close(host(x_out) - st["x_fwd"], want, "bf16", f"C5 layer {layer} stack step, update")
+    st["splits"].append(split)
+    # ---- both oracle streams move on (teacher forcing)
+    st["x_fwd"] = st["x_fwd"] + want
+    st["x_cal"] = st["x_cal"] + orc.dense_ffn(xn_cal, L["W1"], L["W2"], None, "gelu")
+    st["done"] = layer + 1
+
+
+@pytest.mark.parametrize("lo,hi", [(0, 8), (8, 16), (16, 24), (24, 32), (32, 40)],
+                         ids=["layers0-7", "layers8-15", "layers16-23", "layers24-31", "layers32-39"])
+def test_c5_opt13b_shape_stack_teacher_forced(ff, lo, hi):
+    cfg = C5
+    st = C5_STATE
+    if not st:
+        st.update({"x_cal": wl.make_tokens(cfg, C5_NC, wl.gen.S_CALIB).astype(np.float64),
+                   "x_fwd": wl.make_tokens(cfg, C5_NF).astype(np.float64), "done": 0, "splits": [],
+                   "narrow_cuts": [], "x0": None})
+        st["x0"] = st["x_fwd"].copy()
+    assert st["done"] == lo, "the layer groups of this test run in order (each starts where the last one stopped)"
+    for layer in range(lo, hi):
+        _c5_layer(ff, layer, st)
+        print(f"[C5 stack] layer {layer} ok", flush=True)
+    torch.cuda.empty_cache()
+
+
+def test_c5_opt13b_shape_stack_free_running(ff):
+    """The 40 splits built above in ONE ffsplit_stack_forward call at T = 4096: the first 64
+    rows start from the oracle's stream and are compared with its end of stack."""
+    cfg = C5
+    st = C5_STATE
+    assert st.get("done") == cfg.n_layers, "needs the 40 teacher-forced layers of the test above"
+    desc = desc_for(ff, cfg)
+    T = cfg.prefill_T
+    x = np.concatenate([st["x0"], wl.make_tokens(cfg, T - C5_NF, wl.gen.S_EVAL, layer=77).astype(np.float64)])
+    xd = torch.from_numpy(x.astype(np.float32)).cuda()
+    g = Guarded(ff.workspace_bytes(desc, ff.WS_STACK, T))
+    ff.stack_forward(desc, st["splits"], xd, workspace=g.view)
+    g.check("stack_forward")
+    got = host(xd[:C5_NF])
+    e = relf(got, st["x_fwd"])
+    print(f"[C5 stack] free-running end of stack, 40 layers: rel-Frobenius {e:.3e} vs the oracle's stream; "
+          f"narrow cuts (layer, score ratio at the cut, size of the symmetric difference to the oracle's set): "
+          f"{st['narrow_cuts']}", flush=True)
+    assert torch.isfinite(xd).all()
+    assert e < 3e-2            # per-layer errors of a few 1e-3 compound over 40 layers (not the graded bar)
+    # a second call on the same input gives the same bits
+    xd2 = torch.from_numpy(x.astype(np.float32)).cuda()
+    ff.stack_forward(desc, st["splits"], xd2)
+    torch.cuda.synchronize()
+    assert torch.equal(xd, xd2)
+    C5_STATE.clear()
+    torch.cuda.empty_cache()
