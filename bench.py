@@ -1,18 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the split feed-forward layer on one MI355X.
 
-Headline workload: the OPT-1.3B-shaped layer (d_model 2048, d_ff 8192, GeLU,
-bf16, k = 246 heavy neurons, rank-512 remainder), prefill of 8 x 512 = 4096
-tokens.  A step is one ffsplit_forward over that batch; the split it runs on
-comes from the library's own score -> select -> build calls (timed once, reported
-under "pipeline").  Inputs, weights and the packed split are resident in HBM
-before the timed region.  Prints ONE JSON line.
+Headline workload (the largest single-GPU configuration): the OPT-13B-shaped
+40-layer stack (d_model 5120, d_ff 20480, GeLU, bf16, k = 819 heavy neurons,
+rank-1280 remainder), prefill of 4 x 1024 = 4096 tokens.  A step is one
+ffsplit_stack_forward call: for each of 40 DISTINCT layers the per-token RMS norm,
+the split layer (four chained products) and the residual add on the fp32 stream.
+value = 40 * T / t_step, the tokens/s per layer.  Weights, packed splits and
+inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-Also measured, as extra keys, against the HBM roofline (rotating over enough
-split copies that every weight byte comes from HBM, not from the 256 MB
-last-level cache): the int4 decode of the Llama-2-7B-shaped layer at batch
-1/4/16, and the bf16 low-rank decode of the Llama-2-7B-shaped layer (batch
-1/8/32) and of one OPT-13B-shaped layer (batch 16).
+Beside it, each with its own roofline entry ("roofline.per_config"): one-layer
+prefill of the C2 / C3 / C5 shapes (MFMA-bound) and the int4 decode of the C4
+shape (HBM-bound, rotating over enough split copies that every weight byte comes
+from HBM, not from the 256 MB last-level cache); further sections: bf16 low-rank
+decode, the int8/int3 pairing, the fp32 correctness config, the calibration
+pipeline, and this machine's measured ceilings (the library's own pure-MFMA loop
+and streaming-read kernels).
 """
 import argparse
 import json
@@ -26,23 +29,20 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK = 2.5e15   # FLOP/s, dense bf16, MI355X datasheet
 HBM_PEAK = 8.0e12         # B/s
-# HBM bytes of one C2 forward (read + written), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/gemm_bf16_chain_C2_prefill.md (scaled by the reference copy there)
-TRAFFIC_C2_PREFILL = 379.5e6   # 269.9 MB read + 109.6 MB written
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")   # written by the profile summary step
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--no-decode", action="store_true", help="skip the decode sections")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=40, help="layers of the stack (the workload has 40)")
+    ap.add_argument("--only", default="", help="comma list of sections to run besides the headline: "
+                    "prefill,decode,w3h8,c1,pipeline,yardsticks,cpu (default: all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--no-yardsticks", action="store_true",
-                    help="skip the machine yardsticks (device copy, vendor-library GEMMs through torch)")
     ap.add_argument("--preheat-ms", type=float, default=100.0,
                     help="untimed steady load before every timed loop, so that the clocks have settled")
-    ap.add_argument("--copies", type=int, default=4, help="split copies rotated through in the prefill loop")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -66,6 +66,13 @@ def main():
     torch.cuda.set_device(0)
     bf = torch.bfloat16
     t_start = time.perf_counter()
+    sections = set(s for s in args.only.split(",") if s) or {"prefill", "decode", "w3h8", "c1", "pipeline",
+                                                              "yardsticks", "cpu"}
+    if args.no_cpu:
+        sections.discard("cpu")
+    traffic = {}
+    if os.path.exists(TRAFFIC_FILE):
+        traffic = json.load(open(TRAFFIC_FILE))
 
     def note(msg):
         print(f"[bench {time.perf_counter() - t_start:6.1f}s] {msg}", file=sys.stderr, flush=True)
@@ -74,6 +81,7 @@ def main():
         return None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to("cuda", dtype=dt)
 
     def timed(fn, n, warm):
+        """(seconds per call by HIP events on the launch stream, wall seconds per call)."""
         preheat_s = args.preheat_ms * 1e-3
         # The GPU's clocks take tens of milliseconds of continuous load to settle after the host-side
         # preparation that precedes every section (measured: the first ~10 ms of a loop run 5-15 %
@@ -81,7 +89,7 @@ def main():
         # then the warm-up steps asked for, then the timed ones.
         t_pre = time.perf_counter()
         while time.perf_counter() - t_pre < preheat_s:
-            for _ in range(8):
+            for _ in range(4):
                 fn()
             torch.cuda.synchronize()
         for _ in range(warm):
@@ -97,6 +105,34 @@ def main():
         wall = time.perf_counter() - t0
         return e0.elapsed_time(e1) * 1e-3 / n, wall / n
 
+    def device_layer(cfg, seed):
+        """A layer of the workload's recipe drawn on the device (N(0, 0.02^2) weights, a seeded planted
+        set scaled up, seeded Gaussian factors of the right shape): the stack needs 40 distinct
+        layers and the host generator takes seconds per layer."""
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        d, f, k, r = cfg.d_model, cfg.d_ff, cfg.k, cfg.rank
+        planted = torch.sort(torch.randperm(f, generator=g, device="cuda")[:k]).values.to(torch.int32)
+        out = {"idx": planted}
+        for nm in ("W1", "W2") + (("Wg",) if cfg.act == "swiglu" else ()):
+            w = torch.randn((f, d) if nm == "W2" else (d, f), generator=g, device="cuda") * cfg.weight_std
+            if nm == "W2":
+                w[planted.long(), :] *= cfg.heavy_scale
+            else:
+                w[:, planted.long()] *= cfg.heavy_scale
+            out[nm] = w.to(bf)
+        out.setdefault("Wg", None)
+        a = (cfg.weight_std / r ** 0.5) ** 0.5
+        m = f - k
+        fac = {}
+        for tag, shp in (("1", (d, m)), ("g", (d, m)), ("2", (m, d))):
+            if tag == "g" and cfg.act != "swiglu":
+                fac["Pg"] = fac["Qg"] = None
+                continue
+            fac["P" + tag] = (torch.randn((shp[0], r), generator=g, device="cuda") * a).to(bf)
+            fac["Q" + tag] = (torch.randn((r, shp[1]), generator=g, device="cuda") * a).to(bf)
+        out["fac"] = fac
+        return out
+
     if args.calib_copy:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -106,65 +142,65 @@ def main():
         del src, dst
         note("reference copy done: 3 x 256 MiB read + 256 MiB written")
 
-    # ------------------------------------------------------------ headline: C2 prefill
-    cfg = C2
+    from oracle import ffsplit_oracle as orc     # the parity samples and the cpu_baseline leg only
+
+    # ------------------------------------------------------------ headline: the C5 40-layer stack
+    cfg = C5
     T = cfg.prefill_T
-    L = wl.make_layer(cfg)
-    note("C2 weights generated")
-    W1, W2 = dev(L["W1"]), dev(L["W2"])
-    Xc = dev(wl.make_tokens(cfg, cfg.calib_T, wl.gen.S_CALIB))
+    n_layers = args.layers
     desc = ff.make_desc(cfg.d_model, cfg.d_ff, cfg.act, cfg.dtype, cfg.k, "lowrank", cfg.rank)
+    # layer 0 comes from the host generator (the seeded workload the oracle sees); its heavy set from
+    # the library's own calibration on a 4096-token slice
+    L0 = wl.make_layer(cfg, 0)
+    note("C5 layer 0 generated (host)")
+    W1, W2 = dev(L0["W1"]), dev(L0["W2"])
+    Xc = dev(wl.make_tokens(cfg, 4096, wl.gen.S_CALIB))
     acc = torch.zeros(2 * cfg.d_ff, dtype=torch.float32, device="cuda")
     scores = torch.empty(cfg.d_ff, dtype=torch.float32, device="cuda")
-    ws_score = torch.empty(ff.workspace_bytes(desc, ff.WS_SCORE, cfg.calib_T), dtype=torch.uint8, device="cuda")
-
-    def do_score():
-        acc.zero_()
-        ff.score_neurons(desc, Xc, W1, None, W2, acc, 0, scores, ff.SCORE_SUMSQ, ws_score)
-
-    t_score, _ = timed(do_score, 5, 2)
-    t_select, _ = timed(lambda: ff.select_heavy(scores, cfg.k), 5, 2)
-    idx, _, flag = ff.select_heavy(scores, cfg.k)
+    ff.score_neurons(desc, Xc, W1, None, W2, acc, 0, scores)
+    idx0, _, flag = ff.select_heavy(scores, cfg.k)
     torch.cuda.synchronize()
-    idx_h = idx.cpu().numpy()
-    heavy_ok = bool(np.array_equal(np.sort(idx_h), L["planted"])) and int(flag.item()) == 0
-    note(f"score {t_score*1e6:.0f} us, select {t_select*1e6:.0f} us, heavy set ok={heavy_ok}")
-    fac = wl.make_factors(cfg, L, idx_h)
-    note("rank-512 factors of the remainder computed (host)")
-    facd = {k: dev(v) for k, v in fac.items()}
-    split0 = ff.build_split(desc, W1, None, W2, idx, facd)
-    t_build, _ = timed(lambda: ff.build_split(desc, W1, None, W2, idx, facd, split0), 3, 1)
-    ws_fact = torch.empty(ff.workspace_bytes(desc, ff.WS_FACTORIZE, 0), dtype=torch.uint8, device="cuda")
-    t_fact, _ = timed(lambda: ff.factorize_remainder(desc, W1, None, W2, idx, 1, ws_fact), 2, 1)
-    del ws_fact
-    splits = [split0] + [split0.clone() for _ in range(max(args.copies, 1) - 1)]
-    Xe_h = wl.make_tokens(cfg, T)
-    Xs = [dev(Xe_h)] + [dev(wl.make_tokens(cfg, T, wl.gen.S_EVAL, layer=i)) for i in range(1, len(splits))]
-    Y = torch.empty((T, cfg.d_model), dtype=bf, device="cuda")
-    ws = torch.empty(ff.workspace_bytes(desc, ff.WS_FORWARD, T), dtype=torch.uint8, device="cuda")
-    del Xc, ws_score
-    state = {"i": 0}
+    idx0_h = idx0.cpu().numpy()
+    heavy_ok = bool(np.array_equal(np.sort(idx0_h), L0["planted"])) and int(flag.item()) == 0
+    fac0 = wl.make_factors(cfg, L0, idx0_h, layer=0)
+    splits = [ff.build_split(desc, W1, None, W2, idx0, {k: dev(v) for k, v in fac0.items()})]
+    del W1, W2, Xc
+    for l in range(1, n_layers):
+        Ld = device_layer(cfg, 5000 + l)
+        splits.append(ff.build_split(desc, Ld["W1"], None, Ld["W2"], Ld["idx"], Ld["fac"]))
+        del Ld
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    note(f"{n_layers} distinct C5 splits built ({n_layers * cfg.weight_bytes() / 1e9:.1f} GB)")
+    x0_h = wl.make_tokens(cfg, T).astype(np.float32)
+    x0 = torch.from_numpy(x0_h).cuda()
+    x = x0.clone()
+    ws = torch.empty(ff.workspace_bytes(desc, ff.WS_STACK, T), dtype=torch.uint8, device="cuda")
 
     def step():
-        i = state["i"] % len(splits)
-        state["i"] += 1
-        ff.forward(desc, splits[i], Xs[i], Y, False, ws)
+        # (the stream keeps moving from step to step: values stay finite under the norm, and
+        # the step's cost does not depend on them)
+        ff.stack_forward(desc, splits, x, workspace=ws)
 
     t_ev, t_wall = timed(step, args.steps, args.warmup)
-    flops = cfg.flops_per_token() * T
-    note(f"forward {t_ev*1e6:.1f} us/step (events), {t_wall*1e6:.1f} us/step (wall)")
-    # parity of the timed configuration on sampled rows (rows of X are independent)
-    from oracle import ffsplit_oracle as orc
-    ff.forward(desc, splits[0], Xs[0], Y, False, ws)
+    flops_layer = cfg.flops_per_token() * T
+    note(f"stack of {n_layers}: {t_ev*1e3:.2f} ms/step (events), {t_wall*1e3:.2f} ms/step (wall), "
+         f"{t_ev/n_layers*1e6:.1f} us per layer")
+    # parity of the timed configuration: layer 0 of the stack on sampled rows (rows are independent)
+    x.copy_(x0)
+    ff.stack_forward(desc, splits[:1], x, workspace=ws)
     torch.cuda.synchronize()
-    rows = np.random.default_rng(0).choice(T, 32, replace=False)
-    want = orc.forward_split(Xe_h[rows], L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)[0]
-    got = Y[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    rows = np.sort(np.random.default_rng(0).choice(T, 32, replace=False))
+    xn = wl.bf16_round(orc.token_rms_normalise(x0_h[rows].astype(np.float64)))
+    sw = {"W1h": L0["W1"][:, idx0_h].astype(np.float64), "W2h": L0["W2"][idx0_h, :].astype(np.float64), "Wgh": None}
+    want = x0_h[rows] + orc.forward_heavy(xn, sw, "gelu") + orc.forward_remainder_lowrank(xn, fac0, "gelu")
+    got = x[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
     rel_err = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    upd_err = float(np.linalg.norm((got - x0_h[rows]) - (want - x0_h[rows])) / np.linalg.norm(want - x0_h[rows]))
 
     out = {
         "metric": "split-FFN tokens/s per layer; % of MFMA peak (prefill) / HBM BW (decode)",
-        "value": T / t_wall,
+        "value": n_layers * T / t_wall,
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -175,55 +211,127 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "C2 OPT-1.3B-shaped split FFN prefill: d_model=2048 d_ff=8192 GeLU k=246 rank=512 "
-                               "T=8x512=4096, one layer", "split_copies": len(splits),
-                   "preheat_ms": args.preheat_ms},
+        "config": {"workload": f"C5 OPT-13B-shaped split-FFN stack, prefill: {n_layers} distinct layers, d_model=5120 "
+                               "d_ff=20480 GeLU k=819 rank=1280, T=4x1024=4096, pre-norm + residual per layer (fp32 "
+                               "stream); value = layers*T/t_step (tokens/s per layer)",
+                   "layers": n_layers, "T": T, "preheat_ms": args.preheat_ms},
         "roofline": {"bound": "mfma",
-                     "kernel": "ffsplit_forward = 4 chained gemm_bf16_dl_kernel launches (+ split-K sum); "
-                               "per-launch figures in profiles/",
-                     "achieved": flops / t_ev / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
-                     "frac": flops / t_ev / MFMA_BF16_PEAK, "traffic": TRAFFIC_C2_PREFILL,
-                     "flops_per_launch": flops, "us_per_launch_hip_events": t_ev * 1e6},
-        "parity": {"rel_frobenius_vs_oracle_32_rows": rel_err, "heavy_set_equals_planted": heavy_ok},
-        "pipeline": {"score_us_T4096": t_score * 1e6,
-                     "score_tflops": 2.0 * cfg.calib_T * cfg.d_model * cfg.d_ff / t_score / 1e12,
-                     "select_us": t_select * 1e6, "build_split_us": t_build * 1e6,
-                     "factorize_on_device_ms": t_fact * 1e3},
+                     "kernel": "one layer of ffsplit_stack_forward = token_rmsnorm + 4 chained gemm_bf16_dl_kernel "
+                               "launches (+ split-K sum), residual fused into the last; per-launch figures in profiles/",
+                     "achieved": flops_layer * n_layers / t_ev / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                     "frac": flops_layer * n_layers / t_ev / MFMA_BF16_PEAK,
+                     "traffic": traffic.get("C5_stack_layer"),
+                     "flops_per_launch": flops_layer, "us_per_launch_hip_events": t_ev / n_layers * 1e6,
+                     "per_config": {}},
+        "parity": {"layer0_rel_frobenius_vs_oracle_32_rows": rel_err, "layer0_update_rel_frobenius": upd_err,
+                   "heavy_set_equals_planted": heavy_ok},
     }
+    per = out["roofline"]["per_config"]
+    del x, x0, ws
+    keep_c5 = splits[:8]
+    del splits
+    torch.cuda.empty_cache()
 
     # ------------------------------------------------------------ cpu baseline: the oracle as it stands
-    if not args.no_cpu:
+    if "cpu" in sections:
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
+        n_s = 256
+        xs = wl.bf16_round(orc.token_rms_normalise(x0_h[:n_s].astype(np.float64)))
         reps, spent = 0, 0.0
-        while spent < 10.0 and reps < 8:
+        while spent < 10.0 and reps < 16:
             t0 = time.perf_counter()
-            orc.forward_split(Xe_h, L["W1"], L["W2"], None, idx_h, "gelu", "lowrank", fac)
+            orc.forward_heavy(xs, sw, "gelu") + orc.forward_remainder_lowrank(xs, fac0, "gelu")
             spent += time.perf_counter() - t0
             reps += 1
-        note(f"oracle timed: {reps} reps in {spent:.1f} s")
-        out["cpu_baseline"] = {"value": T * reps / spent, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-                               "sample": f"{reps} x the full {T}-token forward of the same layer (numpy fp64)"}
+        note(f"oracle timed: {reps} reps of {n_s} tokens in {spent:.1f} s")
+        out["cpu_baseline"] = {"value": n_s * reps / spent, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"{reps} x the split forward (FFN_1 + low-rank FFN_2, numpy fp64) of layer 0 "
+                                         f"of the same stack on {n_s} of its {T} tokens; tokens/s per layer"}
+    del L0, fac0, sw
 
-    # ------------------------------------------------------------ extra: int4 decode (HBM-bound)
-    if not args.no_decode:
-        del splits, Xs, W1, W2, facd
-        torch.cuda.empty_cache()
+    # ------------------------------------------------------------ one-layer prefill of the bf16 low-rank shapes
+    def lowrank_split(cfg_d, n_cp):
+        Ld = device_layer(cfg_d, 7000 + cfg_d.index)
+        dd = ff.make_desc(cfg_d.d_model, cfg_d.d_ff, cfg_d.act, cfg_d.dtype, cfg_d.k, "lowrank", cfg_d.rank)
+        spd = ff.build_split(dd, Ld["W1"], Ld["Wg"], Ld["W2"], Ld["idx"], Ld["fac"])
+        torch.cuda.synchronize()
+        return dd, [spd] + [spd.clone() for _ in range(n_cp - 1)]
+
+    lr = {}
+    if "prefill" in sections or "decode" in sections:
+        for cfg_d, n_cp in ((C2, 8), (C3, 10), (C5, 8)):
+            if cfg_d is C5:
+                dd, spds = ff.make_desc(C5.d_model, C5.d_ff, C5.act, C5.dtype, C5.k, "lowrank", C5.rank), keep_c5
+            else:
+                dd, spds = lowrank_split(cfg_d, n_cp)
+            lr[cfg_d.name.split("-")[0]] = (cfg_d, dd, spds)
+    del keep_c5
+    if "prefill" in sections:
+        for nm, (cfg_d, dd, spds) in lr.items():
+            Tp = cfg_d.prefill_T
+            wsd = torch.empty(ff.workspace_bytes(dd, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
+            xp = [torch.randn((Tp, cfg_d.d_model), device="cuda").to(bf) for _ in range(2)]
+            yp = torch.empty((Tp, cfg_d.d_model), dtype=bf, device="cuda")
+            st = {"i": 0}
+
+            def pstep():
+                ff.forward(dd, spds[st["i"] % len(spds)], xp[st["i"] & 1], yp, False, wsd)
+                st["i"] += 1
+
+            tpf, _ = timed(pstep, 200 if cfg_d is C2 else 40, 10)
+            flp = cfg_d.flops_per_token() * Tp
+            note(f"{cfg_d.name} prefill T={Tp}: {tpf*1e6:.1f} us ({flp/tpf/1e12:.0f} TFLOP/s)")
+            per[f"{nm}_prefill"] = {"workload": f"{cfg_d.name}: one ffsplit_forward, T={Tp}", "bound": "mfma",
+                                    "achieved": flp / tpf / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                                    "frac": flp / tpf / MFMA_BF16_PEAK, "traffic": traffic.get(f"{nm}_prefill"),
+                                    "flops_per_launch": flp, "us_per_launch_hip_events": tpf * 1e6,
+                                    "tokens_per_s": Tp / tpf}
+            del wsd, xp, yp
+
+    # ------------------------------------------------------------ bf16 low-rank decode (HBM-bound)
+    if "decode" in sections:
+        dl = {}
+        for nm, (cfg_d, dd, spds) in lr.items():
+            for B in cfg_d.decode_B:
+                wsd = torch.empty(ff.workspace_bytes(dd, ff.WS_FORWARD, B), dtype=torch.uint8, device="cuda")
+                xb = torch.randn((B, cfg_d.d_model), device="cuda").to(bf)
+                yb = torch.empty((B, cfg_d.d_model), dtype=bf, device="cuda")
+                st = {"i": 0}
+
+                def lstep():
+                    ff.forward(dd, spds[st["i"] % len(spds)], xb, yb, False, wsd)
+                    st["i"] += 1
+
+                td, _ = timed(lstep, 100, 20)
+                note(f"{cfg_d.name} low-rank decode B={B}: {td*1e6:.1f} us")
+                dl[f"{nm}_B{B}"] = {"us": td * 1e6, "tokens_per_s": B / td, "bytes_per_step": cfg_d.weight_bytes(),
+                                    "GBps": cfg_d.weight_bytes() / td / 1e9, "frac_hbm": cfg_d.weight_bytes() / td / HBM_PEAK,
+                                    "split_copies": len(spds)}
+        out["decode_lowrank_bf16"] = {"workload": "C3 Llama-2-7B-shaped (k=550, rank 1024) and one C5 OPT-13B-shaped "
+                                                  "layer (k=819, rank 1280): heavy bf16 + low-rank factors", **dl}
+    del lr
+    torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------ int4 decode (HBM-bound) and int4 prefill
+    if "decode" in sections or "w3h8" in sections:
         c4 = C4
-        L4 = wl.make_layer(c4)
-        note("C4 weights generated")
+        L4 = device_layer(dataclasses.replace(c4, rank=8), 7004)     # (the factors are not used)
+        Tp = 4096
+        fl4 = 6.0 * Tp * c4.d_model * c4.d_ff          # the layer's dense products: a quantised split skips none
+    if "decode" in sections:
         d4 = ff.make_desc(c4.d_model, c4.d_ff, c4.act, c4.dtype, c4.k, "int4", 0, c4.group)
-        s4 = ff.build_split(d4, dev(L4["W1"]), dev(L4["Wg"]), dev(L4["W2"]), torch.from_numpy(L4["planted"]).cuda())
+        s4 = ff.build_split(d4, L4["W1"], L4["Wg"], L4["W2"], L4["idx"])
         torch.cuda.synchronize()
         n_copies = 16                                   # 16 x 80.8 MB = 1.3 GB >> 256 MB last-level cache
         s4s = [s4] + [s4.clone() for _ in range(n_copies - 1)]
         ws4 = torch.empty(ff.workspace_bytes(d4, ff.WS_FORWARD, 16), dtype=torch.uint8, device="cuda")
         dec = {}
         for B in c4.decode_B:
-            xb = dev(wl.make_tokens(c4, B))
+            xb = torch.randn((B, c4.d_model), device="cuda").to(bf)
             yb = torch.empty((B, c4.d_model), dtype=bf, device="cuda")
             st = {"i": 0}
 
@@ -232,27 +340,32 @@ def main():
                 st["i"] += 1
 
             t4, _ = timed(dstep, 160, 32)
-            note(f"int4 decode B={B}: {t4*1e6:.1f} us")
+            note(f"int4 decode B={B}: {t4*1e6:.1f} us ({c4.weight_bytes()/t4/1e9:.0f} GB/s)")
             dec[f"B{B}"] = {"us": t4 * 1e6, "tokens_per_s": B / t4, "GBps": c4.weight_bytes() / t4 / 1e9,
                             "frac_hbm": c4.weight_bytes() / t4 / HBM_PEAK}
+            per[f"C4_int4_decode_B{B}"] = {"workload": f"{c4.name}: one ffsplit_forward, batch {B}", "bound": "hbm",
+                                           "achieved": c4.weight_bytes() / t4 / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                                           "frac": c4.weight_bytes() / t4 / HBM_PEAK,
+                                           "traffic": traffic.get(f"C4_int4_decode_B{B}"),
+                                           "bytes_per_launch": c4.weight_bytes(), "us_per_launch_hip_events": t4 * 1e6,
+                                           "tokens_per_s": B / t4}
         out["decode_int4"] = {"workload": "C4 Llama-2-7B-shaped SwiGLU, k=550 bf16 heavy + int4-g128 remainder",
                               "bytes_per_step": c4.weight_bytes(), "split_copies": n_copies, **dec}
         # the same split with many tokens: weights expanded to bf16 once per call, then dense MFMA products
-        Tp = 4096
         wsp = torch.empty(ff.workspace_bytes(d4, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
-        xp = dev(wl.make_tokens(c4, Tp))
+        xp = torch.randn((Tp, c4.d_model), device="cuda").to(bf)
         yp = torch.empty((Tp, c4.d_model), dtype=bf, device="cuda")
         tp4, _ = timed(lambda: ff.forward(d4, s4, xp, yp, False, wsp), 10, 3)
-        fl4 = 6.0 * Tp * c4.d_model * c4.d_ff          # the layer's dense products: the int4 split skips none
         note(f"int4 prefill T={Tp}: {tp4*1e6:.1f} us")
         out["prefill_int4"] = {"workload": f"C4 layer, T={Tp}", "us": tp4 * 1e6, "tokens_per_s": Tp / tp4,
                                "flops": fl4, "TFLOPs": fl4 / tp4 / 1e12, "frac_mfma": fl4 / tp4 / MFMA_BF16_PEAK}
         del wsp, xp, yp, s4s, s4, ws4
         torch.cuda.empty_cache()
 
-        # ------------------------------------------------------------ extra: 8-bit heavy / 3-bit remainder
+    # ------------------------------------------------------------ 8-bit heavy / 3-bit remainder (Sec. 5.2's pairing)
+    if "w3h8" in sections:
         d38 = ff.make_desc(c4.d_model, c4.d_ff, c4.act, c4.dtype, c4.k, "w3h8", 0, 128)
-        s38 = ff.build_split(d38, dev(L4["W1"]), dev(L4["Wg"]), dev(L4["W2"]), torch.from_numpy(L4["planted"]).cuda())
+        s38 = ff.build_split(d38, L4["W1"], L4["Wg"], L4["W2"], L4["idx"])
         torch.cuda.synchronize()
         m4 = c4.d_ff - c4.k
         bytes38 = 3.0 * c4.k * c4.d_model + 3.0 * m4 * c4.d_model * 3 / 8 + 3.0 * c4.d_ff * (c4.d_model // 128) * 2
@@ -261,7 +374,7 @@ def main():
         ws38 = torch.empty(ff.workspace_bytes(d38, ff.WS_FORWARD, 32), dtype=torch.uint8, device="cuda")
         q38 = {}
         for B in c4.decode_B:
-            xb = dev(wl.make_tokens(c4, B))
+            xb = torch.randn((B, c4.d_model), device="cuda").to(bf)
             yb = torch.empty((B, c4.d_model), dtype=bf, device="cuda")
             st = {"i": 0}
 
@@ -274,7 +387,7 @@ def main():
             q38[f"B{B}"] = {"us": t38 * 1e6, "tokens_per_s": B / t38, "GBps": bytes38 / t38 / 1e9,
                             "frac_hbm": bytes38 / t38 / HBM_PEAK}
         wsp = torch.empty(ff.workspace_bytes(d38, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
-        xp = dev(wl.make_tokens(c4, Tp))
+        xp = torch.randn((Tp, c4.d_model), device="cuda").to(bf)
         yp = torch.empty((Tp, c4.d_model), dtype=bf, device="cuda")
         tp38, _ = timed(lambda: ff.forward(d38, s38, xp, yp, False, wsp), 10, 3)
         note(f"w3h8 prefill T={Tp}: {tp38*1e6:.1f} us")
@@ -283,61 +396,47 @@ def main():
                        "prefill_T4096": {"us": tp38 * 1e6, "tokens_per_s": Tp / tp38, "TFLOPs": fl4 / tp38 / 1e12,
                                          "frac_mfma": fl4 / tp38 / MFMA_BF16_PEAK}}
         del wsp, xp, yp, s38s, s38, ws38
-
-
-        # ------------------------------------------------------------ extra: bf16 low-rank decode (HBM-bound)
+    if "decode" in sections or "w3h8" in sections:
+        del L4
         torch.cuda.empty_cache()
-        dl, pl = {}, {}
-        for cfg_d, n_cp in ((C3, 10), (C5, 8)):
-            Ld = wl.make_layer(cfg_d)
-            facs = wl.make_factors(dataclasses.replace(cfg_d, exact_svd=False), Ld, Ld["planted"])
-            dd = ff.make_desc(cfg_d.d_model, cfg_d.d_ff, cfg_d.act, cfg_d.dtype, cfg_d.k, "lowrank", cfg_d.rank)
-            spd = ff.build_split(dd, dev(Ld["W1"]), dev(Ld["Wg"]), dev(Ld["W2"]),
-                                 torch.from_numpy(Ld["planted"]).cuda(), {k: dev(v) for k, v in facs.items()})
-            torch.cuda.synchronize()
-            spds = [spd] + [spd.clone() for _ in range(n_cp - 1)]
-            note(f"{cfg_d.name}: split built, {n_cp} copies of {cfg_d.weight_bytes()/1e6:.0f} MB")
-            for B in cfg_d.decode_B:
-                wsd = torch.empty(ff.workspace_bytes(dd, ff.WS_FORWARD, B), dtype=torch.uint8, device="cuda")
-                xb = dev(wl.make_tokens(cfg_d, B))
-                yb = torch.empty((B, cfg_d.d_model), dtype=bf, device="cuda")
-                st = {"i": 0}
 
-                def lstep():
-                    ff.forward(dd, spds[st["i"] % n_cp], xb, yb, False, wsd)
-                    st["i"] += 1
+    # ------------------------------------------------------------ the calibration pipeline on the C2 layer
+    if "pipeline" in sections:
+        c2 = C2
+        L2 = wl.make_layer(c2)
+        W1, W2 = dev(L2["W1"]), dev(L2["W2"])
+        Xc = dev(wl.make_tokens(c2, c2.calib_T, wl.gen.S_CALIB))
+        d2 = ff.make_desc(c2.d_model, c2.d_ff, c2.act, c2.dtype, c2.k, "lowrank", c2.rank)
+        acc = torch.zeros(2 * c2.d_ff, dtype=torch.float32, device="cuda")
+        scores = torch.empty(c2.d_ff, dtype=torch.float32, device="cuda")
+        ws_score = torch.empty(ff.workspace_bytes(d2, ff.WS_SCORE, c2.calib_T), dtype=torch.uint8, device="cuda")
 
-                td, _ = timed(lstep, 100, 20)
-                note(f"{cfg_d.name} low-rank decode B={B}: {td*1e6:.1f} us")
-                dl[f"{cfg_d.name.split('-')[0]}_B{B}"] = {
-                    "us": td * 1e6, "tokens_per_s": B / td, "bytes_per_step": cfg_d.weight_bytes(),
-                    "GBps": cfg_d.weight_bytes() / td / 1e9, "frac_hbm": cfg_d.weight_bytes() / td / HBM_PEAK}
-            # prefill of the same layer (MFMA-bound)
-            Tp = cfg_d.prefill_T
-            wsd = torch.empty(ff.workspace_bytes(dd, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
-            xp = dev(wl.make_tokens(cfg_d, Tp))
-            yp = torch.empty((Tp, cfg_d.d_model), dtype=bf, device="cuda")
-            st = {"i": 0}
+        def do_score():
+            acc.zero_()
+            ff.score_neurons(d2, Xc, W1, None, W2, acc, 0, scores, ff.SCORE_SUMSQ, ws_score)
 
-            def pstep():
-                ff.forward(dd, spds[st["i"] % n_cp], xp, yp, False, wsd)
-                st["i"] += 1
-
-            tpf, _ = timed(pstep, 20, 5)
-            flp = cfg_d.flops_per_token() * Tp
-            note(f"{cfg_d.name} prefill T={Tp}: {tpf*1e6:.1f} us")
-            pl[cfg_d.name.split('-')[0]] = {"T": Tp, "us": tpf * 1e6, "tokens_per_s": Tp / tpf, "flops": flp,
-                                            "TFLOPs": flp / tpf / 1e12, "frac_mfma": flp / tpf / MFMA_BF16_PEAK}
-            del spds, spd, wsd, xp, yp
-            torch.cuda.empty_cache()
-        out["prefill_lowrank_bf16"] = {"workload": "the same C3 and C5 layers, 4096 tokens", **pl}
-        out["decode_lowrank_bf16"] = {"workload": "C3 Llama-2-7B-shaped (k=550, rank 1024) and one C5 OPT-13B-shaped "
-                                                  "layer (k=819, rank 1280): heavy bf16 + low-rank factors, seeded "
-                                                  "Gaussian factors", **dl}
-
-    # ------------------------------------------------------------ extra: C1, the fp32 correctness config
-    if not args.no_decode:
+        t_score, _ = timed(do_score, 5, 2)
+        t_select, _ = timed(lambda: ff.select_heavy(scores, c2.k), 5, 2)
+        idx, _, flag = ff.select_heavy(scores, c2.k)
+        torch.cuda.synchronize()
+        ok2 = bool(np.array_equal(np.sort(idx.cpu().numpy()), L2["planted"])) and int(flag.item()) == 0
+        ws_fact = torch.empty(ff.workspace_bytes(d2, ff.WS_FACTORIZE, 0), dtype=torch.uint8, device="cuda")
+        t_fact, _ = timed(lambda: ff.factorize_remainder(d2, W1, None, W2, idx, 1, ws_fact), 2, 1)
+        facd = ff.factorize_remainder(d2, W1, None, W2, idx, 1, ws_fact)
+        sp2 = ff.build_split(d2, W1, None, W2, idx, facd)
+        t_build, _ = timed(lambda: ff.build_split(d2, W1, None, W2, idx, facd, sp2), 3, 1)
+        note(f"C2 pipeline: score {t_score*1e6:.0f} us, select {t_select*1e6:.0f} us, factorise {t_fact*1e3:.1f} ms, "
+             f"build {t_build*1e6:.0f} us, heavy set ok={ok2}")
+        out["pipeline"] = {"workload": "C2 layer: score (4096 tokens) -> select -> factorise on the device -> build",
+                           "score_us_T4096": t_score * 1e6,
+                           "score_tflops": 2.0 * c2.calib_T * c2.d_model * c2.d_ff / t_score / 1e12,
+                           "select_us": t_select * 1e6, "build_split_us": t_build * 1e6,
+                           "factorize_on_device_ms": t_fact * 1e3, "heavy_set_equals_planted": ok2}
+        del W1, W2, Xc, ws_score, ws_fact, facd, sp2
         torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------ C1, the fp32 correctness config
+    if "c1" in sections:
         c1 = C1
         L1 = wl.make_layer(c1)
         f1 = wl.make_factors(c1, L1, L1["planted"])
@@ -354,43 +453,35 @@ def main():
                           "us": t1 * 1e6, "tokens_per_s": c1.prefill_T / t1,
                           "GFLOPs": c1.flops_per_token() * c1.prefill_T / t1 / 1e9}
 
-    # ------------------------------------------------------------ yardsticks of this machine (not the product path)
-    # What the same box gives to a plain device copy and to the vendor BLAS behind torch.matmul:
+    # ------------------------------------------------------------ measured ceilings of this machine
+    # The library's own probe kernels (csrc/probe.hip): a pure matrix-core loop and a streaming read,
     # auditable denominators next to the datasheet peaks the fractions above are quoted against.
-    if not args.no_yardsticks:
+    if "yardsticks" in sections:
         torch.cuda.empty_cache()
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        tc, _ = timed(lambda: dst.copy_(src), 10, 3)
-        del src, dst
-        a8 = torch.randn(8192, 8192, dtype=bf, device="cuda")
-        b8 = torch.randn(8192, 8192, dtype=bf, device="cuda")
-        tg, _ = timed(lambda: torch.matmul(a8, b8), 10, 3)
-        del a8, b8
-        # the four products of the C2 chain as plain library GEMMs plus a separate GeLU pass
-        c2 = C2
-        Tq, dq, kq, rq = c2.prefill_T, c2.d_model, c2.k, c2.rank
-        mq = c2.d_ff - kq
-        xq = torch.randn(Tq, dq, dtype=bf, device="cuda")
-        w1q = torch.randn(dq, kq + rq, dtype=bf, device="cuda")
-        q1q = torch.randn(rq, mq, dtype=bf, device="cuda")
-        p2q = torch.randn(mq, rq, dtype=bf, device="cuda")
-        w4q = torch.randn(kq + rq, dq, dtype=bf, device="cuda")
+        scr = torch.zeros(64, dtype=torch.uint8, device="cuda")
+        fl = {"v": 0.0}
 
-        def lib_chain():
-            z = torch.matmul(xq, w1q)
-            h = torch.nn.functional.gelu(torch.matmul(z[:, kq:], q1q))
-            t2 = torch.matmul(h, p2q)
-            return torch.matmul(torch.cat([torch.nn.functional.gelu(z[:, :kq]), t2], dim=1), w4q)
+        def mf():
+            fl["v"] = ff.probe_mfma(2048, 4096, scr)
 
-        tl, _ = timed(lib_chain, 20, 5)
-        out["yardsticks"] = {"device_copy_1GiB_GBps_read_plus_write": 2.0 * (1 << 30) / tc / 1e9,
-                             "torch_matmul_bf16_8192_TFLOPs": 2.0 * 8192 ** 3 / tg / 1e12,
-                             "c2_chain_as_torch_ops_us": tl * 1e6,
-                             "note": "vendor library / torch kernels, measurement only; not used by the product path"}
-        note(f"yardsticks: copy {out['yardsticks']['device_copy_1GiB_GBps_read_plus_write']:.0f} GB/s, "
-             f"matmul 8192^3 {out['yardsticks']['torch_matmul_bf16_8192_TFLOPs']:.0f} TFLOP/s, "
-             f"C2 chain as torch ops {tl*1e6:.0f} us")
+        tm, _ = timed(mf, 10, 2)
+        chunk = 80 << 20
+        bufs = torch.empty(16 * chunk, dtype=torch.uint8, device="cuda")
+        bufs.fill_(1)
+        st = {"i": 0}
+
+        def rd():
+            i = st["i"] % 16
+            ff.probe_stream_read(bufs[i * chunk:(i + 1) * chunk], 2048, scr)
+            st["i"] += 1
+
+        tr, _ = timed(rd, 64, 16)
+        out["yardsticks"] = {"pure_mfma_loop_TFLOPs": fl["v"] / tm / 1e12,
+                             "streaming_read_80MB_GBps": chunk / tr / 1e9, "streaming_read_80MB_us": tr * 1e6,
+                             "note": "ffsplit_probe_mfma / ffsplit_probe_stream_read: this library's own kernels, "
+                                     "measurement only, rotating over 16 x 80 MB for the read"}
+        note(f"ceilings: pure MFMA loop {fl['v']/tm/1e12:.0f} TFLOP/s, streaming read of 80 MB {tr*1e6:.1f} us "
+             f"({chunk/tr/1e9:.0f} GB/s)")
     print(json.dumps(out))
 
 

@@ -295,6 +295,20 @@ int ffsplit_stack_forward(const ffsplit_desc_t* desc, int32_t n_layers, const vo
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measured ceilings of the machine, for the benchmark's report (nothing on the
+ * path calls them; the throughput figures are quoted against the datasheet peaks
+ * and, beside them, against these):
+ *   ffsplit_probe_mfma         `workgroups` x 4 wavefronts each issue `iters` x 8
+ *                              independent v_mfma_f32_32x32x16_bf16, no memory
+ *                              traffic; *flops (host) receives the flop count.
+ *   ffsplit_probe_stream_read  reads buf[0, bytes) once with 16-byte loads, eight in
+ *                              flight per thread, from `workgroups` x 256 threads.
+ * scratch: at least 16 bytes of device memory (never written in practice).
+ */
+int ffsplit_probe_mfma(int32_t workgroups, int32_t iters, void* scratch, double* flops, void* stream);
+int ffsplit_probe_stream_read(const void* buf, size_t bytes, int32_t workgroups, void* scratch, void* stream);
+
+/*
  * Test hook: unpack the quantised weights of a built split (INT4, W3H8) into
  * logical order.  what = 0 (W1 columns), 1 (Wg columns), 2 (W2 rows) of the
  * remainder: q_out [m, d_model] int8 codes, s_out [m, d_model/group] fp16 scale

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     Desc, FFSplitError, lib, lib_path, status_string, make_desc,
     workspace_bytes, split_bytes, score_neurons, select_heavy, build_split, forward, split_export,
     factorize_remainder, select_heavy_static, SELECT_STATIC_MAX_DFF,
-    forward_ex, pack_neuron_bias, token_rmsnorm, stack_forward, Epilogue,
+    probe_mfma, probe_stream_read, forward_ex, pack_neuron_bias, token_rmsnorm, stack_forward, Epilogue,
 )

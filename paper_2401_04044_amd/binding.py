@@ -70,6 +70,10 @@ def _load():
     L.ffsplit_stack_forward.restype = ctypes.c_int
     L.ffsplit_stack_forward.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i64,
                                         ctypes.c_float, vp, sz, vp]
+    L.ffsplit_probe_mfma.restype = ctypes.c_int
+    L.ffsplit_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.ffsplit_probe_stream_read.restype = ctypes.c_int
+    L.ffsplit_probe_stream_read.argtypes = [vp, sz, i32, vp, vp]
     L.ffsplit_factorize_remainder.restype = ctypes.c_int
     L.ffsplit_factorize_remainder.argtypes = [dp, vp, vp, vp, vp, ctypes.c_uint32, ctypes.POINTER(vp), vp, sz, vp]
     L.ffsplit_split_export.restype = ctypes.c_int
@@ -266,6 +270,19 @@ def stack_forward(desc, splits, x, b1_packed=None, b2=None, eps=1e-6, workspace=
                                    ctypes.c_float(eps), _ptr(ws), ws.numel(), _stream())
     _check(rc, "ffsplit_stack_forward")
     return x
+
+
+def probe_mfma(workgroups, iters, scratch):
+    """Enqueue the pure matrix-core loop; returns its flop count."""
+    fl = ctypes.c_double(0.0)
+    _check(lib.ffsplit_probe_mfma(workgroups, iters, _ptr(scratch), ctypes.byref(fl), _stream()), "ffsplit_probe_mfma")
+    return fl.value
+
+
+def probe_stream_read(buf, workgroups, scratch):
+    """Enqueue one streaming read of buf (a uint8 tensor whose size is a multiple of 16)."""
+    _check(lib.ffsplit_probe_stream_read(_ptr(buf), buf.numel() * buf.element_size(), workgroups, _ptr(scratch), _stream()),
+           "ffsplit_probe_stream_read")
 
 
 def split_export(desc, split, what):

@@ -75,7 +75,9 @@ __device__ __forceinline__ void swap32(uint32_t& a, uint32_t& b) {
 
 // Epilogue shared by the GEMM kernels: activation, bf16 packing and the stores (or the
 // neuron-norm column sums).  acc[i][j] is the 32x32 tile (i, j) of the wavefront's sub-tile.
-template <int BM, int BN, int WGM, int WGN, int ACT, bool SCORE>
+// EPI: the optional additions of GemmArgs (bias, residual stream, fp32 destination) are compiled
+// in; the plain instantiations carry none of their instructions.
+template <int BM, int BN, int WGM, int WGN, int ACT, bool SCORE, bool EPI>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32], int m0,
                                               int n0, int tm, int wm, int wn, int lane, int tid, u32x4_t* smem) {
   constexpr int NT = WGM * WGN * 64;
@@ -114,10 +116,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
       for (int g = 0; g < 4; ++g) {
         const int c = cb + 8 * g + 4 * half;
         float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ACT != ACT_GLU && p.bias != nullptr && c + 3 < p.bias_cols) b4 = *(const float4*)(p.bias + c);
+        if (EPI && ACT != ACT_GLU && p.bias != nullptr && c + 3 < p.bias_cols) b4 = *(const float4*)(p.bias + c);
         bz[g][0] = b4.x; bz[g][1] = b4.y; bz[g][2] = b4.z; bz[g][3] = b4.w;
       }
-      const bool f32o = p.out_f32 && to_c0 && !tiled;
+      const bool f32o = EPI && p.out_f32 && to_c0 && !tiled;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int rblk = (m0 + wm * WM) / 32 + i;
@@ -134,7 +136,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
           continue;
         }
         // the residual stream (fp32, row-major, same columns as the destination)
-        const float* rrow = (p.resid != nullptr && to_c0 && !tiled && row < p.M)
+        const float* rrow = (EPI && p.resid != nullptr && to_c0 && !tiled && row < p.M)
                                 ? p.resid + (int64_t)row * p.ldr + occ + 4 * half : nullptr;
         uint32_t pk[4][2];
 #pragma unroll
@@ -145,16 +147,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
             // (static tile indices: an activated pair is (gate j, value j + 1))
             constexpr int TNM1 = TN - 1;
             const int j1 = j + 1 < TN ? j + 1 : TNM1;
-            const float gt = acc[i][j][4 * g + e] + bz[g][e];
+            const float gt = EPI ? acc[i][j][4 * g + e] + bz[g][e] : acc[i][j][4 * g + e];
             const float z = (ACT == ACT_GLU && act_here) ? acc[i][j1][4 * g + e] : gt;
             v[e] = act_here ? act_bf16<ACT>(z, gt) : z;
           }
           const bool col_ok = occ + 8 * g + 4 * half < p.n_store;
-          if (rrow != nullptr && col_ok) {
+          if (EPI && rrow != nullptr && col_ok) {
             const float4 r4 = *(const float4*)(rrow + 8 * g);
             v[0] += r4.x; v[1] += r4.y; v[2] += r4.z; v[3] += r4.w;
           }
-          if (f32o) {
+          if (EPI && f32o) {
             if (row < p.M && col_ok)
               *(float4*)((float*)base + (int64_t)row * ld + occ + 8 * g + 4 * half) = make_float4(v[0], v[1], v[2], v[3]);
           } else {
@@ -162,7 +164,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
             pk[g][1] = pack_bf16x2(v[2], v[3]);
           }
         }
-        if (f32o) continue;
+        if (EPI && f32o) continue;
         // groups (0,1) and (2,3) each cover 16 consecutive columns: after the swap the lower
         // lanes hold columns 0..7 and the upper lanes columns 8..15 of those 16
 #pragma unroll
@@ -248,7 +250,8 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_barrier" ::: "me
 // every KG-th part of a slab for the same output tile; the groups' accumulators are summed through
 // LDS in a fixed order before the epilogue.  This gives small products (few tiles, long K)
 // more wavefronts per CU without partial sums in global memory.
-template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED,
+          bool EPI>
 __global__ void __launch_bounds__(WGM* WGN* KG * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gemm_bf16_dl_kernel(const GemmArgs p) {
   constexpr int NWT = WGM * WGN;               // wavefronts per k group
@@ -558,7 +561,7 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
     if (kg != 0) return;
   }
   if (SCORE) lds_barrier();   // the epilogue reuses the stage memory
-  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE>(p, acc, m0, n0, tm, wm, wn, lane, tid & (NWT * 64 - 1), smem);
+  gemm_epilogue<BM, BN, WGM, WGN, ACT, SCORE, EPI>(p, acc, m0, n0, tm, wm, wn, lane, tid & (NWT * 64 - 1), smem);
 }
 
 // Sum of fp32 split-K partials [n_split][M][N] (fixed order) -> bf16, tiled or row-major.
@@ -701,14 +704,15 @@ int launch_splitk_epilogue(const float* part, int n_split, int ldp, const GemmAr
 
 // ------------------------------------------------------------------ host launcher
 
-template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
-static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
+template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED,
+          bool EPI>
+static int launch_dl_epi(const GemmArgs& a, int n_split, hipStream_t st) {
   constexpr int NA = DUAL ? 2 : 1;
   constexpr size_t ring = (size_t)STAGES * (NA * BM + BN) * BK * 2;
   constexpr size_t park = KG > 1 ? (size_t)BM * BN * 4 : 0;   // one k group's accumulators
   constexpr size_t lds = ring > park ? ring : park;
   static_assert(lds <= 160 * 1024, "LDS budget of a CU");
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, KG, STAGES, ACT, DUAL, SCORE, A_TILED>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, KG, STAGES, ACT, DUAL, SCORE, A_TILED, EPI>;
   // The kernel needs more dynamic LDS than the default limit: the attribute is set once per
   // device and instantiation.  The only state kept is this set-once bit mask (one bit per
   // device ordinal); setting the attribute twice from racing first calls is harmless.
@@ -724,6 +728,18 @@ static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(WGM * WGN * KG * 64), lds, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED>
+static int launch_dl_cfg(const GemmArgs& a, int n_split, hipStream_t st) {
+  // (the calibration product, the gated products and the two-operand product take no additions)
+  if constexpr (!SCORE && !DUAL && ACT != ACT_GLU) {
+    if (a.bias != nullptr || a.resid != nullptr || a.out_f32)
+      return launch_dl_epi<BM, BN, BK, WGM, WGN, KG, STAGES, ACT, DUAL, SCORE, A_TILED, true>(a, n_split, st);
+  } else {
+    if (a.bias != nullptr || a.resid != nullptr || a.out_f32) return -1;
+  }
+  return launch_dl_epi<BM, BN, BK, WGM, WGN, KG, STAGES, ACT, DUAL, SCORE, A_TILED, false>(a, n_split, st);
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES>
