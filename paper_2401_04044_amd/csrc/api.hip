@@ -108,7 +108,14 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.group_m = 1;   // X is the large operand: its row tiles stay within one XCD
     g.bias = ep.b1; g.bias_cols = ep.b1 ? acted : 0;   // the activated neurons' biases (packed order)
     // (few tiles: eight wavefronts on 64-deep slabs, whose row-major gather takes whole cache lines)
-    const int wide = fill256(M, L.n1) >= 50 ? GEMM_256x256 : (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_KSPLIT);
+    int wide = fill256(M, L.n1) >= 50 ? GEMM_256x256 : (L.n1 >= 4096 ? GEMM_256x128 : GEMM_128x128_KSPLIT);
+    // A product with fewer 256 x 256 tiles than CUs takes one tile's time whatever the count: where
+    // 128 x 320 tiles still fit one round, each CU's share is 0.63 of that (C5: 144 -> 224 tiles,
+    // 128 -> 116 us).  Not for gated layers (a wave tile of five column blocks cannot hold pairs).
+    if (!glu && wide == GEMM_256x256) {
+      const int t256 = ((M + 255) / 256) * ((L.n1 + 255) / 256), t320 = ((M + 127) / 128) * ((L.n1 + 319) / 320);
+      if (t256 <= 256 && t320 <= 256) wide = GEMM_128x320;
+    }
     FFS_TRY(run(g, act, big_m ? wide : GEMM_128x128, 1));
   }
   if (rem_lr) {
@@ -134,7 +141,9 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     if (w.g3_split > 1 && !small_m) {
       float* part = (float*)(ws + w.off_kpart);
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
-      FFS_TRY(run(g, ACT_NONE, big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128, w.g3_split));
+      int g3s = big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128;
+      if (w.g3_wide == 2) g3s = GEMM_256x320;
+      FFS_TRY(run(g, ACT_NONE, g3s, w.g3_split));
       FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, L.tiled, st,
                                    bf16 ? 0 : 1));
     } else {
@@ -153,7 +162,14 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
       g.bias = ep.b2; g.bias_cols = ep.b2 ? dm : 0;
       g.resid = ep.resid; g.ldr = dm; g.out_f32 = bf16 ? ep.out_f32 : 0;
     }
-    return run(g, ACT_NONE, (big_m && fill256(M, dm) >= 90) ? GEMM_256x256 : GEMM_128x128, 1);
+    int shp = (big_m && fill256(M, dm) >= 90) ? GEMM_256x256 : GEMM_128x128;
+    // 256 x 320 tiles where they fill whole rounds of the 256 CUs and 256 x 256 tiles do not
+    // (C5: d_model 5120 = 16 x 320, 4096 rows: exactly 256 tiles; 107 -> 83 us)
+    if (big_m && shp == GEMM_128x128 && dm % 320 == 0) {
+      const int t320 = ((M + 255) / 256) * (dm / 320);
+      if (100 * t320 / (256 * ((t320 + 255) / 256)) >= 90) shp = GEMM_256x320;
+    }
+    return run(g, ACT_NONE, shp, 1);
   };
   if (L.k4 > 0) {
     FFS_TRY(down(Y, 0, L.k4, true));

@@ -250,9 +250,14 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_barrier" ::: "me
 // every KG-th part of a slab for the same output tile; the groups' accumulators are summed through
 // LDS in a fixed order before the epilogue.  This gives small products (few tiles, long K)
 // more wavefronts per CU without partial sums in global memory.
+// wavefronts per SIMD the kernel is compiled for: a wave tile of 16 or more 32 x 32 accumulator
+// tiles (256+ registers) runs alone on its SIMD, with 512 registers per lane
+constexpr int gemm_waves_per_simd(int wm, int wn) { return (wm / 32) * (wn / 32) >= 16 ? 1 : 2; }
+
 template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT, bool DUAL, bool SCORE, bool A_TILED,
           bool EPI>
-__global__ void __launch_bounds__(WGM* WGN* KG * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(WGM* WGN* KG * 64)
+    __attribute__((amdgpu_waves_per_eu(gemm_waves_per_simd(BM / WGM, BN / WGN), gemm_waves_per_simd(BM / WGM, BN / WGN))))
 gemm_bf16_dl_kernel(const GemmArgs p) {
   constexpr int NWT = WGM * WGN;               // wavefronts per k group
   constexpr int NW = NWT * KG;
@@ -263,10 +268,14 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
   constexpr int KS = KB / KG;                  // k steps of a slab per wavefront
   constexpr int A_BLK = NA * (BM / 32) * KB;   // 1 KiB blocks of one slab
   constexpr int B_BLK = (BN / 32) * KB;
-  constexpr int LA = A_BLK / NW, LB = B_BLK / NW, LPW = LA + LB;   // loads per wavefront and slab
-  constexpr int STAGE = (A_BLK + B_BLK) * 64;  // 16-byte chunks per stage
+  // loads per wavefront and slab; where the weights' blocks do not divide over the wavefronts the
+  // last round is padded with repeats of the tile's last row block, which land in spare slots
+  // that nothing reads (every wavefront then issues the same number of loads, which the
+  // wait counts below rely on)
+  constexpr int LA = A_BLK / NW, LB = (B_BLK + NW - 1) / NW, LPW = LA + LB;
+  constexpr int STAGE = (A_BLK + LB * NW) * 64;  // 16-byte chunks per stage
   constexpr bool SWAP = !SCORE;
-  static_assert(A_BLK % NW == 0 && B_BLK % NW == 0, "operand blocks must divide over the wavefronts");
+  static_assert(A_BLK % NW == 0, "the tokens' blocks must divide over the wavefronts");
   static_assert(KB % KG == 0 && (KS == 1 || KS == 2), "one or two k steps per wavefront and slab");
   static_assert(STAGES >= 2 && (STAGES - 1) * LPW + LPW <= 63, "loads in flight must fit the counter");
   static_assert(ACT != ACT_GLU || (TN % 2 == 0), "GLU needs paired column blocks per wave");
@@ -344,7 +353,7 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
     const int b = wave + i * NW;
-    const int rb = b / KB, kb = b % KB;
+    const int rb = min(b / KB, BN / 32 - 1), kb = b % KB;
     int grb = n0 / 32 + rb;
     grb = grb <= nrb_last ? grb : nrb_last;
     src[LA + i] = (const char*)p.Bt + (((int64_t)grb * (p.ldb / 16) + (int64_t)kt0 * KB + kb) * 64 + lane) * 16;
@@ -708,7 +717,8 @@ template <int BM, int BN, int BK, int WGM, int WGN, int KG, int STAGES, int ACT,
           bool EPI>
 static int launch_dl_epi(const GemmArgs& a, int n_split, hipStream_t st) {
   constexpr int NA = DUAL ? 2 : 1;
-  constexpr size_t ring = (size_t)STAGES * (NA * BM + BN) * BK * 2;
+  constexpr int NWH = WGM * WGN * KG, BBLK = (BN / 32) * (BK / 16);
+  constexpr size_t ring = (size_t)STAGES * ((size_t)NA * BM * BK * 2 + (size_t)((BBLK + NWH - 1) / NWH) * NWH * 1024);
   constexpr size_t park = KG > 1 ? (size_t)BM * BN * 4 : 0;   // one k group's accumulators
   constexpr size_t lds = ring > park ? ring : park;
   static_assert(lds <= 160 * 1024, "LDS budget of a CU");
@@ -752,7 +762,7 @@ static int launch_dl_shape(const GemmArgs& a, int act, int n_split, hipStream_t 
   if (act == ACT_GELU)
     return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GELU, false, false, true>(a, 1, st)
               : launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GELU, false, false, false>(a, 1, st);
-  if constexpr (BN / WGN >= 64) {
+  if constexpr (BN / WGN >= 64 && (BN / WGN / 32) % 2 == 0) {
     if (act == ACT_GLU && !dual)
       return at ? launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, false, false, true>(a, 1, st)
                 : launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, STAGES, ACT_GLU, false, false, false>(a, 1, st);
@@ -785,6 +795,8 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
     case GEMM_128x128: return launch_dl_shape<128, 128, 32, 2, 2, 1, 3>(a, act, n_split, st);
     case GEMM_128x128_KSPLIT: return launch_dl_shape<128, 128, 64, 2, 2, 2, 4>(a, act, n_split, st);
     case GEMM_256x256: return launch_dl_shape<256, 256, 32, 2, 4, 1, 3>(a, act, n_split, st);
+    case GEMM_256x320: return launch_dl_shape<256, 320, 32, 4, 2, 1, 3>(a, act, n_split, st);
+    case GEMM_128x320: return launch_dl_shape<128, 320, 32, 2, 2, 1, 3>(a, act, n_split, st);
   }
   return -1;
 }
