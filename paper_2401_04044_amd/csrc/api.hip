@@ -143,6 +143,7 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
       g.partial = 1; g.C0 = part; g.ldc0 = L.rp;
       int g3s = big_m ? (w.g3_wide ? GEMM_256x128 : GEMM_128x128_KSPLIT) : GEMM_128x128;
       if (w.g3_wide == 2) g3s = GEMM_256x320;
+      if (w.g3_wide == 3) g3s = GEMM_256x256;
       FFS_TRY(run(g, ACT_NONE, g3s, w.g3_split));
       FFS_TRY(launch_splitk_reduce(part, w.g3_split, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, L.tiled, st,
                                    bf16 ? 0 : 1));

@@ -968,12 +968,19 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
       // 256 x 320 tiles (eight wavefronts with wave tiles of 64 x 160: fewer fragment reads and
       // barriers per product than 256 x 128 on four) where the rank is a multiple of 320 and some
       // split count fills whole rounds of one workgroup per CU (C5: rank 1280, 16 x 4 tiles x 4
-      // splits = 256 workgroups; 201 -> 175 us)
+      // splits = 256 workgroups; 201 -> 175 us); likewise 256 x 256 tiles on eight wavefronts where
+      // the rank is a multiple of 256 (the Llama shape: rank 1024, 16 x 4 x 4; 94 -> 83 us)
       if (L.rp % 320 == 0) {
         const int t320 = (int)((T + 255) / 256) * (L.rp / 320);
         for (int c = 1; c <= 8 && c <= max_sp; ++c) {
           const int wgs = t320 * c;
           if (100 * wgs / (256 * ((wgs + 255) / 256)) >= 95) { w.g3_wide = 2; sp = c; break; }
+        }
+      } else if (L.rp % 256 == 0) {
+        const int t256 = (int)((T + 255) / 256) * (L.rp / 256);
+        for (int c = 1; c <= 8 && c <= max_sp; ++c) {
+          const int wgs = t256 * c;
+          if (100 * wgs / (256 * ((wgs + 255) / 256)) >= 95) { w.g3_wide = 3; sp = c; break; }
         }
       }
     }
