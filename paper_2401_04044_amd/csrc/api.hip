@@ -67,7 +67,20 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
   auto run = [&](GemmArgs& g, int a, int shape, int n_split) -> int {
     if (g.group_m <= 0) g.group_m = 8;
     g.m_pad = w.t_pad;
-    if (!bf16) return launch_gemm_f32(g, a, false, st, n_split);
+    if (!bf16) {
+      // few tiles: split the reduction, bias / activation / routing with the sum (never beyond
+      // the scratch the workspace was sized with: the plain launch is always valid)
+      const int sp = (g.partial || g.A1) ? 1 : f32_split(M, g.N, g.K);
+      if (sp > 1 && (size_t)sp * M * g.N * 4 <= w.kpart_bytes) {
+        float* part = (float*)(ws + w.off_kpart);
+        GemmArgs gp = g;
+        gp.partial = 1; gp.C0 = part; gp.ldc0 = g.N; gp.split_col = g.N; gp.act_cols = 0;
+        gp.bias = nullptr; gp.bias_cols = 0; gp.resid = nullptr; gp.out_f32 = 0;
+        if (launch_gemm_f32(gp, ACT_NONE, false, st, sp) != 0) return -1;
+        return launch_splitk_epilogue_f32(part, sp, g.N, g, a, st);
+      }
+      return launch_gemm_f32(g, a, false, st, n_split);
+    }
     if (small_m && !g.partial && (g.N & 31) == 0) return launch_skinny_bf16(g, a, (float*)(ws + w.off_kpart), st);
     if (!small_m && M <= 1024 && !g.partial && !g.A1) {
       // a few hundred rows and few tiles: split the reduction, epilogue in a second launch

@@ -108,6 +108,8 @@ struct Epilogue {
 
 // n_split > 1: only with a.partial and no activation: fp32 partials [split][M][ldc0] into C0
 int launch_gemm_f32(const GemmArgs& a, int act, bool score, hipStream_t st, int n_split = 1);
+// sum of fp32 partials [n_split][a.M][ldp] of a whole product + the fp32 store epilogue described by a
+int launch_splitk_epilogue_f32(const float* part, int n_split, int ldp, const GemmArgs& a, int act, hipStream_t st);
 // tile configurations of the bf16 kernel
 enum {
   GEMM_256x128 = 0,        // 4 wavefronts, 3 stages: the default for large products

@@ -147,6 +147,62 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs p) {
   }
 }
 
+// Sum of fp32 partials [n_split][M][ldp] of a whole product (GEMM column order, written with
+// a.partial and no activation) followed by the store epilogue of gemm_f32_kernel: bias,
+// activation (exact GeLU, or SwiGLU on (gate, up) pairs of 32-column blocks), routing to two
+// fp32 destinations, residual.  One thread per (row, output column), columns fastest.
+struct SplitEpiF32Args {
+  const float* part;
+  int n_split, M, ldp, n_out;
+  int act, act_cols, split_col;
+  float* C0;
+  float* C1;
+  int64_t ldc0, ldc1;
+  const float* bias;
+  int bias_cols;
+  const float* resid;
+  int64_t ldr;
+};
+
+__global__ void __launch_bounds__(256) splitk_epilogue_f32_kernel(const SplitEpiF32Args p) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (int64_t)p.M * p.n_out) return;
+  const int row = (int)(id / p.n_out), oc = (int)(id % p.n_out);
+  const bool glu = p.act == ACT_GLU;
+  const bool pair = glu && oc < p.act_cols / 2;
+  int c = oc;   // GEMM column of the (gate) value
+  if (glu) c = pair ? (oc / 32) * 64 + (oc & 31) : oc + p.act_cols / 2;
+  float v = 0.f, u = 0.f;
+  for (int s = 0; s < p.n_split; ++s) {
+    const float* src = p.part + ((int64_t)s * p.M + row) * p.ldp + c;
+    v += src[0];
+    if (pair) u += src[32];
+  }
+  if (!glu && p.bias != nullptr && c < p.bias_cols) v += p.bias[c];
+  if (pair) v = silu_f(v) * u;
+  else if (p.act == ACT_GELU && c < p.act_cols) v = gelu_f(v);
+  if (oc < p.split_col) {
+    if (p.resid != nullptr) v += p.resid[(int64_t)row * p.ldr + oc];
+    p.C0[(int64_t)row * p.ldc0 + oc] = v;
+  } else {
+    p.C1[(int64_t)row * p.ldc1 + (oc - p.split_col)] = v;
+  }
+}
+
+int launch_splitk_epilogue_f32(const float* part, int n_split, int ldp, const GemmArgs& g, int act, hipStream_t st) {
+  SplitEpiF32Args a = {};
+  a.part = part; a.n_split = n_split; a.M = g.M; a.ldp = ldp;
+  a.n_out = act == ACT_GLU ? g.N - g.act_cols / 2 : g.N;
+  a.act = act; a.act_cols = g.act_cols; a.split_col = g.split_col;
+  a.C0 = (float*)g.C0; a.C1 = (float*)g.C1; a.ldc0 = g.ldc0; a.ldc1 = g.ldc1;
+  a.bias = g.bias; a.bias_cols = g.bias_cols; a.resid = g.resid; a.ldr = g.ldr;
+  if (act == ACT_GLU && (g.act_cols & 63)) return -1;
+  const int64_t n = (int64_t)a.M * a.n_out;
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(splitk_epilogue_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 // ------------------------------------------------------------------ host launchers
 
 template <int ACT, bool DUAL, bool SCORE>

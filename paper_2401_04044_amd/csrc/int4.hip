@@ -942,7 +942,28 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     if (sp > 32) sp = 32;
     if (sp < 1) sp = 1;
     w.g3_split = sp;
-    if (sp > 1) off = align256(off + (size_t)sp * T * L.rp * 4);
+    size_t scratch = sp > 1 ? (size_t)sp * T * L.rp * 4 : 0;
+    // the other products' own splits (f32_split)
+    const int ns[3] = {L.n1, L.n_up * L.mp, L.dn};
+    const int ks[3] = {L.dk, L.rp, L.k4};
+    for (int i = 0; i < 3; ++i) {
+      const int s2 = f32_split(T, ns[i], ks[i]);
+      const size_t b = (size_t)s2 * T * ns[i] * 4;
+      if (s2 > 1 && b > scratch) scratch = b;
+    }
+    w.kpart_bytes = scratch;
+    if (scratch > 0) off = align256(off + scratch);
+  } else if (!L.tiled && T > 0) {
+    size_t scratch = 0;
+    const int ns[2] = {L.n1, L.dn};
+    const int ks[2] = {L.dk, L.k4};
+    for (int i = 0; i < 2; ++i) {
+      const int s2 = f32_split(T, ns[i], ks[i]);
+      const size_t b = (size_t)s2 * T * ns[i] * 4;
+      if (s2 > 1 && b > scratch) scratch = b;
+    }
+    w.kpart_bytes = scratch;
+    if (scratch > 0) off = align256(off + scratch);
   }
   if (L.tiled && L.rp > 0 && L.mp > 0 && T > 0) {
     // Split the long reduction of h2 * P2 across workgroups (more splits cost more partial-sum

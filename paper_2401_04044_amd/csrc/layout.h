@@ -135,6 +135,19 @@ inline int mid_split(int64_t T, int N, int K) {
   return sp > 1 ? sp : 1;
 }
 
+// fp32 path: a product with few 64 x 64 tiles (its workgroups each walk the whole reduction in
+// 16-deep slabs, one after the other) is split along the reduction into up to about 192
+// workgroups of at least 64 reduction elements; fp32 partials, then one summing launch that
+// also applies bias / activation / routing.
+inline int f32_split(int64_t T, int N, int K) {
+  const int tiles = (int)((T + 63) / 64) * ((N + 63) / 64);
+  if (tiles <= 0 || tiles >= 96 || K < 128) return 1;
+  int sp = 192 / tiles;
+  if (sp > K / 64) sp = K / 64;
+  if (sp > 32) sp = 32;
+  return sp > 1 ? sp : 1;
+}
+
 struct FwdWs {
   size_t off_cat, off_t, off_h2, off_kpart;
   size_t kpart_bytes;   // bytes of split-K scratch at off_kpart (65..1024 rows: checked before use)
