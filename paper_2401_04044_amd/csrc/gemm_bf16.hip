@@ -136,7 +136,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, f32x16_t (&acc)
           continue;
         }
         // the residual stream (fp32, row-major, same columns as the destination)
-        const float* rrow = (EPI && p.resid != nullptr && to_c0 && !tiled && row < p.M)
+        // (un-activated products start their accumulators from the residual instead: see the kernel)
+        const float* rrow = (EPI && ACT != ACT_NONE && p.resid != nullptr && to_c0 && !tiled && row < p.M)
                                 ? p.resid + (int64_t)row * p.ldr + occ + 4 * half : nullptr;
         uint32_t pk[4][2];
 #pragma unroll
@@ -390,6 +391,32 @@ gemm_bf16_dl_kernel(const GemmArgs p) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // Residual stream of an un-activated product: the accumulators start from it (same lane
+  // layout as the store epilogue: row lane & 31, columns 8 g + 4 (lane >> 5) + 0..3 of each
+  // tile), so its loads overlap the filling of the ring instead of forming one dependent
+  // round trip per tile between the last product and the stores.  This workgroup alone
+  // reads and later writes these elements, so the destination may be the residual buffer.
+  if (EPI && ACT == ACT_NONE && !SCORE && SWAP) {
+    if (p.resid != nullptr && !p.partial && !p.c0_tiled && kg == 0) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int cb = n0 + wn * WN + j * 32;
+        if (cb >= p.N || cb >= p.split_col) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int row = m0 + wm * WM + i * 32 + (lane & 31);
+          if (row >= p.M) continue;
+          const float* rrow = p.resid + (int64_t)row * p.ldr + cb + 4 * (lane >> 5);
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            if (cb + 8 * g + 4 * (lane >> 5) < p.n_store) {
+              const float4 r4 = *(const float4*)(rrow + 8 * g);
+              acc[i][j][4 * g] = r4.x; acc[i][j][4 * g + 1] = r4.y; acc[i][j][4 * g + 2] = r4.z; acc[i][j][4 * g + 3] = r4.w;
+            }
+        }
+      }
+    }
+  }
 
   // Fragment reads run one k step ahead of the MFMAs (two register sets), also across the
   // slab boundary, so LDS traffic overlaps the matrix pipeline instead of following a barrier.
