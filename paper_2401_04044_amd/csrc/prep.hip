@@ -147,10 +147,23 @@ __global__ void __launch_bounds__(256) token_rmsnorm_kernel(const float* x, int 
   __shared__ float wsum[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* row = x + (int64_t)blockIdx.x * d;
+  // rows of up to 8192 elements stay in registers between the sum and the scaling (one read
+  // of the stream); longer rows are read a second time
+  constexpr int NV = 8;
+  float4 v[NV];
   float s = 0.f;
-  for (int c = tid * 4; c < d; c += 1024) {
-    const float4 v = *(const float4*)(row + c);
-    s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = tid * 4 + i * 1024;
+    v[i] = c < d ? *(const float4*)(row + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    s = fmaf(v[i].x, v[i].x, s); s = fmaf(v[i].y, v[i].y, s); s = fmaf(v[i].z, v[i].z, s); s = fmaf(v[i].w, v[i].w, s);
+  }
+  for (int c = tid * 4 + NV * 1024; c < d; c += 1024) {
+    const float4 w = *(const float4*)(row + c);
+    s = fmaf(w.x, w.x, s); s = fmaf(w.y, w.y, s); s = fmaf(w.z, w.z, s); s = fmaf(w.w, w.w, s);
   }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
@@ -158,15 +171,20 @@ __global__ void __launch_bounds__(256) token_rmsnorm_kernel(const float* x, int 
   __syncthreads();
   const float tot = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int c = tid * 4; c < d; c += 1024) {
-    const float4 v = *(const float4*)(row + c);
+  auto emit = [&](int c, const float4& w) {
     if (BF16) {
       *(uint2*)((bf16_t*)out + (int64_t)blockIdx.x * d + c) =
-          make_uint2(pack_bf16x2(v.x * inv, v.y * inv), pack_bf16x2(v.z * inv, v.w * inv));
+          make_uint2(pack_bf16x2(w.x * inv, w.y * inv), pack_bf16x2(w.z * inv, w.w * inv));
     } else {
-      *(float4*)((float*)out + (int64_t)blockIdx.x * d + c) = make_float4(v.x * inv, v.y * inv, v.z * inv, v.w * inv);
+      *(float4*)((float*)out + (int64_t)blockIdx.x * d + c) = make_float4(w.x * inv, w.y * inv, w.z * inv, w.w * inv);
     }
+  };
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = tid * 4 + i * 1024;
+    if (c < d) emit(c, v[i]);
   }
+  for (int c = tid * 4 + NV * 1024; c < d; c += 1024) emit(c, *(const float4*)(row + c));
 }
 
 int launch_token_rmsnorm(const float* x, int64_t T, int d, float eps, int bf16, void* out, hipStream_t st) {

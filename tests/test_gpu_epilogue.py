@@ -164,7 +164,7 @@ def test_forward_ex_output_bias_and_residual_on_gated_and_quantised_layers(ff, n
     assert e.value.code == -6
 
 
-@pytest.mark.parametrize("T,d", [(1, 64), (37, 328), (300, 5120), (5, 8)])
+@pytest.mark.parametrize("T,d", [(1, 64), (37, 328), (300, 5120), (5, 8), (3, 10240)])
 def test_token_rmsnorm_matches_oracle(ff, T, d):
     x = (np.random.default_rng(T).standard_normal((T, d)) * np.linspace(0.01, 40.0, T)[:, None]).astype(np.float32)
     if T > 2:
