@@ -142,7 +142,10 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     g.C0 = h2; g.ldc0 = L.mp; g.c0_tiled = L.tiled;
     g.bias = ep.b1 ? ep.b1 + L.kp : nullptr; g.bias_cols = ep.b1 ? L.mp : 0;   // the remainder neurons' biases
     // (a short reduction leaves a 256x256 tile's epilogue uncovered: one workgroup per CU)
-    const int g2s = (!glu && g.K >= 1024 && fill256(M, g.N) >= 90) ? GEMM_256x256 : GEMM_256x128;
+    int g2s = (!glu && g.K >= 1024 && fill256(M, g.N) >= 90) ? GEMM_256x256 : GEMM_256x128;
+    // two left operands: 256 x 256 tiles with wave tiles of 64 x 128 read each token fragment for
+    // four weight blocks instead of two (the Llama shape: 231 -> 200 us)
+    if (glu && g.K >= 1024 && fill256(M, g.N) >= 80) g2s = GEMM_256x256_W64;
     FFS_TRY(run(g, act, big_m ? g2s : GEMM_128x128, 1));
     // G3: h2 * P2 -> t2 into cat[:, kp:]  (long reduction: split-K, fixed-order sum)
     g = {};

@@ -117,7 +117,8 @@ enum {
   GEMM_128x128_KSPLIT = 2, // 8 wavefronts, 64-deep slabs, reduction split inside the workgroup (few tiles)
   GEMM_256x256 = 3,        // 8 wavefronts, 3 stages
   GEMM_256x320 = 4,        // 4 wavefronts, wave tile 128 x 160 (one wavefront per SIMD): N a multiple of 320
-  GEMM_128x320 = 5         // 4 wavefronts, wave tile 64 x 160
+  GEMM_128x320 = 5,        // 4 wavefronts, wave tile 64 x 160
+  GEMM_256x256_W64 = 6     // 8 wavefronts as 4 x 2, wave tile 64 x 128: fewer reads of two left operands
 };
 // n_split > 1 only with a.partial
 int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_split, hipStream_t st);

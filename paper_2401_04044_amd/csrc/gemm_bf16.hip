@@ -796,7 +796,9 @@ static int launch_dl_shape(const GemmArgs& a, int act, int n_split, hipStream_t 
     if constexpr ((2 * (BM / 32) * (BK / 16)) % (WGM * WGN * KG) == 0) {
       // two left operands double the A part of a stage: fewer stages where that keeps two
       // workgroups per CU (80 KiB each)
-      constexpr int DST = ((size_t)STAGES * (2 * BM + BN) * BK * 2 > 80 * 1024 && STAGES > 2) ? 2 : STAGES;
+      // (a 256 x 256 tile runs one workgroup per CU anyway: it keeps its three stages, 144 KiB)
+      constexpr int DST = (BM * BN >= 256 * 256) ? STAGES
+                          : (((size_t)STAGES * (2 * BM + BN) * BK * 2 > 80 * 1024 && STAGES > 2) ? 2 : STAGES);
       if constexpr ((size_t)DST * (2 * BM + BN) * BK * 2 <= 160 * 1024) {
         if (act == ACT_GLU && dual && at)
           return launch_dl_cfg<BM, BN, BK, WGM, WGN, KG, DST, ACT_GLU, true, false, true>(a, 1, st);
@@ -824,6 +826,7 @@ int launch_gemm_bf16(const GemmArgs& a, int act, bool score, int shape, int n_sp
     case GEMM_256x256: return launch_dl_shape<256, 256, 32, 2, 4, 1, 3>(a, act, n_split, st);
     case GEMM_256x320: return launch_dl_shape<256, 320, 32, 4, 2, 1, 3>(a, act, n_split, st);
     case GEMM_128x320: return launch_dl_shape<128, 320, 32, 2, 2, 1, 3>(a, act, n_split, st);
+    case GEMM_256x256_W64: return launch_dl_shape<256, 256, 32, 4, 2, 1, 3>(a, act, n_split, st);
   }
   return -1;
 }

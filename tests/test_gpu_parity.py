@@ -162,6 +162,8 @@ FWD_CASES = [
     # more than 1024 rows: 256-row tiles, split-K of the long reduction, dual-operand SwiGLU
     ("c2_reduced_tall", reduced(C2, 256, 2100, rank=128), 1300),
     ("c3_reduced_tall", reduced(C3, 192, 1500, rank=64), 1059),
+    # rank 1024 and enough tiles: the two-operand SwiGLU product on 256x256 tiles (64x128 wave tiles)
+    ("c3_dual_256_tiles", reduced(C3, 1024, 3700, rank=1024), 2048),
 ]
 
 
