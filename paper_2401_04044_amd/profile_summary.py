@@ -23,30 +23,31 @@ import json
 import os
 import re
 
-# (label, kernel-name regex, workgroups x, workgroups y) per workload; `None` matches any count
+# (label, kernel-name regex, workgroups x, workgroups y [, regex of the kernel launched just before])
+# per workload: where two products share template and workgroup count, the chain's order tells them apart
 G = r"gemm_bf16_dl_kernel<"
 SIGNATURES = {
     "C5_stack_layer": [
         ("pre-norm  token_rmsnorm_kernel", r"token_rmsnorm_kernel<true>", 4096, 1),
         ("G1 X [W1h | P1]  128x320 tiles", G + r"128, 320, 32, 2, 2, 1, 3, 1, false, false, false, false>", 224, 1),
         ("G2 gelu(t Q1)  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 1, false, false, true, false>", 1232, 1),
-        ("G3 h2 P2  256x320 tiles x 4 splits", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, false>", 64, 4),
+        ("G3 h2 P2  256x320 tiles x 4 splits", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, false>", 64, 4, G),
         ("G3 sum of the splits", r"splitk_reduce_kernel", 2560, 1),
         ("G4 [h1 | t2] [W2h ; Q2] + residual, fp32 out  256x320 tiles", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, true>", 256, 1),
     ],
     "C5_prefill": [
         ("G1  128x320 tiles", G + r"128, 320, 32, 2, 2, 1, 3, 1, false, false, false, false>", 224, 1),
         ("G2  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 1, false, false, true, false>", 1232, 1),
-        ("G3  256x320 tiles x 4 splits", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, false>", 64, 4),
+        ("G3  256x320 tiles x 4 splits", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, false>", 64, 4, G),
         ("G3 sum of the splits", r"splitk_reduce_kernel", 2560, 1),
-        ("G4  256x320 tiles", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, false>", 256, 1),
+        ("G4  256x320 tiles", G + r"256, 320, 32, 4, 2, 1, 3, 0, false, false, true, false>", 256, 1, r"splitk_reduce_kernel"),
     ],
     "C3_prefill": [
         ("G1 X [gate/up heavy | Pg | P1]  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 2, false, false, false, false>", 208, 1),
-        ("G2 silu(tg Qg) * (tu Q1), two left operands  256x128 tiles", G + r"256, 128, 32, 2, 2, 1, 2, 2, true, false, true, false>", 2624, 1),
-        ("G3 h2 P2  256x256 tiles x 4 splits", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 64, 4),
+        ("G2 silu(tg Qg) * (tu Q1), two left operands  256x256 tiles", G + r"256, 256, 32, 4, 2, 1, 3, 2, true, false, true, false>", 1312, 1),
+        ("G3 h2 P2  256x256 tiles x 4 splits", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 64, 4, G),
         ("G3 sum of the splits", r"splitk_reduce_kernel", 2048, 1),
-        ("G4  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 256, 1),
+        ("G4  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 256, 1, r"splitk_reduce_kernel"),
     ],
     "C2_prefill": [
         ("G1  128x128 tiles, in-workgroup K split", G + r"128, 128, 64, 2, 2, 2, 4, 1, false, false, false, false>", 192, 1),
@@ -63,7 +64,7 @@ SIGNATURES = {
         ("expand up/gate to bf16", r"expand_up_kernel", 44288, 1),
         ("expand down to bf16", r"expand_down_kernel", 22144, 1),
         ("G1 X [W1 ; Wg]  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 2, false, false, false, false>", 1392, 1),
-        ("G4 h W2  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 256, 1),
+        ("G4 h W2  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 256, 1, G + r"256, 256, 32, 2, 4, 1, 3, 2,"),
     ],
     "C4_w3h8_decode": [
         ("up/gate stream (int8 heavy + int3 rest)", r"skinny_stream_q2_kernel<false>", 800, 1),
@@ -118,55 +119,62 @@ def _find(d, suffix):
     return hits[0]
 
 
-def _wg(r, pmc=False):
-    if pmc:   # counter files give the grid in work-items (x * y * z) and the workgroup size
-        return None
-    gx = int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1)
-    gy = int(r["Grid_Size_Y"]) // max(int(r["Workgroup_Size_Y"]), 1)
-    return gx, gy
+class Dispatch:
+    __slots__ = ("name", "gx", "gy", "wgs", "us", "counters", "prev")
+
+    def __init__(self, name, gx, gy, wgs, us):
+        self.name, self.gx, self.gy, self.wgs, self.us = name, gx, gy, wgs, us
+        self.counters = {}
+        self.prev = ""
+
+
+def _chain(ds):
+    """Dispatches in launch order, each with the name of the one before it."""
+    ds = [d for _, d in sorted(ds.items())]
+    for a, b in zip(ds, ds[1:]):
+        b.prev = a.name
+    return ds
 
 
 def load_trace(d):
-    agg = collections.defaultdict(list)
+    ds = {}
     for r in csv.DictReader(open(_find(d, "kernel_trace.csv"))):
-        gx, gy = _wg(r)
-        agg[(_short(r["Kernel_Name"]), gx, gy)].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
-    return agg
+        gx = int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1)
+        gy = int(r["Grid_Size_Y"]) // max(int(r["Workgroup_Size_Y"]), 1)
+        ds[int(r["Dispatch_Id"])] = Dispatch(_short(r["Kernel_Name"]), gx, gy, gx * gy,
+                                             (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    return _chain(ds)
 
 
 def load_counters(d):
-    """{(kernel, total workgroups): {counter: [values]}} (the counter CSV has only the flat grid size)."""
-    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    """The counter CSV has one row per (dispatch, counter) and only the flat grid size."""
+    ds = {}
     for r in csv.DictReader(open(_find(d, "counter_collection.csv"))):
-        wgs = int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1)
-        agg[(_short(r["Kernel_Name"]), wgs)][r["Counter_Name"]].append(float(r["Counter_Value"]))
-    return agg
+        i = int(r["Dispatch_Id"])
+        if i not in ds:
+            wgs = int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1)
+            ds[i] = Dispatch(_short(r["Kernel_Name"]), None, None, wgs, None)
+        ds[i].counters[r["Counter_Name"]] = ds[i].counters.get(r["Counter_Name"], 0.0) + float(r["Counter_Value"])
+    return _chain(ds)
 
 
-def pick(agg, pat, gx, gy):
-    out = []
-    for (name, x, y), v in agg.items():
-        if re.search(pat, name) and x == gx and y == gy:
-            out += v
-    return out
+def pick(ds, sig):
+    """Durations of the dispatches that match a signature (kernel, grid, kernel launched before)."""
+    _, pat, gx, gy, prev = sig
+    return [d.us for d in ds if d.gx == gx and d.gy == gy and re.search(pat, d.name)
+            and (prev is None or re.search(prev, d.prev))]
 
 
-def pick_counter(agg, pat, wgs, counter):
-    out = []
-    for (name, w), c in agg.items():
-        if re.search(pat, name) and w == wgs:
-            out += c.get(counter, [])
-    return out
+def pick_counter(ds, sig, counter):
+    _, pat, gx, gy, prev = sig
+    return [d.counters[counter] for d in ds if d.wgs == gx * gy and counter in d.counters and re.search(pat, d.name)
+            and (prev is None or re.search(prev, d.prev))]
 
 
-def copy_factor(agg, counter):
+def copy_factor(ds, counter):
     """KiB the counter reports per KiB moved, from the three 256 MiB device-to-device reference
     copies of --calib-copy (the largest dispatches of the runtime's copy kernel)."""
-    best = []
-    for (name, w), c in agg.items():
-        if "rocclr_copyBuffer" in name:
-            best += c.get(counter, [])
-    big = sorted(best)[-3:]
+    big = sorted(d.counters.get(counter, 0.0) for d in ds if "rocclr_copyBuffer" in d.name)[-3:]
     if not big or max(big) <= 0:
         return None
     return (sum(big) / len(big)) / 262144.0
@@ -189,7 +197,7 @@ def main():
     ff_ = copy_factor(fe, "FETCH_SIZE") if fe else None
     fw_ = copy_factor(wr, "WRITE_SIZE") if wr else None
     traffic = {}
-    cmds = ["rocprofv3 --kernel-trace --output-format csv -d <out> -o kt -- python3 <repo>/bench.py --steps 10 --warmup 3 --no-cpu"]
+    cmds = ["rocprofv3 --kernel-trace --stats --output-format csv -d <out> -o kt -- python3 <repo>/bench.py --steps 10 --warmup 3 --no-cpu"]
     if fe:
         cmds.append("rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -o fetch -- python3 <repo>/bench.py --steps 3 --warmup 1 "
                     "--preheat-ms 0 --no-cpu --calib-copy")
@@ -216,8 +224,10 @@ def main():
         lines += [head, sep]
         tot_us = tot_r = tot_w = 0.0
         complete = True
-        for label, pat, gx, gy in sig:
-            v = pick(kt, pat, gx, gy)
+        for one in sig:
+            one = tuple(one) + (None,) * (5 - len(one))
+            label, pat, gx, gy, _ = one
+            v = pick(kt, one)
             if not v:
                 lines.append(f"| {label} | `{pat}` | {gx}{' x ' + str(gy) if gy > 1 else ''} | 0 | - | - |")
                 complete = False
@@ -226,8 +236,8 @@ def main():
             tot_us += avg
             row = f"| {label} | `{pat.replace(G, 'gemm_bf16_dl_kernel<')}` | {gx}{' x ' + str(gy) if gy > 1 else ''} | {len(v)} | {avg:.1f} | {min(v):.1f} |"
             if fe and wr:
-                f_ = pick_counter(fe, pat, gx * gy, "FETCH_SIZE")
-                w_ = pick_counter(wr, pat, gx * gy, "WRITE_SIZE")
+                f_ = pick_counter(fe, one, "FETCH_SIZE")
+                w_ = pick_counter(wr, one, "WRITE_SIZE")
                 if f_ and w_ and ff_ and fw_:
                     rmb = sum(f_) / len(f_) * 1024 / ff_ / 1e6
                     wmb = sum(w_) / len(w_) * 1024 / fw_ / 1e6
@@ -237,10 +247,10 @@ def main():
                 else:
                     row += " - | - |"
             if pm:
-                busy = pick_counter(pm, pat, gx * gy, "SQ_BUSY_CU_CYCLES")
-                mf = pick_counter(pm, pat, gx * gy, "SQ_VALU_MFMA_BUSY_CYCLES")
-                bc = pick_counter(pm, pat, gx * gy, "SQ_LDS_BANK_CONFLICT")
-                la = pick_counter(pm, pat, gx * gy, "SQ_LDS_IDX_ACTIVE")
+                busy = pick_counter(pm, one, "SQ_BUSY_CU_CYCLES")
+                mf = pick_counter(pm, one, "SQ_VALU_MFMA_BUSY_CYCLES")
+                bc = pick_counter(pm, one, "SQ_LDS_BANK_CONFLICT")
+                la = pick_counter(pm, one, "SQ_LDS_IDX_ACTIVE")
                 if busy and mf and sum(busy) > 0:
                     # MFMA busy cycles are summed over the four SIMDs of a CU
                     row += f" {100.0 * sum(mf) / (4.0 * sum(busy)):.1f} | {sum(bc) / max(len(bc), 1):.0f} | {100.0 * sum(la) / (4.0 * sum(busy)):.1f} |"
