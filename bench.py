@@ -476,7 +476,53 @@ def main():
             st["i"] += 1
 
         tr, _ = timed(rd, 64, 16)
+        def stream_floor(sizes, reps=20):
+            """us per pass of a sequence of plain streaming-read launches of the given byte counts,
+            replayed from a HIP graph (no host time between the launches): what the same bytes in the
+            same number of dependent launches cost with no arithmetic at all."""
+            views, o = [], 0
+            for _ in range(reps):
+                for nb in sizes:
+                    nb = int(nb) // 4096 * 4096
+                    if o + nb > bufs.numel():
+                        o = 0
+                    views.append(bufs[o:o + nb])
+                    o += nb
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for v in views[:len(sizes)]:
+                    ff.probe_stream_read(v, 2048, scr)
+                side.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    for v in views:
+                        ff.probe_stream_read(v, 2048, scr)
+            torch.cuda.synchronize()
+            tg, _ = timed(g.replay, 10, 3)
+            return tg / reps * 1e6
+
+        MBs = 1e6
+        c3w, c4w, c5w = C3.weight_bytes(), C4.weight_bytes(), C5.weight_bytes()
+
+        def lowrank_launch_bytes(c):
+            nu = 2 if c.act == "swiglu" else 1
+            m = c.d_ff - c.k
+            g = [2 * c.d_model * nu * (c.k + c.rank), 2 * nu * c.rank * m, 2 * m * c.rank, 2 * (c.k + c.rank) * c.d_model]
+            # G1 and G3 are a streaming launch plus a summing launch that reads a few MB of partials
+            return [g[0], 4 * MBs, g[1], g[2], 4 * MBs, g[3]]
+
+        floors = {
+            "C4_int4_decode (2 launches: up/gate 2/3 of the bytes, down 1/3)": stream_floor([c4w * 2 / 3, c4w / 3]),
+            "C3_lowrank_decode (6 launches)": stream_floor(lowrank_launch_bytes(C3)),
+            "C5_lowrank_decode (6 launches)": stream_floor(lowrank_launch_bytes(C5)),
+            "C4_w3h8_decode (4 launches: 38 MB, 4 MB of partials, 19 MB, 4 MB)": stream_floor([38 * MBs, 4 * MBs, 19 * MBs, 4 * MBs]),
+            "one launch of 1 MB (fixed cost of a dependent launch)": stream_floor([1 * MBs]),
+        }
+        note("streaming-read floors of the decode launch sequences (us): " +
+             ", ".join(f"{k.split(' ')[0]} {v:.1f}" for k, v in floors.items()))
         out["yardsticks"] = {"pure_mfma_loop_TFLOPs": fl["v"] / tm / 1e12,
+                             "decode_launch_sequence_stream_floor_us": floors,
                              "streaming_read_80MB_GBps": chunk / tr / 1e9, "streaming_read_80MB_us": tr * 1e6,
                              "note": "ffsplit_probe_mfma / ffsplit_probe_stream_read: this library's own kernels, "
                                      "measurement only, rotating over 16 x 80 MB for the read"}

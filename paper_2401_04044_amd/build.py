@@ -10,6 +10,9 @@ SOURCES = ["api.hip", "gemm.hip", "gemm_bf16.hip", "prep.hip", "select.hip", "in
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
+# The small-batch kernels apply vector arithmetic to every MFMA result (scales, activations):
+# keep those results in vector registers, not in the accumulator file, which costs a move each.
+FILE_FLAGS = {"skinny.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose: bool = True) -> str:
@@ -18,7 +21,8 @@ def build(verbose: bool = True) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc] + [f for f in FLAGS if f != "-shared"] + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = ([hipcc] + [f for f in FLAGS if f != "-shared"] + FILE_FLAGS.get(src, []) +
+               ["-c", os.path.join(CSRC, src), "-o", obj])
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False

@@ -86,11 +86,19 @@ __device__ __forceinline__ int q_get(const QPacked<3>& p, int t) {
   return (int)(lo | (hi << 2)) - 4;
 }
 
+// (a & mask) | o in one instruction (the compiler's own choice, two ands and a three-input or,
+// costs one more per register; the unpack is what bounds the small-batch kernels)
+__device__ __forceinline__ uint32_t q_and_or(uint32_t a, uint32_t mask, uint32_t o) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(o));
+  return r;
+}
+
 // register i (elements 2 i, 2 i + 1) of operand block j as the pair (magic + u) in both halves
 __device__ __forceinline__ uint32_t q_pair(const QPacked<3>& p, int j, int i, uint32_t magic) {
   const int pr = 4 * j + i;
-  const uint32_t r = ((p.lo[j >> 1] >> (2 * (pr & 7))) & 0x00030003u) | magic;
-  return (__builtin_amdgcn_alignbit(p.hi, p.hi, pr) & 0x00040004u) | r;
+  const uint32_t r = q_and_or(p.lo[j >> 1] >> (2 * (pr & 7)), 0x00030003u, magic);
+  return q_and_or(__builtin_amdgcn_alignbit(p.hi, p.hi, pr), 0x00040004u, r);
 }
 // 8 bits: bytes (2 i, 2 i + 1) of operand block j under the high byte of magic
 __device__ __forceinline__ uint32_t q_pair(const QPacked<8>& p, int j, int i, uint32_t magic_bytes) {

@@ -141,19 +141,20 @@ __global__ void __launch_bounds__(256) skinny_stream_kernel(const SkinnyArgs p) 
 //   UP    (one scale per row and 128 reduction elements; activations = the caller's bf16 X):
 //         the unscaled codes go through the MFMA, one group of 128 at a time, and the group's
 //         fp32 result is scaled per row afterwards.  3 bits: operands are the bf16 values
-//         128 + u, and a second MFMA with an all-ones operand gives the group's sum of
-//         activations, so that 132 times it removes the offset.  8 bits: the codes do not fit
-//         a bf16 mantissa; X is converted to fp16 (exact) and the operands are the fp16 values
-//         q = (1024 + u) - 1152.
+//         128 + u.  8 bits: the codes do not fit a bf16 mantissa; X is converted to fp16 (exact)
+//         and the operands are the fp16 values 1024 + u.
 //   DOWN  (one scale per reduction element and 128 rows; activations fp16, written by the UP
-//         products' reduce step): operands are the fp16 values s * q, from one packed add and
-//         one packed multiply with the scale pair as loaded.
+//         products' reduce step): the scale multiplies the activations (one packed multiply per
+//         register, shared by the row blocks of the group) and the operands are the fp16 values
+//         1024 + u.
+//   In both, the constant 128 + 4, 1024 + 4 or 1024 + 128 leaves through a second MFMA per
+//   operand block whose left operand holds the negated constant in every row.
 // Work split: a workgroup of four wavefronts owns RB adjacent row blocks (they share the
 // activation blocks, and for DOWN the scales) over one range of the reduction; the wavefronts
 // take a quarter of the range each and add their accumulators through LDS in a fixed order.
-// Each wavefront keeps two units in registers: everything the next unit needs (weights,
-// scales, activations) is requested in one batch before the current one is computed, so no
-// younger load ever has to be waited for behind an older one.
+// A wavefront requests the packed weights of up to SKQ_UNITS units (its whole share at the
+// usual shapes) in one batch, so that they cost one round trip to memory, and then the
+// activations and scales (cache resident) unit by unit, one unit ahead of the arithmetic.
 struct SkinnyQArgs {
   const void* A;
   int64_t lda;
@@ -178,15 +179,29 @@ union H2 {
   f16x2_t h;
 };
 
+// Units whose weights a wavefront holds at once, and row blocks per workgroup of the 3-bit parts.
+// Both are set by registers: at most 168 per lane keeps three workgroups per CU resident, which
+// matters more here than sharing the activation loads among more row blocks (measured: four
+// units and four row blocks, two workgroups per CU, 47 us per step at the Llama shape against 41.5).
+constexpr int SKQ_UNITS = 2;
+constexpr int SKQ_RB_UP3 = 2, SKQ_RB_DOWN3 = 2;
+
+// row blocks per workgroup (they share the activation blocks and, for DOWN, the scales)
+constexpr int skq_rb(int bits, bool down) { return bits == 3 ? (down ? SKQ_RB_DOWN3 : SKQ_RB_UP3) : (down ? 2 : 1); }
+
 template <int BITS, bool DOWN>
 struct QShape {
-  static constexpr int RB = BITS == 3 ? (DOWN ? 4 : 2) : (DOWN ? 2 : 1);   // row blocks per workgroup
+  static constexpr int RB = skq_rb(BITS, DOWN);
   static constexpr int UB = DOWN ? 1 : 2;                                  // blocks per unit
 };
 
 template <int BITS, bool DOWN>
-struct QUnit {
+struct QWts {
   QPacked<BITS> w[QShape<BITS, DOWN>::RB][QShape<BITS, DOWN>::UB];
+};
+
+template <int BITS, bool DOWN>
+struct QAct {
   u32x4_t a[QShape<BITS, DOWN>::UB * 4];
   u32x4_t sd[DOWN ? 4 : 1];                                  // DOWN: scale pairs of the block's 64 elements
   u32x2_t su[DOWN ? 1 : QShape<BITS, DOWN>::RB][4];          // UP: the lane's 16 row scales per row block
@@ -215,8 +230,9 @@ __device__ __forceinline__ void skinny_q_body(const SkinnyQArgs& p, int wg, floa
   if (DOWN) abase += (int64_t)lane * 16;                              // tiled, one row block
   else abase += ((int64_t)min(r, p.M - 1) * p.lda + c2 * 8) * 2;      // the caller's row-major X
 
-  auto load = [&](QUnit<BITS, DOWN>& q, int u) {
-    const int uc = max(U0, min(u, U1 - 1));                  // past the range: any valid unit, masked later
+  // (a unit past the range reads some valid unit of it and is not computed)
+  auto load_w = [&](QWts<BITS, DOWN>& q, int u) {
+    const int uc = max(U0, min(u, U1 - 1));
 #pragma unroll
     for (int i = 0; i < RB; ++i)
 #pragma unroll
@@ -225,6 +241,9 @@ __device__ __forceinline__ void skinny_q_body(const SkinnyQArgs& p, int wg, floa
         if constexpr (BITS == 8) q.w[i][x] = q_load8(blk, lane);
         else q.w[i][x] = q_load3(blk, lane);
       }
+  };
+  auto load_a = [&](QAct<BITS, DOWN>& q, int u) {
+    const int uc = max(U0, min(u, U1 - 1));
 #pragma unroll
     for (int kb = 0; kb < UB * 4; ++kb)
       q.a[kb] = *(const u32x4_t*)(abase + (int64_t)(uc * UB * 4 + kb) * (DOWN ? 1024 : 32));
@@ -248,11 +267,11 @@ __device__ __forceinline__ void skinny_q_body(const SkinnyQArgs& p, int wg, floa
 #pragma unroll
   for (int i = 0; i < RB; ++i) tot[i] = zero;
 
-  auto compute = [&](const QUnit<BITS, DOWN>& q, bool live) {
+  auto compute = [&](const QWts<BITS, DOWN>& qw, const QAct<BITS, DOWN>& q) {
     QFrag a[UB * 4];
 #pragma unroll
     for (int kb = 0; kb < UB * 4; ++kb) {
-      a[kb].u = live ? q.a[kb] : u32x4_t{0, 0, 0, 0};
+      a[kb].u = q.a[kb];
       if constexpr (!DOWN && BITS == 8) {
         // bf16 -> fp16: eight significant bits, exact (round toward zero never rounds)
 #pragma unroll
@@ -265,50 +284,61 @@ __device__ __forceinline__ void skinny_q_body(const SkinnyQArgs& p, int wg, floa
         }
       }
     }
+    // The unpacked operands are the integers magic + u (u the offset-binary code); the constant
+    // magic + 2^(bits-1) is removed by a second MFMA whose left operand is that constant,
+    // negated, in every row: the vector ALU, which bounds these kernels, only unpacks.
+    QFrag negc;
+    {
+      const uint32_t c = F16 ? (BITS == 8 ? 0xE480E480u /* -1152 */ : 0xE404E404u /* -1028 */) : 0xC304C304u /* bf16 -132 */;
+      negc.u = u32x4_t{c, c, c, c};
+    }
     if constexpr (DOWN) {
-      const _Float16 off = BITS == 8 ? (_Float16)-1152.0f : (_Float16)-1028.0f;
+      // the scale depends on the reduction element (and the group of 128 rows, which the RB row
+      // blocks share): it multiplies the activations, one packed multiply per register
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          H2 v, s2;
+          v.u = a[j].u[i];
+          s2.u = q.sd[j][i];
+          v.h = v.h * s2.h;
+          a[j].u[i] = v.u;
+        }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
         for (int rbi = 0; rbi < RB; ++rbi) {
           QFrag wf;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            H2 v, s2;
-            v.u = q_pair(q.w[rbi][0], j, i, BITS == 8 ? 0x64646464u : 0x64006400u);
-            s2.u = q.sd[j][i];
-            v.h = (v.h + f16x2_t{off, off}) * s2.h;
-            wf.u[i] = v.u;
-          }
+          for (int i = 0; i < 4; ++i) wf.u[i] = q_pair(qw.w[rbi][0], j, i, BITS == 8 ? 0x64646464u : 0x64006400u);
           tot[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf.h, a[j].h, tot[rbi], 0, 0, 0);
         }
+#pragma unroll
+        for (int rbi = 0; rbi < RB; ++rbi)
+          tot[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(negc.h, a[j].h, tot[rbi], 0, 0, 0);
+      }
     } else {
-      f32x16_t ag[RB], ao = zero;
+      f32x16_t ag[RB];
 #pragma unroll
       for (int i = 0; i < RB; ++i) ag[i] = zero;
-      QFrag ones;
-      ones.u = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
 #pragma unroll
       for (int kb = 0; kb < 8; ++kb) {
-        if constexpr (!F16) ao = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.b, a[kb].b, ao, 0, 0, 0);
 #pragma unroll
         for (int rbi = 0; rbi < RB; ++rbi) {
           QFrag wf;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            if constexpr (BITS == 8) {
-              H2 v;
-              v.u = q_pair(q.w[rbi][kb >> 2], kb & 3, i, 0x64646464u);
-              v.h = v.h + f16x2_t{(_Float16)-1152.0f, (_Float16)-1152.0f};
-              wf.u[i] = v.u;
-            } else {
-              wf.u[i] = q_pair(q.w[rbi][kb >> 2], kb & 3, i, 0x43004300u);
-            }
-          }
+          for (int i = 0; i < 4; ++i) wf.u[i] = q_pair(qw.w[rbi][kb >> 2], kb & 3, i, BITS == 8 ? 0x64646464u : 0x43004300u);
           if constexpr (F16) ag[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf.h, a[kb].h, ag[rbi], 0, 0, 0);
           else ag[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.b, a[kb].b, ag[rbi], 0, 0, 0);
         }
+#pragma unroll
+        for (int rbi = 0; rbi < RB; ++rbi) {
+          if constexpr (F16) ag[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(negc.h, a[kb].h, ag[rbi], 0, 0, 0);
+          else ag[rbi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(negc.b, a[kb].b, ag[rbi], 0, 0, 0);
+        }
       }
+      // the group's integer dot products times the rows' scales for this group
 #pragma unroll
       for (int rbi = 0; rbi < RB; ++rbi)
 #pragma unroll
@@ -317,26 +347,25 @@ __device__ __forceinline__ void skinny_q_body(const SkinnyQArgs& p, int wg, floa
           const float s4[4] = {q_half((uint16_t)(sc[0] & 0xffffu)), q_half((uint16_t)(sc[0] >> 16)),
                                q_half((uint16_t)(sc[1] & 0xffffu)), q_half((uint16_t)(sc[1] >> 16))};
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float raw = F16 ? ag[rbi][4 * g + i] : fmaf(-132.0f, ao[4 * g + i], ag[rbi][4 * g + i]);
-            tot[rbi][4 * g + i] = fmaf(s4[i], raw, tot[rbi][4 * g + i]);
-          }
+          for (int i = 0; i < 4; ++i) tot[rbi][4 * g + i] = fmaf(s4[i], ag[rbi][4 * g + i], tot[rbi][4 * g + i]);
         }
     }
   };
 
-  QUnit<BITS, DOWN> qa, qb;
-  load(qa, u0);
-  for (int u = u0; u < u1; u += 2) {
-    // (the scheduling barriers keep each batch of loads ahead of the arithmetic of the unit before)
-    load(qb, u + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(qa, u < u1);
-    __builtin_amdgcn_sched_barrier(0);
-    load(qa, u + 2);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(qb, u + 1 < u1);
-    __builtin_amdgcn_sched_barrier(0);
+  for (int ub = u0; ub < u1; ub += SKQ_UNITS) {
+    QWts<BITS, DOWN> qw[SKQ_UNITS];
+    QAct<BITS, DOWN> qa[2];
+#pragma unroll
+    for (int i = 0; i < SKQ_UNITS; ++i) load_w(qw[i], ub + i);
+    load_a(qa[0], ub);
+#pragma unroll
+    for (int i = 0; i < SKQ_UNITS; ++i) {
+      // (the scheduling barriers keep each batch of loads ahead of the arithmetic of the unit before)
+      if (i + 1 < SKQ_UNITS) load_a(qa[(i + 1) & 1], ub + i + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ub + i < u1) compute(qw[i], qa[i & 1]);   // (wavefront-uniform)
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   // fixed-order sum over the four wavefronts; wavefront w finishes accumulator registers 4 w ..
 #pragma unroll
@@ -504,7 +533,9 @@ struct SkinnyFusedArgs {
 
 template <bool A_TILED, int RB, int NW, bool DUAL>
 __global__ void __launch_bounds__(NW * 64) skinny_fused_kernel(const SkinnyFusedArgs q) {
-  constexpr int U = DUAL ? 4 : 8;   // blocks per register group (register budget)
+  // blocks per register group: four keep the kernel at three workgroups per CU (at most 168
+  // registers per lane); eight, two per CU, measured 4 us slower per step at the OPT-13B shape
+  constexpr int U = 4;
   constexpr int NA = DUAL ? 2 : 1;
   extern __shared__ float red_mem[];
   float (*red)[RB][16][64] = (float (*)[RB][16][64])red_mem;   // [NW][RB][16][64]
@@ -717,14 +748,14 @@ size_t skinny_q_part_bytes(int n_max) {
 
 // kernel arguments and workgroup count of one part (0 workgroups if it is empty)
 static int q_part_args(const GemmArgs& g, const SkinnyQ& q, float* part, int slot0, int rb_out0, int n_rb_part,
-                       SkinnyQArgs* out, int* wgs) {
+                       int max_wgs, SkinnyQArgs* out, int* wgs) {
   *wgs = 0;
   SkinnyQArgs a = {};
   *out = a;
   if (g.N <= 0 || g.K <= 0) return 0;
   if (g.M <= 0 || g.M > 32 || (g.K & 63) || (q.bits != 3 && q.bits != 8)) return -1;
   if ((q.down != 0) != (g.a_tiled != 0) || (!q.down && (g.K & 127))) return -1;
-  const int rbs = q.bits == 3 ? (q.down ? 4 : 2) : (q.down ? 2 : 1);   // QShape::RB
+  const int rbs = skq_rb(q.bits, q.down != 0);
   if (g.N % (32 * rbs)) return -1;
   a.A = g.A; a.lda = g.lda; a.M = g.M;
   a.n_rb = g.N / 32;
@@ -739,6 +770,7 @@ static int q_part_args(const GemmArgs& g, const SkinnyQ& q, float* part, int slo
   const int cap = (int)(wbytes / ((size_t)8192 * a.n_rb));
   if (S > cap) S = cap;
   if (S > SKQ_MAX_SPLIT) S = SKQ_MAX_SPLIT;
+  if (S > max_wgs / n_rbg) S = max_wgs / n_rbg;
   if (S < 1) S = 1;
   a.nu_per = (a.nu_total + S - 1) / S;
   a.n_split = (a.nu_total + a.nu_per - 1) / a.nu_per;
@@ -756,21 +788,29 @@ int launch_skinny_q_pair(const GemmArgs& g8, const SkinnyQ& q8, const GemmArgs& 
   const bool down = (g8.N > 0 && g8.K > 0) ? q8.down != 0 : q3.down != 0;
   SkinnyQ2Args a = {};
   int w8 = 0, w3 = 0;
+  // The kernels hold three workgroups per CU: the 3-bit part takes its ranges first, the 8-bit
+  // part what is left of one full round (768 workgroups), so that no second round starts for a
+  // few workgroups.
+  constexpr int ROUND = 768;
   if (down) {
     // same rows, two segments of the reduction: the 3-bit ranges follow the 8-bit ones
     const int n_rb = (g8.N > 0 ? g8.N : g3.N) / 32;
-    if (q_part_args(g8, q8, part, 0, 0, n_rb, &a.s8, &w8)) return -1;
-    if (q_part_args(g3, q3, part, a.s8.n_split, 0, n_rb, &a.s3, &w3)) return -1;
+    if (q_part_args(g3, q3, part, 0, 0, n_rb, ROUND, &a.s3, &w3)) return -1;
+    if (q_part_args(g8, q8, part, 0, 0, n_rb, ROUND - w3, &a.s8, &w8)) return -1;
+    a.s3.slot0 = a.s8.n_split;
   } else {
     // two row ranges of one output: the 3-bit rows follow the 8-bit rows
     const int n_rb = (g8.N > 0 ? g8.N / 32 : 0) + (g3.N > 0 ? g3.N / 32 : 0);
-    if (q_part_args(g8, q8, part, 0, 0, n_rb, &a.s8, &w8)) return -1;
-    if (q_part_args(g3, q3, part, 0, g8.N > 0 ? g8.N / 32 : 0, n_rb, &a.s3, &w3)) return -1;
+    if (q_part_args(g3, q3, part, 0, g8.N > 0 ? g8.N / 32 : 0, n_rb, ROUND, &a.s3, &w3)) return -1;
+    if (q_part_args(g8, q8, part, 0, 0, n_rb, ROUND - w3, &a.s8, &w8)) return -1;
   }
   if (w8 + w3 == 0) return 0;
   a.wg8 = w8;
-  if (down) hipLaunchKernelGGL(skinny_stream_q2_kernel<true>, dim3(w8 + w3), dim3(256), 65536, st, a);
-  else hipLaunchKernelGGL(skinny_stream_q2_kernel<false>, dim3(w8 + w3), dim3(256), 32768, st, a);
+  // LDS: the four wavefronts' accumulators of the row blocks, [4][RB][16][64] floats
+  constexpr int rb_dn = skq_rb(3, true) > skq_rb(8, true) ? skq_rb(3, true) : skq_rb(8, true);
+  constexpr int rb_up = skq_rb(3, false) > skq_rb(8, false) ? skq_rb(3, false) : skq_rb(8, false);
+  if (down) hipLaunchKernelGGL(skinny_stream_q2_kernel<true>, dim3(w8 + w3), dim3(256), 4 * rb_dn * 4096, st, a);
+  else hipLaunchKernelGGL(skinny_stream_q2_kernel<false>, dim3(w8 + w3), dim3(256), 4 * rb_up * 4096, st, a);
   if (hipGetLastError() != hipSuccess) return -1;
   n_split[0] = a.s8.n_split; n_split[1] = a.s3.n_split;
   return 0;
