@@ -106,6 +106,64 @@ def test_argument_errors_are_found_on_the_host():
     assert tt.value == 0
 
 
+def test_argument_errors_of_the_epilogue_norm_stack_and_probe_calls():
+    """The calls added around the layer stack validate on the host like the others (no launch here)."""
+    import paper_2401_04044_amd as ff
+    L = ff.lib
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    ref = ctypes.byref
+    good = ff.make_desc(64, 256, "gelu", "bf16", 16, "lowrank", 8)
+    gated = ff.make_desc(256, 1024, "swiglu", "bf16", 16, "int4", 0, 128)
+    big = 1 << 30
+
+    def epi(b1=None, b2=None, res=None, f32=0):
+        e = ff.Epilogue()
+        e.b1_packed, e.b2, e.residual, e.y_f32 = b1, b2, res, f32
+        return e
+
+    fwd = L.ffsplit_forward_ex
+    assert fwd(ref(good), fake, fake, 4, fake, None, None, None, fake, 16, None) == -5            # as ffsplit_forward
+    assert fwd(ref(good), fake, fake, 4, fake, None, None, ref(epi(b2=odd)), fake, big, None) == -4
+    assert fwd(ref(good), fake, fake, 4, fake, None, None, ref(epi(res=odd)), fake, big, None) == -4
+    assert fwd(ref(gated), fake, fake, 4, fake, None, None, ref(epi(b1=fake)), fake, big, None) == -6   # no b1 for gated units
+    assert fwd(ref(good), fake, fake, 0, fake, None, None, ref(epi(b2=fake)), None, 0, None) == 0  # T = 0: no-op
+    # neuron-bias packing
+    assert ff.lib.ffsplit_neuron_bias_floats(ref(good)) == 64 + 256                                 # 16 -> 64, 240 -> 256
+    assert L.ffsplit_pack_neuron_bias(ref(good), None, fake, fake, fake, big, None) == -1
+    assert L.ffsplit_pack_neuron_bias(ref(good), fake, None, fake, fake, big, None) == -1          # k > 0 needs idx
+    assert L.ffsplit_pack_neuron_bias(ref(good), odd, fake, fake, fake, big, None) == -4
+    assert L.ffsplit_pack_neuron_bias(ref(good), fake, fake, fake, fake, 8, None) == -5
+    # per-token RMS norm
+    f32, bf16 = 0, 1
+    assert {int(ff.make_desc(64, 256, "gelu", "f32", 0, "none").dtype), int(good.dtype)} == {f32, bf16}
+    norm = L.ffsplit_token_rmsnorm
+    assert norm(fake, 4, 60, ctypes.c_float(1e-6), bf16, fake, None) == -3                           # d_model % 8
+    assert norm(fake, -1, 64, ctypes.c_float(1e-6), bf16, fake, None) == -3
+    assert norm(fake, 4, 64, ctypes.c_float(1e-6), 7, fake, None) == -2
+    assert norm(None, 4, 64, ctypes.c_float(1e-6), bf16, fake, None) == -1
+    assert norm(odd, 4, 64, ctypes.c_float(1e-6), bf16, fake, None) == -4
+    assert norm(None, 0, 64, ctypes.c_float(1e-6), bf16, None, None) == 0
+    # stack driver
+    vp2 = ctypes.c_void_p * 2
+    stack = L.ffsplit_stack_forward
+    eps = ctypes.c_float(1e-6)
+    assert stack(ref(good), -1, vp2(fake, fake), None, None, fake, 4, eps, fake, big, None) == -3
+    assert stack(ref(good), 2, None, None, None, fake, 4, eps, fake, big, None) == -1
+    assert stack(ref(good), 2, vp2(fake, None), None, None, fake, 4, eps, fake, big, None) == -1   # a missing layer
+    assert stack(ref(good), 2, vp2(fake, fake), None, None, odd, 4, eps, fake, big, None) == -4
+    assert stack(ref(good), 2, vp2(fake, fake), None, None, fake, 4, eps, fake, 64, None) == -5
+    assert stack(ref(good), 0, None, None, None, None, 4, eps, None, 0, None) == 0
+    need = ff.workspace_bytes(good, ff.WS_STACK, 4)
+    assert need >= ff.workspace_bytes(good, ff.WS_FORWARD, 4) + 4 * 64 * 2
+    # probes
+    fl = ctypes.c_double(0.0)
+    assert L.ffsplit_probe_mfma(0, 10, fake, ref(fl), None) == -3
+    assert L.ffsplit_probe_mfma(8, 10, None, ref(fl), None) == -1
+    assert L.ffsplit_probe_stream_read(fake, 24, 8, fake, None) == -3                              # bytes % 16
+    assert L.ffsplit_probe_stream_read(None, 32, 8, fake, None) == -1
+    assert L.ffsplit_probe_stream_read(odd, 32, 8, fake, None) == -4
+
+
 def test_forward_workspace_has_room_for_every_split_product():
     """65..1024 rows of the low-rank chain (bf16): a product with few tiles is split along its
     reduction and keeps fp32 partials [split][T][N] in the call's workspace.  The size the library
