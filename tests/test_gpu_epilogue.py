@@ -226,3 +226,66 @@ def test_stack_forward_matches_oracle(ff, with_bias, T):
                      [ly["b2d"] for ly in layers] if with_bias else None, workspace=g.view)
     g.check("stack_forward")
     assert_close(host(x), xs[-1], "bf16", "stack free-running end")
+
+
+GRAPH_CASES = [
+    # name, cfg, remainder kind, tokens: prefill chain, small-batch chain, int4 decode, W3H8 decode
+    ("lowrank_T1300", reduced(C5, 256, 1000, rank=64), "lowrank", 1300),
+    ("lowrank_T16", reduced(C5, 256, 1000, rank=64), "lowrank", 16),
+    ("int4_T16", reduced(C4, 256, 768), "int4", 16),
+    ("w3h8_T16", reduced(C4, 256, 768), "w3h8", 16),
+]
+
+
+@pytest.mark.parametrize("name,cfg,kind,T", GRAPH_CASES, ids=[c[0] for c in GRAPH_CASES])
+def test_stack_and_forward_replay_from_a_hip_graph(ff, name, cfg, kind, T):
+    """The calls launch kernels only (no allocation, no synchronisation, no memset): a caller may
+    capture them.  Three layers of the stack driver resp. one forward are captured once and replayed
+    three times, with eager work and synchronisations of the program's own between the replays;
+    every replay must equal the eager result bit for bit."""
+    gated = cfg.act == "swiglu"
+    L = wl.make_layer(cfg, 0)
+    idx = L["planted"]
+    Ld = layer_to_dev(L, cfg.dtype)
+    desc = desc_for(ff, cfg, kind)
+    fac = wl.make_factors(cfg, L, idx) if kind == "lowrank" else None
+    split = ff.build_split(desc, Ld["W1"], Ld["Wg"] if gated else None, Ld["W2"], torch.from_numpy(idx).cuda(),
+                           {k: dev(v, cfg.dtype) for k, v in fac.items()} if fac else None)
+    x0 = torch.from_numpy((wl.make_tokens(cfg, T) * 2.0).astype(np.float32)).cuda()
+    use_stack = kind == "lowrank"
+    if use_stack:
+        ws = torch.empty(ff.workspace_bytes(desc, ff.WS_STACK, T), dtype=torch.uint8, device="cuda")
+        x = x0.clone()
+
+        def step():
+            ff.stack_forward(desc, [split, split, split], x, workspace=ws)
+    else:
+        ws = torch.empty(ff.workspace_bytes(desc, ff.WS_FORWARD, T), dtype=torch.uint8, device="cuda")
+        xb = x0.to(torch.bfloat16)
+        x = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+
+        def step():
+            ff.forward(desc, split, xb, x, False, ws)
+    # eager result (also the warm-up that sets the kernels' one-time attributes before the capture)
+    step()
+    torch.cuda.synchronize()
+    want = x.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        if use_stack:
+            x.copy_(x0)
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        if use_stack:
+            x.copy_(x0)            # eager work between the replays
+        else:
+            x.zero_()
+        ws.random_(0, 255)         # the workspace holds nothing a later call relies on
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(x, want), f"replay {rep} differs from the eager result"
