@@ -317,10 +317,18 @@ union VFrag {
   uint32_t w[4];
 };
 
+// (a & mask) | o in one instruction: the compiler emits an and and an or, and the unpack is most
+// of phase 1's vector arithmetic
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t o) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(o));
+  return r;
+}
+
 __device__ __forceinline__ VFrag dequant8v(uint32_t w) {
   VFrag f;
 #pragma unroll
-  for (int p = 0; p < 4; ++p) f.w[p] = ((w >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
+  for (int p = 0; p < 4; ++p) f.w[p] = and_or(w >> (4 * p), 0x000F000Fu, 0x43004300u);
   return f;
 }
 
