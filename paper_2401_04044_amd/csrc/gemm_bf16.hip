@@ -43,22 +43,6 @@ __device__ __forceinline__ int xcd_remap(int i, int total) {
   return x * q + (x < rem ? x : rem) + (i >> 3);
 }
 
-// GeLU for the bf16 path with one transcendental: for a = |z|, Phi(-a) = 2^q(a) with q a cubic
-// fitted to log2 Phi(-a) (leading coefficient negative, so large a underflows to 0), and
-// z Phi(z) = max(z, 0) - a Phi(-a).  Max abs error 5.7e-5 on the real line, below the bf16
-// rounding of the result (2^-9 relative) wherever |result| > 0.03.
-__device__ __forceinline__ float gelu_fast(float z) {
-  const float a = fabsf(z);
-  float q = fmaf(a, -0.024829373f, -0.49904245f);
-  q = fmaf(a, q, -1.1289980f);
-  q = fmaf(a, q, -1.0036056f);
-  return fmaxf(z, 0.0f) - a * __builtin_amdgcn_exp2f(q);
-}
-__device__ __forceinline__ float silu_fast(float z) {
-  const float e = __builtin_amdgcn_exp2f(-1.44269504f * z);
-  return z * __builtin_amdgcn_rcpf(1.0f + e);
-}
-
 template <int ACT>
 __device__ __forceinline__ float act_bf16(float z, float g) {
   if (ACT == ACT_GELU) return gelu_fast(z);

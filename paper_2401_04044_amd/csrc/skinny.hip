@@ -401,7 +401,7 @@ __global__ void __launch_bounds__(256) skinny_stream_q2_kernel(const SkinnyQ2Arg
   else skinny_q_body<3, DOWN>(p.s3, (int)blockIdx.x - p.wg8, red_mem);
 }
 
-__device__ __forceinline__ float sk_silu(float z) { return z / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float sk_silu(float z) { return silu_fast(z); }   // exp2 and rcp: no division sequence
 
 // Sum over the ranges (fixed order), activation, bf16 stores.  One thread per (block, lane,
 // g): token row = lane & 31, four consecutive columns.
@@ -452,7 +452,9 @@ __device__ __forceinline__ void sk_emit(const SkinnyReduceArgs& p, int rb, int t
       for (int e = 0; e < 4; ++e) v[e] = sk_silu(v[e]) * u[e];
     } else if (p.act == ACT_GELU) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
+      // the bf16 path's GeLU (common.h); erff here costs the kernels that inline this 60 registers per
+      // lane and with them a workgroup per CU
+      for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
     }
   }
   const int row = tb * 32 + (lane & 31);
@@ -697,9 +699,11 @@ int launch_skinny_bf16(const GemmArgs& g, int act, float* part, hipStream_t st) 
     const int fused = launch_skinny_fused(a, g, act, kb_total, st);
     if (fused <= 0) return fused;   // launched (0) or failed (-1); 1 = not applicable
   }
-  // enough ranges for about 2048 wavefronts, at least 32 blocks (32 KiB of weights) each
-  int S = 2048 / a.n_rb;
+  // enough ranges for about 1024 wavefronts (one per SIMD), at least 32 blocks (32 KiB of weights)
+  // each.  Measured per decode step (Llama shape / OPT-13B shape): 2048 wavefronts 48.5 / 60.8 us,
+  // 1024: 48.4 / 56.6, 768: 49.5 / 56.9, 512: 50.8 / 60.4; 16 blocks each: 53.1 / 62.0, 64: 52.7 / 59.7.
   const int max_s = kb_total / 32 > 0 ? kb_total / 32 : 1;
+  int S = 1024 / a.n_rb;
   if (S > max_s) S = max_s;
   if (S < 1) S = 1;
   a.kb_per = (kb_total + S - 1) / S;
