@@ -311,6 +311,11 @@ def main():
                 dl[f"{nm}_B{B}"] = {"us": td * 1e6, "tokens_per_s": B / td, "bytes_per_step": cfg_d.weight_bytes(),
                                     "GBps": cfg_d.weight_bytes() / td / 1e9, "frac_hbm": cfg_d.weight_bytes() / td / HBM_PEAK,
                                     "split_copies": len(spds)}
+                per[f"{nm}_lowrank_decode_B{B}"] = {
+                    "workload": f"{cfg_d.name}: one ffsplit_forward, batch {B}", "bound": "hbm",
+                    "achieved": cfg_d.weight_bytes() / td / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                    "frac": cfg_d.weight_bytes() / td / HBM_PEAK, "traffic": traffic.get(f"{nm}_lowrank_decode"),
+                    "bytes_per_launch": cfg_d.weight_bytes(), "us_per_launch_hip_events": td * 1e6, "tokens_per_s": B / td}
         out["decode_lowrank_bf16"] = {"workload": "C3 Llama-2-7B-shaped (k=550, rank 1024) and one C5 OPT-13B-shaped "
                                                   "layer (k=819, rank 1280): heavy bf16 + low-rank factors", **dl}
     del lr
@@ -386,6 +391,11 @@ def main():
             note(f"w3h8 decode B={B}: {t38*1e6:.1f} us")
             q38[f"B{B}"] = {"us": t38 * 1e6, "tokens_per_s": B / t38, "GBps": bytes38 / t38 / 1e9,
                             "frac_hbm": bytes38 / t38 / HBM_PEAK}
+            per[f"C4_w3h8_decode_B{B}"] = {
+                "workload": f"{c4.name} shape with int8 heavy / int3 remainder: one ffsplit_forward, batch {B}",
+                "bound": "hbm", "achieved": bytes38 / t38 / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": bytes38 / t38 / HBM_PEAK, "traffic": traffic.get("C4_w3h8_decode"),
+                "bytes_per_launch": bytes38, "us_per_launch_hip_events": t38 * 1e6, "tokens_per_s": B / t38}
         wsp = torch.empty(ff.workspace_bytes(d38, ff.WS_FORWARD, Tp), dtype=torch.uint8, device="cuda")
         xp = torch.randn((Tp, c4.d_model), device="cuda").to(bf)
         yp = torch.empty((Tp, c4.d_model), dtype=bf, device="cuda")

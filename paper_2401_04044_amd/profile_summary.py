@@ -67,9 +67,9 @@ SIGNATURES = {
         ("G4 h W2  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 256, 1, G + r"256, 256, 32, 2, 4, 1, 3, 2,"),
     ],
     "C4_w3h8_decode": [
-        ("up/gate stream (int8 heavy + int3 rest)", r"skinny_stream_q2_kernel<false>", 800, 1),
+        ("up/gate stream (int8 heavy + int3 rest)", r"skinny_stream_q2_kernel<false>", 764, 1),
         ("sum, activation", r"skinny_reduce_kernel", 692, 1),
-        ("down stream", r"skinny_stream_q2_kernel<true>", 544, 1),
+        ("down stream", r"skinny_stream_q2_kernel<true>", 576, 1),
         ("sum", r"skinny_reduce_kernel", 128, 1),
     ],
     "C3_lowrank_decode": [
@@ -84,7 +84,7 @@ SIGNATURES = {
         ("G1 stream", r"skinny_stream_kernel<false, 1>", 165, 1),
         ("G1 sum, activation", r"skinny_reduce_kernel", 66, 1),
         ("G2", r"skinny_fused_kernel<true, 2, 4, false>", 308, 1),
-        ("G3 stream", r"skinny_stream_kernel<true, 1>", 380, 1),
+        ("G3 stream", r"skinny_stream_kernel<true, 1>", 250, 1),
         ("G3 sum", r"skinny_reduce_kernel", 40, 1),
         ("G4", r"skinny_fused_kernel<true, 1, 8, false>", 160, 1),
     ],
@@ -104,7 +104,9 @@ SIGNATURES = {
 # workloads whose summed FETCH + WRITE bytes bench.py reports as roofline.traffic
 TRAFFIC_KEYS = {"C5_stack_layer": "C5_stack_layer", "C5_prefill": "C5_prefill", "C3_prefill": "C3_prefill",
                 "C2_prefill": "C2_prefill", "C4_int4_decode": ["C4_int4_decode_B1", "C4_int4_decode_B4",
-                                                                "C4_int4_decode_B16"]}
+                                                                "C4_int4_decode_B16"],
+                "C3_lowrank_decode": "C3_lowrank_decode", "C5_lowrank_decode": "C5_lowrank_decode",
+                "C4_w3h8_decode": "C4_w3h8_decode"}
 
 
 def _short(name):
@@ -178,6 +180,23 @@ def copy_factor(ds, counter):
     if not big or max(big) <= 0:
         return None
     return (sum(big) / len(big)) / 262144.0
+
+
+def write_kernel_stats(csv_path, out_dir, cmd):
+    """rocprofv3's own per-kernel statistics (--stats) of the traced bench.py run as a short table:
+    one row per kernel name, over every workload that launches it."""
+    rows = list(csv.DictReader(open(csv_path)))
+    rows.sort(key=lambda r: -float(r["TotalDurationNs"]))
+    lines = ["# rocprofv3 --kernel-trace --stats: per-kernel statistics of one bench.py run", "",
+             "Command (from the repository root on the MI355X box, after `cd /tmp && export TMPDIR=/tmp`):", "",
+             "    " + cmd, "",
+             "Rows are rocprofv3's `kernel_stats` (one per kernel name, all workloads of the run together; the",
+             "per-workload tables in this folder split them by workgroup count). The 30 largest by total time.", "",
+             "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---:|---:|---:|---:|---:|"]
+    for r in rows[:30]:
+        lines.append(f"| `{_short(r['Name'])}` | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | "
+                     f"{float(r['MinNs']) / 1e3:.1f} | {float(r['MaxNs']) / 1e3:.1f} | {float(r['Percentage']):.2f} |")
+    open(os.path.join(out_dir, "kernel_stats_bench.md"), "w").write("\n".join(lines) + "\n")
 
 
 def main():
@@ -277,6 +296,9 @@ def main():
         if a.note:
             lines += ["", a.note]
         open(os.path.join(a.out, wl_name + ".md"), "w").write("\n".join(lines) + "\n")
+    stats = glob.glob(os.path.join(a.kt, "*kernel_stats.csv"))
+    if stats:
+        write_kernel_stats(stats[0], a.out, cmds[0])
     if traffic:
         json.dump(traffic, open(os.path.join(a.out, "hbm_traffic.json"), "w"), indent=1, sort_keys=True)
     print("wrote", ", ".join(sorted(SIGNATURES)), "and", "hbm_traffic.json" if traffic else "no traffic file")
