@@ -289,3 +289,47 @@ def test_stack_and_forward_replay_from_a_hip_graph(ff, name, cfg, kind, T):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(x, want), f"replay {rep} differs from the eager result"
+
+
+def test_stack_calibration_runs_on_the_gpu():
+    """The calibration pass of a layer stack on the device alone (Sec. 4.2, first step: heavy hitters
+    are found on the unmodified model): per layer the library's norm kernel, the score call on the
+    normalised tokens, the selection, and the step x <- x + FFN_dense(n(x)) through the stack driver
+    on the exact dense layer (k heavy neurons + dense remainder).  Free-running over six layers of a
+    scaled-down 40-layer-stack shape; scores, heavy sets and the propagated stream against the
+    oracle's calibration chain."""
+    from gpu_util import assert_scores_close
+    cfg = reduced(C5, 256, 1000, rank=64)
+    n_layers, T = 6, 600
+    ffm = ff_mod()
+    desc = desc_for(ffm, cfg, "dense")
+    x_o = wl.make_tokens(cfg, T, wl.gen.S_CALIB).astype(np.float64) * 2.0
+    x_d = torch.from_numpy(x_o.astype(np.float32)).cuda()
+    xn_d = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    for l in range(n_layers):
+        L = wl.make_layer(cfg, l)
+        Ld = layer_to_dev(L, cfg.dtype)
+        # oracle: scores on the normalised tokens (rounded as stored), then the dense step
+        xn_o = wl.bf16_round(orc.token_rms_normalise(x_o))
+        acc_o = orc.score_accumulate(orc.new_accumulator(cfg.d_ff), xn_o, L["W1"], None, "gelu")
+        want_scores = orc.neuron_scores(acc_o, L["W2"])
+        want_idx = orc.select_heavy(want_scores, cfg.k)
+        x_o = x_o + orc.dense_ffn(xn_o, L["W1"], L["W2"], None, "gelu")
+        # device
+        ffm.token_rmsnorm(x_d, out=xn_d)
+        acc = torch.zeros(2 * cfg.d_ff, dtype=torch.float32, device="cuda")
+        scores = torch.empty(cfg.d_ff, dtype=torch.float32, device="cuda")
+        ffm.score_neurons(desc, xn_d, Ld["W1"], None, Ld["W2"], acc, 0, scores)
+        idx, _, flag = ffm.select_heavy(scores, cfg.k)
+        split = ffm.build_split(desc, Ld["W1"], None, Ld["W2"], idx)
+        ffm.stack_forward(desc, [split], x_d)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        assert_scores_close(host(scores), want_scores, "bf16", f"stack calibration layer {l}")
+        assert np.array_equal(np.sort(idx.cpu().numpy()), np.sort(want_idx)), f"heavy set of layer {l}"
+        assert_close(host(x_d), x_o, "bf16", f"stack calibration stream after layer {l}")
+
+
+def ff_mod():
+    import paper_2401_04044_amd as m
+    return m
