@@ -239,10 +239,10 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        n_s = 256
+        n_s = 1024
         xs = wl.bf16_round(orc.token_rms_normalise(x0_h[:n_s].astype(np.float64)))
         reps, spent = 0, 0.0
-        while spent < 10.0 and reps < 16:
+        while spent < 12.0 and reps < 64:      # about 12 s of host work
             t0 = time.perf_counter()
             orc.forward_heavy(xs, sw, "gelu") + orc.forward_remainder_lowrank(xs, fac0, "gelu")
             spent += time.perf_counter() - t0
