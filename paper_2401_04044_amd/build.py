@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libffsplit.so")
-SOURCES = ["api.hip", "gemm.hip", "gemm_bf16.hip", "prep.hip", "select.hip", "int4.hip", "skinny.hip", "quant.hip", "factor.hip", "probe.hip"]
+SOURCES = ["api.hip", "gemm.hip", "gemm_bf16.hip", "ffn2_fused.hip", "prep.hip", "select.hip", "int4.hip", "skinny.hip", "quant.hip", "factor.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

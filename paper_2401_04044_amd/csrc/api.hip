@@ -131,7 +131,22 @@ static int forward_chain(const ffsplit_desc_t* d, const Layout& L, const FwdWs& 
     }
     FFS_TRY(run(g, act, big_m ? wide : GEMM_128x128, 1));
   }
-  if (rem_lr) {
+  // G2 + G3 in one launch where the rank allows it (no neuron bias: that epilogue is G2's)
+  bool fused_mid = false;
+  if (rem_lr && bf16 && ffn2_fused_applies(L, M) && ep.b1 == nullptr) {
+    const int sp2 = ffn2_fused_splits(M, L.mp);
+    if ((size_t)sp2 * M * L.rp * 4 <= w.kpart_bytes) {
+      float* part = (float*)(ws + w.off_kpart);
+      const int rc = launch_ffn2_fused(tbuf, (int64_t)L.n_up * L.rp, sp + L.off_q1, L.rp, sp + L.off_p2, L.mp, M, L.mp,
+                                       L.rp, part, sp2, st);
+      if (rc < 0) return FFSPLIT_E_HIP;
+      if (rc == 0) {
+        FFS_TRY(launch_splitk_reduce(part, sp2, M, L.rp, w.t_pad, cat + koff_bytes(L.kp), L.k4, L.tiled, st, 0));
+        fused_mid = true;
+      }
+    }
+  }
+  if (rem_lr && !fused_mid) {
     // G2: t * Q1 -> activation -> h2
     GemmArgs g = {};
     g.A = tbuf; g.lda = (int64_t)L.n_up * L.rp; g.a_tiled = L.tiled;

@@ -145,6 +145,15 @@ int launch_splitk_reduce(const float* part, int n_split, int M, int N, int m_pad
 // activation, GEMM column order) + the store epilogue described by a (activation act)
 int launch_splitk_epilogue(const float* part, int n_split, int ldp, const GemmArgs& a, int act, hipStream_t st);
 int bf16_score_tile_m();
+// The two middle products of the low-rank remainder in one launch (ffn2_fused.hip):
+// part[n_split][M][512] = per neuron range, gelu(T1 * Q1t^T) * P2t^T, all operands tiled bf16 with
+// the padded reduction lengths given (ldt, ldq = 512 = rp; ldp2 = mp, a multiple of 64).
+// n_split must be ffn2_fused_splits(M, mp).  Returns 0, -1 on an error, 1 where the device does
+// not grant the LDS the kernel needs (nothing launched).
+constexpr int FFN2_FUSED_RANK = 512;
+int ffn2_fused_splits(int M, int mp);
+int launch_ffn2_fused(const void* T1, int64_t ldt, const void* Q1t, int64_t ldq, const void* P2t, int64_t ldp2, int M,
+                      int mp, int rp, float* part, int n_split, hipStream_t st);
 // small-batch path (M <= SKINNY_MAX_M, N a multiple of 32): weight-streaming kernels, one or two
 // blocks of 32 tokens per pass over the weights (four blocks were measured no better than the
 // tiled GEMM at 128 rows); part: scratch of skinny_part_bytes(N, M) bytes

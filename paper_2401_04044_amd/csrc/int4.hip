@@ -1018,6 +1018,10 @@ FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T) {
     if (sp < 1) sp = 1;
     w.g3_split = sp;
     size_t scratch = sp > 1 ? (size_t)sp * T * L.rp * 4 : 0;
+    if (ffn2_fused_applies(L, T)) {
+      const size_t fb = (size_t)ffn2_fused_splits((int)T, L.mp) * T * L.rp * 4;
+      if (fb > scratch) scratch = fb;
+    }
     if (T <= SKINNY_MAX_M) {
       // small batches take the weight-streaming kernels: room for their partial tiles
       int n_max = L.n1 > L.n_up * L.mp ? L.n1 : L.n_up * L.mp;

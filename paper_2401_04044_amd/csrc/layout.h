@@ -171,6 +171,15 @@ constexpr int INT4_DECODE_MAX_T = 192;
 // expanded (four passes cost less than expanding plus the chain at that size)
 constexpr int W3H8_DECODE_MAX_T = 128;
 
+// The fused middle products (ffn2_fused.hip) serve un-gated bf16 layers of padded rank 512 from
+// 8192 tokens on.  With fewer tokens its 128-row tiles have to split the neurons over more than
+// four workgroups to fill the machine, and the fp32 partial sums of those ranges cost more than
+// not storing h2 saves (measured at the OPT-1.3B shape: 4096 tokens 132 against 128 us per
+// forward, 7168 equal, 8192 220 against 250, 16384 421 against 445).
+inline bool ffn2_fused_applies(const Layout& L, int64_t T) {
+  return L.tiled && L.n_up == 1 && L.rp == 512 && L.mp >= 64 && T >= 8192;
+}
+
 inline size_t build_ws_bytes(const ffsplit_desc_t& d) { return align256((size_t)8 * d.d_ff) + 256; }
 
 FwdWs make_fwd_ws(const ffsplit_desc_t& d, const Layout& L, int64_t T);

@@ -56,6 +56,12 @@ SIGNATURES = {
         ("G3 sum of the splits", r"splitk_reduce_kernel", 1024, 1),
         ("G4  128x128 tiles", G + r"128, 128, 32, 2, 2, 1, 3, 0, false, false, true, false>", 512, 1),
     ],
+    "C2_prefill_T16384": [
+        ("G1  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 1, false, false, false, false>", 192, 1),
+        ("G2 + G3 in one launch, h2 never stored: 128 rows x 2 neuron ranges", r"ffn2_fused_kernel", 256, 1),
+        ("sum of the ranges", r"splitk_reduce_kernel", 4096, 1),
+        ("G4  256x256 tiles", G + r"256, 256, 32, 2, 4, 1, 3, 0, false, false, true, false>", 512, 1),
+    ],
     "C4_int4_decode": [
         ("phase 1: gate/up, activation", r"int4_phase1_kernel<4, 8, 2>", 253, 1),
         ("phase 2: down, sum", r"int4_phase2_kernel", 32, 8),
@@ -103,7 +109,7 @@ SIGNATURES = {
 }
 # workloads whose summed FETCH + WRITE bytes bench.py reports as roofline.traffic
 TRAFFIC_KEYS = {"C5_stack_layer": "C5_stack_layer", "C5_prefill": "C5_prefill", "C3_prefill": "C3_prefill",
-                "C2_prefill": "C2_prefill", "C4_int4_decode": ["C4_int4_decode_B1", "C4_int4_decode_B4",
+                "C2_prefill": "C2_prefill", "C2_prefill_T16384": "C2_prefill_T16384", "C4_int4_decode": ["C4_int4_decode_B1", "C4_int4_decode_B4",
                                                                 "C4_int4_decode_B16"],
                 "C3_lowrank_decode": "C3_lowrank_decode", "C5_lowrank_decode": "C5_lowrank_decode",
                 "C4_w3h8_decode": "C4_w3h8_decode"}

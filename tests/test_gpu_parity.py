@@ -164,6 +164,12 @@ FWD_CASES = [
     ("c3_reduced_tall", reduced(C3, 192, 1500, rank=64), 1059),
     # rank 1024 and enough tiles: the two-operand SwiGLU product on 256x256 tiles (64x128 wave tiles)
     ("c3_dual_256_tiles", reduced(C3, 1024, 3700, rank=1024), 2048),
+    # padded rank 512, un-gated, 8192 rows or more: the two middle products in one launch (h2 never
+    # stored): three neuron ranges of three / three / one chunks with a ragged last row tile / one
+    # range of 18 chunks, the last one ragged / a rank padded up to 512
+    ("c2_rank512_fused", reduced(C2, 512, 1800, rank=512), 8200),
+    ("c2_rank512_fused_chunks", reduced(C2, 512, 4500, rank=512), 16500),
+    ("c2_rank480_fused", reduced(C2, 512, 2000, rank=480), 8192),
 ]
 
 
