@@ -18,7 +18,8 @@
  *   - Element type of X, Y and all dense weights/factors is desc->dtype.
  *   - The library allocates nothing, keeps no state between calls (apart from
  *     a set-once, thread-safe note per device that a kernel's shared-memory limit
- *     has been raised) and never synchronises: a call validates its arguments on the host, enqueues
+ *     has been raised, or that the device refused it and the kernel is not used there)
+ *     and never synchronises: a call validates its arguments on the host, enqueues
  *     kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and returns.  Outputs are valid once the caller has synchronised the stream.
  *   - Caller owns every buffer.  `workspace` is scratch of at least
