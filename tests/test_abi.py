@@ -203,3 +203,35 @@ def test_forward_workspace_has_room_for_every_split_product():
         need = max(split_of(T, N, K) * T * up(N, 32) * 4 if split_of(T, N, K) > 1 else 0 for N, K in products)
         got = ff.workspace_bytes(desc, ff.WS_FORWARD, T)
         assert got >= inter + need, (d, d_ff, k, r, T, glu, got, inter, need)
+
+
+def test_forward_workspace_has_room_for_the_fused_middle_products():
+    """From 8192 tokens on, an un-gated bf16 layer of padded rank 512 runs its two middle products
+    as one launch: 128-row tiles, the neurons in chunks of 256 dealt to about 256 / row-tiles ranges,
+    one fp32 partial [T, 512] per range in the call's workspace.  The reported size must cover
+    the intermediates plus those partials (the policy restated from its description)."""
+    import numpy as np
+    import paper_2401_04044_amd as ff
+
+    def up(v, q):
+        return (v + q - 1) // q * q
+
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        d = int(rng.integers(64, 400)) * 8
+        d_ff = int(rng.integers(600, 12000))
+        k = int(rng.integers(0, d_ff // 4))
+        m = d_ff - k
+        r = int(rng.integers(449, 513))
+        T = int(rng.integers(8192, 70000))
+        desc = ff.make_desc(d, d_ff, "gelu", "bf16", k, "lowrank", r)
+        kp, rp, mp = up(k, 64), up(r, 64), up(m, 64)
+        assert rp == 512
+        k4, tp = kp + rp, up(T, 32)
+        inter = sum(up(tp * c * 2, 256) for c in (k4, rp, mp))
+        row_tiles, chunks = (T + 127) // 128, (mp + 255) // 256
+        S = max(1, min(256 // row_tiles, chunks))
+        per = (chunks + S - 1) // S
+        S = (chunks + per - 1) // per
+        got = ff.workspace_bytes(desc, ff.WS_FORWARD, T)
+        assert got >= inter + S * T * 512 * 4, (d, d_ff, k, r, T, got, inter, S)
