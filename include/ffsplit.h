@@ -43,12 +43,13 @@ extern "C" {
 
 enum { FFSPLIT_ACT_GELU = 0,      /* GeLU z*Phi(z) (the erf form, not the tanh fit)       */
        FFSPLIT_ACT_SWIGLU = 1 };  /* silu(X Wg) * (X W1)                                  */
-/* How the activation is evaluated.  F32: erff / expf.  BF16 prefill (more than 64
- * tokens) and the BF16 calibration pass: Phi(-|z|) = 2^q(|z|) with q a cubic fitted
- * to log2 Phi (max absolute error of z*Phi(z) 5.7e-5, relative error up to 0.25 %
- * for |z| < 0.03: at most one bf16 unit in the last place of the result, which is
- * stored in bf16), silu through exp2 and a reciprocal.  BF16 small-batch kernels:
- * erff / expf.  The calibration pass ranks what the forward pass computes.        */
+/* How the activation is evaluated.  F32: erff / expf.  BF16 (the forward pass at any
+ * batch size with dense or low-rank or W3H8 parts, and the calibration pass):
+ * Phi(-|z|) = 2^q(|z|) with q a cubic fitted to log2 Phi (max absolute error of
+ * z*Phi(z) 5.7e-5, relative error up to 0.25 % for |z| < 0.03: at most one bf16 unit
+ * in the last place of the result, which is stored in bf16), silu through exp2 and a
+ * reciprocal.  The int4 small-batch kernels: erff / expf.  The calibration pass ranks
+ * what the forward pass computes.                                                  */
 enum { FFSPLIT_F32 = 0, FFSPLIT_BF16 = 1 };
 enum { FFSPLIT_REM_NONE = 0,      /* FFN_2 dropped                                        */
        FFSPLIT_REM_DENSE = 1,     /* FFN_2 kept uncompressed                              */
