@@ -214,6 +214,10 @@ int ffsplit_factorize_remainder(const ffsplit_desc_t* desc, const void* W1, cons
  * buffers that receive FFN_1(X) and FFN_2~(X) separately (diagnostic; costs
  * extra launches).  Accumulation is fp32; intermediates between the chained
  * products are stored in desc->dtype.
+ * LOWRANK: the activated remainder act((X P1) Q1) [T, m] is such an intermediate,
+ * except for un-gated BF16 layers of rank 449..512 from 8192 tokens on, where it
+ * is multiplied by P2 chunk by chunk without being stored (rounded to bf16 all
+ * the same; only the order of the fp32 partial sums differs).
  * INT4: up to 192 tokens run in passes of 16 through weight-streaming kernels
  * that apply the group scales in fp32; above that the dequantised weights
  * float(s) * q are first written once, rounded to bf16, into the workspace
